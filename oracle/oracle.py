@@ -1,0 +1,175 @@
+"""ctypes front end of ``intattn_oracle.c`` -- TEST INFRASTRUCTURE ONLY.
+
+Argument marshalling and a thread fan-out over heads; all arithmetic of the
+method lives in the C file.  numpy arrays in, numpy arrays out.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import threading
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "intattn_oracle.c")
+_LIB = os.path.join(_HERE, "libintattn_oracle.so")
+_lock = threading.Lock()
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    with _lock:
+        if _lib is None:
+            build()
+            lib = ctypes.CDLL(_LIB)
+            i32, i64, dbl, f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_double, ctypes.c_float
+            vp = ctypes.c_void_p
+            lib.intattn_oracle_lut.argtypes = [i32, dbl, vp]
+            lib.intattn_oracle_lut.restype = i32
+            lib.intattn_oracle_c_int.argtypes = [dbl, f32, f32, i32]
+            lib.intattn_oracle_c_int.restype = i64
+            lib.intattn_oracle_requant_params.argtypes = [f32, f32, ctypes.POINTER(i64), ctypes.POINTER(i32)]
+            lib.intattn_oracle_requant_params.restype = i32
+            lib.intattn_oracle_index.argtypes = [i64, i64, i32]
+            lib.intattn_oracle_index.restype = i64
+            lib.intattn_oracle_prob.argtypes = [i64, i64]
+            lib.intattn_oracle_prob.restype = i64
+            lib.intattn_oracle_forward.argtypes = (
+                [i32] * 6 + [vp] * 3 + [i32] + [vp] * 4 + [i32, dbl] + [i32] * 4 + [vp] * 5
+            )
+            lib.intattn_oracle_forward.restype = i32
+            lib.intattn_oracle_rows.argtypes = (
+                [i32] * 6 + [vp] * 3 + [i32] + [vp] * 4 + [i32, dbl] + [i32] * 3 + [vp] * 5
+            )
+            lib.intattn_oracle_rows.restype = i32
+            _lib = lib
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f32(x):
+    return None if x is None else np.ascontiguousarray(np.atleast_1d(np.asarray(x, dtype=np.float32)))
+
+
+def lut(lut_bits: int = 5, clip: float = 6.6) -> np.ndarray:
+    out = np.zeros(1 << lut_bits, dtype=np.uint8)
+    rc = _load().intattn_oracle_lut(lut_bits, clip, _ptr(out))
+    if rc:
+        raise ValueError(f"intattn_oracle_lut rc={rc}")
+    return out
+
+
+def c_int(clip: float, s_q: float, s_k: float, d: int) -> int:
+    return int(_load().intattn_oracle_c_int(clip, float(np.float32(s_q)), float(np.float32(s_k)), d))
+
+
+def requant_params(s_v: float, s_o: float):
+    m, sh = ctypes.c_int64(0), ctypes.c_int32(0)
+    rc = _load().intattn_oracle_requant_params(
+        float(np.float32(s_v)), float(np.float32(s_o)), ctypes.byref(m), ctypes.byref(sh)
+    )
+    if rc:
+        raise ValueError(f"intattn_oracle_requant_params rc={rc}")
+    return int(m.value), int(sh.value)
+
+
+def index_map(delta_clipped: int, c_int_: int, lut_bits: int = 5) -> int:
+    return int(_load().intattn_oracle_index(delta_clipped, c_int_, lut_bits))
+
+
+def prob(e: int, row_sum: int) -> int:
+    return int(_load().intattn_oracle_prob(e, row_sum))
+
+
+def _check_inputs(q, k, v):
+    for name, a in (("q", q), ("k", k), ("v", v)):
+        if a.dtype != np.int8 or a.ndim != 4 or not a.flags.c_contiguous:
+            raise ValueError(f"{name} must be a C-contiguous int8 [B,H,L,d] array")
+    B, Hq, L, d = q.shape
+    Bk, Hkv, Lk, dk = k.shape
+    if (Bk, Lk, dk) != (B, L, d) or v.shape != k.shape:
+        raise ValueError("shape mismatch between q, k, v")
+    return B, Hq, Hkv, L, d
+
+
+def forward(q, k, v, s_q, s_k, s_v, s_o=None, *, causal=False, per_head=False, lut_bits=5, clip=6.6,
+            taps=False, want_prob=False, threads=1, rows_range=None):
+    """Run the oracle over all (b, h).  Returns a dict with ``out`` (int8 [B,Hq,L,d]) and,
+    with ``taps``, ``row_max``/``row_sum`` (int32 [B,Hq,L]) and ``acc`` (int32 [B,Hq,L,d]);
+    with ``want_prob``, ``prob`` (uint8 [B,Hq,L,L]).  ``threads`` fans heads over host threads
+    (the C call releases the GIL); each thread runs the same single-threaded row routine."""
+    lib = _load()
+    B, Hq, Hkv, L, d = _check_inputs(q, k, v)
+    sq, sk, sv, so = _f32(s_q), _f32(s_k), _f32(s_v), _f32(s_o)
+    if per_head:
+        if sq.size != Hq or sk.size != Hkv or sv.size != Hkv or (so is not None and so.size != Hq):
+            raise ValueError("per-head scales must have Hq (q, out) / Hkv (k, v) entries")
+    out = np.zeros((B, Hq, L, d), dtype=np.int8)
+    res = {"out": out}
+    if taps:
+        res["row_max"] = np.zeros((B, Hq, L), dtype=np.int32)
+        res["row_sum"] = np.zeros((B, Hq, L), dtype=np.int32)
+        res["acc"] = np.zeros((B, Hq, L, d), dtype=np.int32)
+    if want_prob:
+        res["prob"] = np.zeros((B, Hq, L, L), dtype=np.uint8)
+    r0, r1 = (0, L) if rows_range is None else rows_range
+
+    def run(bh0, bh1):
+        rc = lib.intattn_oracle_forward(
+            B, Hq, Hkv, L, d, int(bool(causal)), _ptr(q), _ptr(k), _ptr(v), int(bool(per_head)),
+            _ptr(sq), _ptr(sk), _ptr(sv), _ptr(so), lut_bits, clip, bh0, bh1, r0, r1, _ptr(out),
+            _ptr(res.get("row_max")), _ptr(res.get("row_sum")), _ptr(res.get("acc")), _ptr(res.get("prob")),
+        )
+        if rc:
+            raise ValueError(f"intattn_oracle_forward rc={rc}")
+
+    nbh = B * Hq
+    threads = max(1, min(int(threads), nbh))
+    if threads == 1:
+        run(0, nbh)
+    else:
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            futs = [ex.submit(run, bh, bh + 1) for bh in range(nbh)]
+            for f in futs:
+                f.result()
+    return res
+
+
+def rows(q, k, v, s_q, s_k, s_v, s_o=None, *, b, hq, rows, causal=False, per_head=False, lut_bits=5,
+         clip=6.6):
+    """Selected query rows of one (b, hq).  Returns dict: out [n,d] int8, row_max/row_sum [n] int32,
+    acc [n,d] int32."""
+    lib = _load()
+    B, Hq, Hkv, L, d = _check_inputs(q, k, v)
+    sq, sk, sv, so = _f32(s_q), _f32(s_k), _f32(s_v), _f32(s_o)
+    idx = np.ascontiguousarray(np.asarray(rows, dtype=np.int32))
+    n = idx.size
+    res = {
+        "out": np.zeros((n, d), dtype=np.int8),
+        "row_max": np.zeros(n, dtype=np.int32),
+        "row_sum": np.zeros(n, dtype=np.int32),
+        "acc": np.zeros((n, d), dtype=np.int32),
+    }
+    rc = lib.intattn_oracle_rows(
+        B, Hq, Hkv, L, d, int(bool(causal)), _ptr(q), _ptr(k), _ptr(v), int(bool(per_head)), _ptr(sq),
+        _ptr(sk), _ptr(sv), _ptr(so), lut_bits, clip, b, hq, n, _ptr(idx), _ptr(res["out"]),
+        _ptr(res["row_max"]), _ptr(res["row_sum"]), _ptr(res["acc"]),
+    )
+    if rc:
+        raise ValueError(f"intattn_oracle_rows rc={rc}")
+    return res

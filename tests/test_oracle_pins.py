@@ -1,0 +1,388 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests needs a GPU or the HIP library.  Each one checks the oracle against
+something other than itself: a closed form evaluated independently, an invariant of the
+definitions, a special case whose answer is known a priori, exact rational arithmetic
+(``fractions``), or fp64 softmax attention within a stated bound.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2511_21513_amd import inputs
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+CLIP, BITS = 6.6, 5
+
+
+def round_half_up(fr: Fraction) -> int:
+    return math.floor(fr + Fraction(1, 2))
+
+
+# ----------------------------------------------------------------------------- LUT
+def test_lut_matches_paper_closed_form(oracle):
+    """Sec. 3.1 Eq. lut_re + Sec. 3.2 Eq. lut16 at (b, c) = (5, 6.6): golden values written by
+    tests/golden/make_lut_golden.py with 50-digit arithmetic."""
+    with open(os.path.join(GOLDEN, "lut_b5_c6p6.txt")) as f:
+        rows = [ln for ln in f if not ln.startswith("#")]
+    golden = np.array([int(t) for t in rows[0].split()], dtype=np.uint8)
+    lut = oracle.lut(5, 6.6)
+    assert lut.dtype == np.uint8 and lut.size == 32  # 32 entries, 32 bytes (Sec. 4.3)
+    np.testing.assert_array_equal(lut, golden)
+
+
+@pytest.mark.parametrize("b,c", [(2, 5.5), (3, 6.6), (4, 6.6), (5, 5.5), (5, 7.7), (6, 6.6), (8, 7.0)])
+def test_lut_against_exp_at_index_points(oracle, b, c):
+    """LUT entries against exp at the paper's index points x_i = c*i/(2^b-1)."""
+    lut = oracle.lut(b, c)
+    n = 1 << b
+    assert lut[0] == 255 and lut[n - 1] == 0
+    assert np.all(np.diff(lut.astype(int)) <= 0)
+    for i in range(n - 1):
+        x = 255.0 * math.exp(-c * i / (n - 1))
+        assert abs(int(lut[i]) - x) <= 0.5 + 1e-9
+
+
+# ----------------------------------------------------------------------------- c_int
+def test_c_int_closed_form(oracle):
+    """Eq. clipping_thr: c_int = round(c*sqrt(d)/(s_Q*s_K)); hence |c_int*alpha - c| <= alpha/2."""
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        sq = np.float32(rng.uniform(0.005, 0.3))
+        sk = np.float32(rng.uniform(0.005, 0.3))
+        d = int(rng.choice([16, 64, 128]))
+        ci = oracle.c_int(CLIP, sq, sk, d)
+        alpha = float(sq) * float(sk) / math.sqrt(d)
+        assert abs(ci * alpha - CLIP) <= alpha / 2 * (1 + 1e-9)
+    # exact-arithmetic instance: s_Q*s_K = 1/4, d = 64 -> c/alpha = 6.6*8*4 = 211.2 -> 211
+    assert oracle.c_int(6.6, 0.5, 0.5, 64) == 211
+    # tie rounds up: c/alpha = 2.5 -> 3
+    assert oracle.c_int(2.5, 1.0, 1.0, 1) == 3
+    # degenerate: threshold below one is raised to one
+    assert oracle.c_int(6.6, 100.0, 100.0, 1) == 1
+
+
+# ----------------------------------------------------------------------------- index map
+@pytest.mark.parametrize("c_int", [1, 2, 3, 31, 62, 63, 100, 445, 1462, 6274])
+def test_index_map_exact_rational(oracle, c_int):
+    """idx = round(delta' * (2^b-1)/c_int) for every delta' in [0, c_int], against exact
+    rational arithmetic; plus the invariants the definition implies."""
+    prev = -1
+    for dl in range(c_int + 1):
+        got = oracle.index_map(dl, c_int, BITS)
+        fr = Fraction(dl * 31, c_int)
+        assert got == round_half_up(fr)
+        assert abs(Fraction(got) - fr) <= Fraction(1, 2)
+        assert got >= prev
+        prev = got
+    assert oracle.index_map(0, c_int, BITS) == 0
+    assert oracle.index_map(c_int, c_int, BITS) == 31
+
+
+def test_prob_exact_rational(oracle):
+    """Eq. uint8-prob element-wise against exact rational arithmetic, including a tie."""
+    lut = oracle.lut(5, 6.6)
+    rng = np.random.default_rng(5)
+    for _ in range(2000):
+        e = int(lut[rng.integers(32)])
+        s = int(rng.integers(max(e, 255), 255 * 64))
+        assert oracle.prob(e, s) == round_half_up(Fraction(255 * e, s))
+    assert oracle.prob(255, 510) == 128  # 127.5 rounds up
+    assert oracle.prob(255, 255) == 255
+    assert oracle.prob(0, 255) == 0
+
+
+# ----------------------------------------------------------------------------- requant
+def test_requant_default_scale_is_round_of_acc_over_255(oracle):
+    """With s_O = s_V the multiplier encodes 1/255, and 255 is odd, so acc/255 never hits a
+    tie: the fixed-point result must equal round(acc/255) for every accumulator in range."""
+    m, sh = oracle.requant_params(0.037, 0.037)
+    assert 2**30 <= m < 2**31 and 1 <= sh <= 62
+    assert abs(m / 2.0**sh - 1.0 / 255.0) < 2.0**-38
+    for acc in list(range(-40000, 40000, 7)) + [-(2**22), 2**22 - 1, 127 * 255, -127 * 255, 128 * 255]:
+        got = (acc * m + (1 << (sh - 1))) >> sh  # python's >> floors
+        assert got == round_half_up(Fraction(acc, 255))
+
+
+def test_requant_general_scale_close_to_ratio(oracle):
+    rng = np.random.default_rng(2)
+    for _ in range(200):
+        sv = np.float32(rng.uniform(0.001, 0.2))
+        so = np.float32(rng.uniform(0.0001, 0.2))
+        m, sh = oracle.requant_params(sv, so)
+        r = float(sv) / (255.0 * float(so))
+        assert 2**30 <= m < 2**31
+        assert abs(m / 2.0**sh - r) <= r * 2.0**-30
+
+
+# ----------------------------------------------------------------------------- helpers
+def run(oracle, p, s_o=None, **kw):
+    return oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, s_o, causal=p.causal,
+                          per_head=p.per_head, **kw)
+
+
+def python_reference_row(qrow, K, V, n_vis, c_int, lut, rq):
+    """Exact-rational restatement of one row (cross-check of the C code's indexing and
+    integer widths; the pins proper are the tests further down)."""
+    a = [int(np.dot(qrow.astype(np.int64), K[j].astype(np.int64))) for j in range(n_vis)]
+    m = max(a)
+    e = [int(lut[round_half_up(Fraction(min(m - x, c_int) * 31, c_int))]) for x in a]
+    s = sum(e)
+    p = [round_half_up(Fraction(255 * x, s)) for x in e]
+    acc = [sum(p[j] * int(V[j, c]) for j in range(n_vis)) for c in range(V.shape[1])]
+    mlt, sh = rq
+    out = [max(-127, min(127, (x * mlt + (1 << (sh - 1))) >> sh)) for x in acc]
+    return m, s, p, acc, out
+
+
+# ----------------------------------------------------------------------------- whole pipeline
+@pytest.mark.parametrize("causal", [False, True])
+def test_pipeline_against_rational_python(oracle, causal):
+    p = inputs.random_problem(3, 1, 2, 1, 19, 8, causal)
+    r = run(oracle, p, taps=True, want_prob=True)
+    lut = oracle.lut()
+    ci = oracle.c_int(CLIP, p.s_q[0], p.s_k[0], p.d)
+    rq = oracle.requant_params(p.s_v[0], p.s_v[0])
+    for h in range(p.Hq):
+        for i in range(p.L):
+            n_vis = i + 1 if causal else p.L
+            m, s, pr, acc, out = python_reference_row(p.q[0, h, i], p.k[0, 0], p.v[0, 0], n_vis, ci, lut, rq)
+            assert r["row_max"][0, h, i] == m and r["row_sum"][0, h, i] == s
+            assert list(r["prob"][0, h, i, :n_vis]) == pr
+            assert not r["prob"][0, h, i, n_vis:].any()
+            assert list(r["acc"][0, h, i]) == acc
+            assert list(r["out"][0, h, i]) == out
+
+
+def test_lut_grid_rows_reproduce_exp_through_the_pipeline(oracle):
+    """d = 1, logits placed exactly on the table's grid: with c_int = 31*t and key values
+    chosen so that delta_j = t*i_j, the index map returns i_j exactly, so E_j must be
+    round(255*exp(-c*i_j/31)) (computed here with math.exp) and the probabilities follow.
+    A wrong sign of delta, a reversed table or an off-by-one gather fails this."""
+    t = 4
+    c_int = 31 * t
+    s_q = np.float32(1.0)
+    s_k = np.float32(CLIP / c_int)  # alpha = s_k -> c/alpha = c_int up to fp rounding
+    assert oracle.c_int(CLIP, s_q, s_k, 1) == c_int
+    steps = np.array([0, 1, 2, 5, 9, 17, 30, 31, 3, 0], dtype=np.int64)
+    kvals = (124 - t * steps).astype(np.int8)  # q = 1 -> a_j = k_j, max = 124 at step 0
+    L = steps.size
+    q = np.ones((1, 1, L, 1), dtype=np.int8)
+    k = kvals.reshape(1, 1, L, 1).copy()
+    v = np.arange(1, L + 1, dtype=np.int8).reshape(1, 1, L, 1).copy()
+    r = oracle.forward(q, k, v, [s_q], [s_k], [1.0], None, taps=True, want_prob=True)
+    e = [0 if i == 31 else math.floor(255 * math.exp(-CLIP * i / 31) + 0.5) for i in steps]
+    s = sum(e)
+    assert r["row_max"][0, 0, 0] == 124
+    assert r["row_sum"][0, 0, 0] == s
+    pr = [math.floor(255 * x / s + 0.5) for x in e]
+    assert list(r["prob"][0, 0, 0]) == pr
+    acc = sum(pj * (j + 1) for j, pj in enumerate(pr))
+    assert r["acc"][0, 0, 0, 0] == acc
+
+
+def test_causal_first_row_and_single_key_copy_v(oracle):
+    """One visible key: P = 255, and with s_O = s_V the output is V_hat[0] exactly."""
+    p = inputs.random_problem(7, 2, 3, 3, 9, 16, True)
+    r = run(oracle, p, taps=True)
+    np.testing.assert_array_equal(r["out"][:, :, 0, :], p.v[:, :, 0, :])
+    assert (r["row_sum"][:, :, 0] == 255).all()
+    p1 = inputs.random_problem(8, 1, 2, 2, 1, 16, False)
+    np.testing.assert_array_equal(run(oracle, p1)["out"], p1.v)
+
+
+def test_dominant_key_gives_one_hot(oracle):
+    """A key whose logit leads every other by at least c_int: every other key lands on the last
+    table entry (zero), P is one-hot, out = V_hat[j*]."""
+    rng = np.random.default_rng(21)
+    L, d, jstar = 12, 16, 5
+    q = np.full((1, 1, L, d), 100, dtype=np.int8)
+    k = rng.integers(-3, 4, size=(1, 1, L, d)).astype(np.int8)
+    k[0, 0, jstar] = 120
+    v = rng.integers(-127, 128, size=(1, 1, L, d)).astype(np.int8)
+    s = np.float32(0.5)  # c_int = round(6.6*4/0.25) = 106, gap >= 100*16*(120-3) >> 106
+    r = oracle.forward(q, k, v, [s], [s], [0.1], None, taps=True, want_prob=True)
+    assert oracle.c_int(CLIP, s, s, d) == 106
+    assert (r["prob"][0, 0, :, jstar] == 255).all()
+    assert r["prob"][0, 0].sum() == 255 * L
+    np.testing.assert_array_equal(r["out"][0, 0], np.broadcast_to(v[0, 0, jstar], (L, d)))
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 7, 100, 510, 511, 600])
+def test_equal_logits_uniform_probabilities(oracle, n):
+    """A zero query row makes all n logits equal: E = 255 each, P = round(255/n),
+    acc = P * sum_j V_hat[j]; beyond n = 510 the row rounds to all-zero (a property of
+    Eq. uint8-prob, not a defect)."""
+    rng = np.random.default_rng(n)
+    d = 8
+    q = np.zeros((1, 1, n, d), dtype=np.int8)
+    k = rng.integers(-127, 128, size=(1, 1, n, d)).astype(np.int8)
+    v = rng.integers(-127, 128, size=(1, 1, n, d)).astype(np.int8)
+    r = oracle.forward(q, k, v, [0.1], [0.1], [0.1], None, taps=True)
+    pexp = math.floor(Fraction(255, n) + Fraction(1, 2))
+    assert (r["row_sum"] == 255 * n).all()
+    acc = pexp * v[0, 0].astype(np.int64).sum(axis=0)
+    np.testing.assert_array_equal(r["acc"][0, 0, 0], acc)
+    if n > 510:
+        assert pexp == 0 and not r["out"].any()
+
+
+def test_key_permutation_invariance(oracle):
+    p = inputs.random_problem(13, 1, 2, 2, 37, 16, False)
+    r0 = run(oracle, p)["out"]
+    perm = np.random.default_rng(1).permutation(p.L)
+    k2 = np.ascontiguousarray(p.k[:, :, perm])
+    v2 = np.ascontiguousarray(p.v[:, :, perm])
+    r1 = oracle.forward(p.q, k2, v2, p.s_q, p.s_k, p.s_v)["out"]
+    np.testing.assert_array_equal(r0, r1)
+
+
+def test_negating_q_and_k_changes_nothing(oracle):
+    p = inputs.random_problem(14, 1, 2, 2, 23, 16, True)
+    r0 = run(oracle, p, taps=True)
+    r1 = oracle.forward(-p.q, -p.k, p.v, p.s_q, p.s_k, p.s_v, causal=True, taps=True)
+    for key in ("out", "row_max", "row_sum", "acc"):
+        np.testing.assert_array_equal(r0[key], r1[key])
+
+
+def test_causal_row_equals_noncausal_prefix(oracle):
+    """Row i under the causal mask is the non-causal problem over keys 0..i."""
+    p = inputs.random_problem(15, 1, 1, 1, 21, 8, True)
+    rc = run(oracle, p, taps=True)
+    for i in (0, 4, 20):
+        q = np.ascontiguousarray(p.q[:, :, : i + 1])
+        k = np.ascontiguousarray(p.k[:, :, : i + 1])
+        v = np.ascontiguousarray(p.v[:, :, : i + 1])
+        rn = oracle.forward(q, k, v, p.s_q, p.s_k, p.s_v, taps=True)
+        np.testing.assert_array_equal(rc["out"][0, 0, i], rn["out"][0, 0, i])
+        assert rc["row_sum"][0, 0, i] == rn["row_sum"][0, 0, i]
+
+
+def test_gqa_maps_query_head_to_kv_head(oracle):
+    """Hq = 4, Hkv = 2: the result must equal plain multi-head attention with each KV head
+    repeated for its group."""
+    p = inputs.random_problem(16, 2, 4, 2, 17, 8, True)
+    r0 = run(oracle, p)["out"]
+    k_rep = np.ascontiguousarray(np.repeat(p.k, 2, axis=1))
+    v_rep = np.ascontiguousarray(np.repeat(p.v, 2, axis=1))
+    r1 = oracle.forward(p.q, k_rep, v_rep, p.s_q, p.s_k, p.s_v, causal=True)["out"]
+    np.testing.assert_array_equal(r0, r1)
+
+
+def test_per_head_scales_equal_per_tensor_runs_head_by_head(oracle):
+    """Sec. 3.3 with one group per head: each head must behave as a per-tensor problem with
+    that head's scales."""
+    p = inputs.random_problem(17, 1, 4, 2, 15, 8, False, per_head=True)
+    assert len(set(p.s_q.tolist())) > 1
+    s_o = np.array([0.02, 0.03, 0.04, 0.05], dtype=np.float32)
+    r = run(oracle, p, s_o)["out"]
+    for h in range(4):
+        kv = h // 2
+        r1 = oracle.forward(np.ascontiguousarray(p.q[:, h:h + 1]), np.ascontiguousarray(p.k[:, kv:kv + 1]),
+                            np.ascontiguousarray(p.v[:, kv:kv + 1]), [p.s_q[h]], [p.s_k[kv]], [p.s_v[kv]],
+                            [s_o[h]])["out"]
+        np.testing.assert_array_equal(r[:, h], r1[:, 0])
+
+
+def test_probability_row_invariants(oracle):
+    """Rows are non-negative, monotone in the logits, bounded per element by the exact
+    quotient +-1/2, and sum to 255 within n_nonzero/2 (what 'within rounding' means for
+    Eq. uint8-prob); the row sum equals the histogram-weighted table sum."""
+    p = inputs.make_problem("c2_vit_b16", B=1, Hq=2, Hkv=2, L=197)
+    r = run(oracle, p, taps=True, want_prob=True)
+    lut = oracle.lut().astype(np.int64)
+    ci = oracle.c_int(CLIP, p.s_q[0], p.s_k[0], p.d)
+    a = np.einsum("hid,hjd->hij", p.q[0].astype(np.int64), p.k[0].astype(np.int64))
+    for h in range(2):
+        for i in range(0, p.L, 9):
+            row, pr = a[h, i], r["prob"][0, h, i].astype(np.int64)
+            assert row.max() == r["row_max"][0, h, i]
+            dl = np.minimum(row.max() - row, ci)
+            idx = (2 * 31 * dl + ci) // (2 * ci)
+            hist = np.bincount(idx, minlength=32)
+            s = int((hist * lut).sum())
+            assert s == r["row_sum"][0, h, i] and 255 <= s <= 255 * p.L
+            order = np.argsort(row, kind="stable")
+            assert np.all(np.diff(pr[order]) >= 0)  # monotone in the logit
+            assert pr.min() >= 0 and pr.max() <= 255
+            e = lut[idx]
+            assert np.all(np.abs(pr * 2 * s - 2 * 255 * e) <= s)  # |P - 255E/S| <= 1/2
+            n_nz = int((e > 0).sum())
+            assert abs(int(pr.sum()) - 255) <= n_nz / 2
+            assert pr[row.argmax()] == (2 * 255 * 255 + s) // (2 * s)
+
+
+def fp64_attention(p, s_o):
+    g = p.Hq // p.Hkv
+    out = np.zeros((p.B, p.Hq, p.L, p.d))
+    prob = np.zeros((p.B, p.Hq, p.L, p.L))
+    for b in range(p.B):
+        for h in range(p.Hq):
+            kv = h // g
+            a = (p.q[b, h].astype(np.float64) * p.s_q[0]) @ (p.k[b, kv].astype(np.float64) * p.s_k[0]).T
+            a /= math.sqrt(p.d)
+            if p.causal:
+                a = np.where(np.tril(np.ones((p.L, p.L), dtype=bool)), a, -np.inf)
+            a -= a.max(axis=1, keepdims=True)
+            w = np.exp(a)
+            w /= w.sum(axis=1, keepdims=True)
+            prob[b, h] = w
+            out[b, h] = w @ (p.v[b, kv].astype(np.float64) * p.s_v[0]) / s_o
+    return prob, out
+
+
+@pytest.mark.parametrize("causal,spread", [(False, 1.0), (True, 1.0), (False, 2.5), (True, 2.5)])
+def test_fidelity_against_fp64_softmax_attention(oracle, causal, spread):
+    """Brute force on tiny inputs (L <= 32, d = 16): the integer pipeline against fp64
+    softmax attention of the same dequantized INT8 inputs (Eq. attention_re).
+
+    Bound used.  The table step is c/31, so E/255 is exp(-alpha*delta) up to a factor
+    e^{+-c/62} (index rounding) and +-1/510 (table rounding); entries past the clip are
+    dropped (each below exp(-c*61/62) < 0.0016).  Normalizing gives probabilities within
+    a factor e^{+-c/31} of softmax, i.e. an L1 distance below e^{c/31} - 1 = 0.2373, plus
+    n*(1/510 + 0.0016 + 1/510) for table rounding, the tail cut and Eq. uint8-prob's own
+    rounding: ||P_hat/255 - p||_1 <= 0.2373 + 0.0056*n.  The output then differs from the
+    fp64 output (in units of s_O = s_V) by at most 127 * that distance + 1/2.
+    Typical values are 5-10x smaller; a looser sanity check on the mean is added."""
+    p = inputs.random_problem(31, 1, 2, 2, 32, 16, causal, spread=spread)
+    r = run(oracle, p, want_prob=True)
+    ref_p, ref_o = fp64_attention(p, float(p.s_v[0]))
+    l1 = np.abs(r["prob"].astype(np.float64) / 255.0 - ref_p).sum(axis=-1)
+    n = np.arange(1, p.L + 1)[None, None, :] if causal else p.L
+    assert np.all(l1 <= 0.2373 + 0.0056 * n)
+    assert l1.mean() <= 0.10
+    err = np.abs(r["out"].astype(np.float64) - ref_o)
+    assert np.all(err.max(axis=-1) <= 127 * (0.2373 + 0.0056 * n) + 0.5)
+    assert err.mean() <= 2.0
+
+
+def test_rows_entry_matches_forward(oracle):
+    p = inputs.random_problem(41, 2, 4, 2, 50, 16, True, per_head=True)
+    full = run(oracle, p, taps=True)
+    sel = [0, 7, 49]
+    r = oracle.rows(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, None, b=1, hq=3, rows=sel, causal=True, per_head=True)
+    np.testing.assert_array_equal(r["out"], full["out"][1, 3, sel])
+    np.testing.assert_array_equal(r["acc"], full["acc"][1, 3, sel])
+    np.testing.assert_array_equal(r["row_max"], full["row_max"][1, 3, sel])
+    np.testing.assert_array_equal(r["row_sum"], full["row_sum"][1, 3, sel])
+
+
+def test_threaded_fanout_matches_single_thread(oracle):
+    p = inputs.random_problem(42, 2, 4, 4, 33, 16, False)
+    a = run(oracle, p, threads=1)["out"]
+    b = run(oracle, p, threads=4)["out"]
+    np.testing.assert_array_equal(a, b)
+
+
+def test_output_saturates_symmetrically(oracle):
+    """Eq. quant's range is [-127, 127]; a small s_O must saturate there, never at -128."""
+    L, d = 4, 8
+    q = np.zeros((1, 1, L, d), dtype=np.int8)
+    k = np.zeros((1, 1, L, d), dtype=np.int8)
+    v = np.empty((1, 1, L, d), dtype=np.int8)
+    v[..., ::2], v[..., 1::2] = -127, 127
+    r = oracle.forward(q, k, v, [0.1], [0.1], [0.1], [0.01])["out"]
+    assert (r[..., ::2] == -127).all() and (r[..., 1::2] == 127).all()

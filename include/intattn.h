@@ -1,0 +1,130 @@
+/*
+ * intattn.h -- C ABI of the MI355X (gfx950) fused integer attention library.
+ *
+ * The library computes the IntAttention pipeline of arxiv 2511.21513 in one fused
+ * pass per (batch, head, query tile), entirely in integers:
+ *
+ *   A_hat  = Q_hat . K_hat^T            INT8 x INT8 -> INT32   (Sec. 2.1, Eq. logit-scale)
+ *   Delta  = rowMax(A_hat) - A_hat      (Sec. 3.1)
+ *   Delta' = min(Delta, c_int),  c_int = round(c * sqrt(d) / (s_Q * s_K))
+ *                                       (Sec. 3.1, Eq. clipping_thr, Eq. int_clipping)
+ *   idx    = round(Delta' * (2^b - 1) / c_int)                  (Sec. 3.1, index map)
+ *   E_hat  = LUT_hat[idx],  LUT_hat[i] = round(255 * exp(-c*i/(2^b-1))), last entry 0
+ *                                       (Sec. 3.1 Eq. lut_re, Sec. 3.2 Eq. lut16, Eq. gather16)
+ *   P_hat  = round(255 * E_hat / rowSum(E_hat))    UINT8        (Sec. 3.2, Eq. uint8-prob)
+ *   acc    = P_hat . V_hat              UINT8 x INT8 -> INT32   (Sec. 2.1 Eq. pv-link, Sec. 3)
+ *   out    = clamp(round(acc * s_V / (255 * s_O)), -127, 127)   INT8
+ *
+ * "round" is round-half-up; for idx, P_hat and out it is evaluated in exact integer
+ * arithmetic.  The output requantization is a fixed-point multiply-shift: with
+ * r = s_V / (255 s_O) = m * 2^e, m in [0.5, 1), M = round(m * 2^31), sh = 31 - e,
+ * out = clamp(floor((acc * M + 2^(sh-1)) / 2^sh), -127, 127).  The paper states no
+ * requantization formula; this one follows from Eq. pv-link with P = P_hat / 255.
+ * With causal != 0, key j is visible to query i iff j <= i; hidden keys take no part in
+ * rowMax / rowSum and get P_hat = 0.  Query head h reads KV head h / (Hq / Hkv).
+ * Per-head scales are the group-wise form of Sec. 3.3 with one group per head.
+ *
+ * The L x L score matrix never reaches HBM.  Results are a deterministic integer
+ * function of the inputs (no dependence on tiling or launch shape).
+ *
+ * All entry points return 0 on success or a negative INTATTN_ERR_* code; none throws,
+ * aborts or synchronizes the stream.  A context is bound to one device and is not
+ * thread-safe; calls that share a context must be issued on one stream at a time.
+ */
+#ifndef INTATTN_H
+#define INTATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define INTATTN_API __attribute__((visibility("default")))
+
+#define INTATTN_OK 0
+#define INTATTN_ERR_INVALID_ARG (-1) /* null / negative / misaligned / inconsistent argument */
+#define INTATTN_ERR_UNSUPPORTED (-2) /* valid request outside what the kernels cover          */
+#define INTATTN_ERR_HIP (-3)         /* a HIP runtime call failed; see intattn_last_error     */
+#define INTATTN_ERR_NOMEM (-4)       /* host or device allocation failed                      */
+
+typedef struct intattn_ctx intattn_ctx; /* opaque; owned by the library */
+
+typedef struct {
+    int32_t device;   /* HIP device ordinal the context is bound to; -1 = host-only context
+                         (parameter derivation and LUT only; forward calls are rejected)     */
+    int32_t lut_bits; /* b of Sec. 3.1: the table has 2^b entries; 1..5; paper default 5     */
+    double clip;      /* c of Sec. 3.1: clip threshold in logit units; > 0; paper default 6.6 */
+    int32_t variant;  /* kernel variant: 0 = automatic choice; others are tuning/debug knobs */
+    int32_t reserved; /* must be 0                                                           */
+} intattn_config;
+
+/*
+ * One forward call.  Tensors are logically [B, H, L, d] with d contiguous; the three
+ * strides per tensor are ELEMENT (= byte) strides of the B, H and L axes.  Every tensor
+ * pointer and every stride must be a multiple of 16.  out must not alias the inputs.
+ * Device buffers are borrowed until the stream reaches the end of the enqueued work;
+ * host scale arrays are read before the call returns.
+ */
+typedef struct {
+    int32_t B, Hq, Hkv, L, d; /* Hq % Hkv == 0; d in {64, 128}; 1 <= L <= 131071            */
+    int32_t causal;           /* 0 or 1                                                       */
+    const int8_t *q;          /* DEVICE  [B, Hq,  L, d]                                       */
+    const int8_t *k;          /* DEVICE  [B, Hkv, L, d]                                       */
+    const int8_t *v;          /* DEVICE  [B, Hkv, L, d]                                       */
+    int8_t *out;              /* DEVICE  [B, Hq,  L, d]                                       */
+    int64_t q_stride[3], k_stride[3], v_stride[3], out_stride[3];
+    int32_t scale_mode;       /* 0: one float per scale array; 1: per head ([Hq] for q and
+                                 out, [Hkv] for k and v), shared over the batch               */
+    const float *scale_q;     /* HOST */
+    const float *scale_k;     /* HOST */
+    const float *scale_v;     /* HOST */
+    const float *scale_out;   /* HOST, or NULL: s_O = s_V of the matching KV head             */
+    int32_t *dbg_row_max;     /* optional DEVICE [B, Hq, L] contiguous: rowMax(A_hat); NULL off */
+    int32_t *dbg_row_sum;     /* optional DEVICE [B, Hq, L] contiguous: rowSum(E_hat); NULL off */
+    int32_t *dbg_acc;         /* optional DEVICE [B, Hq, L, d] contiguous: P_hat.V_hat; NULL off */
+} intattn_args;
+
+/* Builds LUT_hat for (lut_bits, clip) (Sec. 3.1 Eq. lut_re, Sec. 3.2 Eq. lut16) and binds the
+ * context to cfg->device.  *out receives the context; release it with intattn_destroy. */
+INTATTN_API int intattn_create(intattn_ctx **out, const intattn_config *cfg);
+
+/* Enqueues the fused IntAttention forward (Sec. 3) on hip_stream (a hipStream_t; NULL is
+ * the default stream) and returns without waiting for it. */
+INTATTN_API int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
+
+/* In-run comparator: the conventional INT8 pipeline the paper calls "Quant-Only"
+ * (Sec. 2.2): INT8 Q.K^T, dequantize to fp32 with alpha, fp32 softmax, requantize P to
+ * signed INT8 (x127), INT8 P.V, requantize the output with the same s_O.  Same arguments
+ * and launch shape as intattn_forward; results are close to, not equal to, fp softmax
+ * attention.  dbg_* taps are ignored. */
+INTATTN_API int intattn_forward_quantonly(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
+
+/* Host-only parameter derivation, exposed for tests: c_int of Eq. clipping_thr for
+ * (s_q, s_k, d), and the output multiplier/shift for (s_v, s_o).  Any output pointer may be
+ * NULL.  Returns INTATTN_ERR_INVALID_ARG for non-positive scales or an unrepresentable ratio. */
+INTATTN_API int intattn_derive_params(const intattn_ctx *ctx, float s_q, float s_k, float s_v, float s_o,
+                          int32_t d, int64_t *c_int, int32_t *rq_mult, int32_t *rq_shift);
+
+/* Host-only, exposed for tests: how the kernels evaluate the index map of Sec. 3.1,
+ * idx = round(x * (2^b - 1) / c_int) for x in [0, c_int], without dividing.  mode 1:
+ * idx = (x * mul + add) >> shift in 32-bit unsigned arithmetic, proven equal to the exact
+ * quotient on the whole range; mode 0: no such constants exist, the kernel divides. */
+INTATTN_API int intattn_derive_index_map(const intattn_ctx *ctx, int64_t c_int, int32_t *mode, uint32_t *mul,
+                                         uint32_t *add, int32_t *shift);
+
+/* Copies the 2^b bytes of LUT_hat to dst (HOST); cap is dst's capacity in bytes.
+ * Returns the number of bytes written, or a negative error. */
+INTATTN_API int intattn_get_lut(const intattn_ctx *ctx, uint8_t *dst, int32_t cap);
+
+/* Text of the last error recorded on ctx (never NULL; empty if none).  With ctx == NULL,
+ * the text of the last failed intattn_create on this thread. */
+INTATTN_API const char *intattn_last_error(const intattn_ctx *ctx);
+
+/* Releases the context and the device memory it owns.  NULL is allowed. */
+INTATTN_API void intattn_destroy(intattn_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INTATTN_H */

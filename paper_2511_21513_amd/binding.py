@@ -1,0 +1,220 @@
+"""Thin ctypes binding of the C ABI in ``include/intattn.h``.
+
+Argument marshalling only: torch supplies device memory and the stream, every step of the
+attention path runs inside ``libintattn.so``.  There is no fallback: if the library has not
+been built (``python -m paper_2511_21513_amd.build`` or ``__graft_entry__.build()``), loading
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libintattn.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = 0, -1, -2, -3, -4
+
+SYMBOLS = (
+    "intattn_create",
+    "intattn_forward",
+    "intattn_forward_quantonly",
+    "intattn_derive_params",
+    "intattn_derive_index_map",
+    "intattn_get_lut",
+    "intattn_last_error",
+    "intattn_destroy",
+)
+
+
+class IntAttnError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"intattn error {code}: {text}")
+        self.code = code
+
+
+class Config(ctypes.Structure):
+    _fields_ = [
+        ("device", ctypes.c_int32),
+        ("lut_bits", ctypes.c_int32),
+        ("clip", ctypes.c_double),
+        ("variant", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
+    ]
+
+
+class Args(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+        ("L", ctypes.c_int32), ("d", ctypes.c_int32), ("causal", ctypes.c_int32),
+        ("q", ctypes.c_void_p), ("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("out", ctypes.c_void_p),
+        ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
+        ("v_stride", ctypes.c_int64 * 3), ("out_stride", ctypes.c_int64 * 3),
+        ("scale_mode", ctypes.c_int32),
+        ("scale_q", ctypes.c_void_p), ("scale_k", ctypes.c_void_p),
+        ("scale_v", ctypes.c_void_p), ("scale_out", ctypes.c_void_p),
+        ("dbg_row_max", ctypes.c_void_p), ("dbg_row_sum", ctypes.c_void_p), ("dbg_acc", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Loads libintattn.so (raises if it is not built) and declares the prototypes."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2511_21513_amd.build` "
+                "(there is no fallback path)"
+            )
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        lib.intattn_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(Config)]
+        lib.intattn_create.restype = i32
+        lib.intattn_forward.argtypes = [vp, ctypes.POINTER(Args), vp]
+        lib.intattn_forward.restype = i32
+        lib.intattn_forward_quantonly.argtypes = [vp, ctypes.POINTER(Args), vp]
+        lib.intattn_forward_quantonly.restype = i32
+        lib.intattn_derive_params.argtypes = [
+            vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float, i32,
+            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(i32), ctypes.POINTER(i32),
+        ]
+        lib.intattn_derive_params.restype = i32
+        lib.intattn_derive_index_map.argtypes = [
+            vp, ctypes.c_int64, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_uint32),
+            ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(i32),
+        ]
+        lib.intattn_derive_index_map.restype = i32
+        lib.intattn_get_lut.argtypes = [vp, vp, i32]
+        lib.intattn_get_lut.restype = i32
+        lib.intattn_last_error.argtypes = [vp]
+        lib.intattn_last_error.restype = ctypes.c_char_p
+        lib.intattn_destroy.argtypes = [vp]
+        lib.intattn_destroy.restype = None
+        _lib = lib
+    return _lib
+
+
+def _host_f32(x):
+    if x is None:
+        return None
+    return np.ascontiguousarray(np.atleast_1d(np.asarray(x, dtype=np.float32)))
+
+
+class IntAttn:
+    """One library context (``intattn_create`` .. ``intattn_destroy``)."""
+
+    def __init__(self, device: int = 0, lut_bits: int = 5, clip: float = 6.6, variant: int = 0):
+        self._lib = load()
+        self._ctx = ctypes.c_void_p()
+        cfg = Config(device, lut_bits, clip, variant, 0)
+        rc = self._lib.intattn_create(ctypes.byref(self._ctx), ctypes.byref(cfg))
+        if rc != OK:
+            raise IntAttnError(rc, (self._lib.intattn_last_error(None) or b"").decode())
+        self.device = device
+
+    def close(self):
+        if getattr(self, "_ctx", None) is not None and self._ctx.value:
+            self._lib.intattn_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def last_error(self) -> str:
+        return (self._lib.intattn_last_error(self._ctx) or b"").decode()
+
+    def lut(self) -> np.ndarray:
+        buf = np.zeros(32, dtype=np.uint8)
+        n = self._lib.intattn_get_lut(self._ctx, buf.ctypes.data_as(ctypes.c_void_p), 32)
+        if n < 0:
+            raise IntAttnError(n, "intattn_get_lut")
+        return buf[:n].copy()
+
+    def derive_params(self, s_q, s_k, s_v, s_o, d):
+        c, m, sh = ctypes.c_int64(0), ctypes.c_int32(0), ctypes.c_int32(0)
+        rc = self._lib.intattn_derive_params(
+            self._ctx, float(np.float32(s_q)), float(np.float32(s_k)), float(np.float32(s_v)),
+            float(np.float32(s_o)), d, ctypes.byref(c), ctypes.byref(m), ctypes.byref(sh),
+        )
+        if rc != OK:
+            raise IntAttnError(rc, "intattn_derive_params")
+        return int(c.value), int(m.value), int(sh.value)
+
+    def derive_index_map(self, c_int: int):
+        mode, sh = ctypes.c_int32(0), ctypes.c_int32(0)
+        mul, add = ctypes.c_uint32(0), ctypes.c_uint32(0)
+        rc = self._lib.intattn_derive_index_map(
+            self._ctx, c_int, ctypes.byref(mode), ctypes.byref(mul), ctypes.byref(add), ctypes.byref(sh)
+        )
+        if rc != OK:
+            raise IntAttnError(rc, "intattn_derive_index_map")
+        return int(mode.value), int(mul.value), int(add.value), int(sh.value)
+
+    def make_args(self, q, k, v, out, s_q, s_k, s_v, s_o=None, *, causal=False, per_head=False,
+                  row_max=None, row_sum=None, acc=None):
+        """Marshals torch int8 tensors [B,H,L,d] (last dim contiguous) into an ``Args``.  Returns
+        (args, keepalive): keepalive holds the host scale arrays the struct points at."""
+        B, Hq, L, d = q.shape
+        Hkv = k.shape[1]
+        for t in (q, k, v, out):
+            if t.stride(-1) != 1:
+                raise ValueError("the head dimension must be contiguous")
+        a = Args()
+        a.B, a.Hq, a.Hkv, a.L, a.d, a.causal = B, Hq, Hkv, L, d, int(bool(causal))
+        a.q, a.k, a.v, a.out = q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr()
+        a.q_stride = (ctypes.c_int64 * 3)(*q.stride()[:3])
+        a.k_stride = (ctypes.c_int64 * 3)(*k.stride()[:3])
+        a.v_stride = (ctypes.c_int64 * 3)(*v.stride()[:3])
+        a.out_stride = (ctypes.c_int64 * 3)(*out.stride()[:3])
+        a.scale_mode = int(bool(per_head))
+        keep = [_host_f32(s_q), _host_f32(s_k), _host_f32(s_v), _host_f32(s_o)]
+        if per_head:
+            if keep[0].size != Hq or keep[1].size != Hkv or keep[2].size != Hkv or (
+                    keep[3] is not None and keep[3].size != Hq):
+                raise ValueError("per-head scales must have Hq (q, out) / Hkv (k, v) entries")
+        a.scale_q, a.scale_k, a.scale_v = (x.ctypes.data for x in keep[:3])
+        a.scale_out = keep[3].ctypes.data if keep[3] is not None else None
+        a.dbg_row_max = row_max.data_ptr() if row_max is not None else None
+        a.dbg_row_sum = row_sum.data_ptr() if row_sum is not None else None
+        a.dbg_acc = acc.data_ptr() if acc is not None else None
+        return a, keep
+
+    def forward_args(self, args: Args, stream: int = 0, quantonly: bool = False):
+        fn = self._lib.intattn_forward_quantonly if quantonly else self._lib.intattn_forward
+        rc = fn(self._ctx, ctypes.byref(args), ctypes.c_void_p(stream))
+        if rc != OK:
+            raise IntAttnError(rc, self.last_error())
+
+    def forward(self, q, k, v, s_q, s_k, s_v, s_o=None, *, causal=False, per_head=False, out=None,
+                taps=False, stream=None, quantonly=False):
+        """intattn_forward on torch tensors.  Returns ``out`` (int8 [B,Hq,L,d]); with ``taps`` a
+        dict with out, row_max, row_sum, acc.  Enqueued on torch's current stream unless given."""
+        import torch
+
+        if out is None:
+            out = torch.empty_like(q)
+        extra = {}
+        if taps:
+            B, Hq, L, d = q.shape
+            extra = {
+                "row_max": torch.zeros((B, Hq, L), dtype=torch.int32, device=q.device),
+                "row_sum": torch.zeros((B, Hq, L), dtype=torch.int32, device=q.device),
+                "acc": torch.zeros((B, Hq, L, d), dtype=torch.int32, device=q.device),
+            }
+        args, keep = self.make_args(q, k, v, out, s_q, s_k, s_v, s_o, causal=causal, per_head=per_head, **extra)
+        if stream is None:
+            stream = torch.cuda.current_stream(q.device).cuda_stream
+        self.forward_args(args, stream, quantonly)
+        del keep
+        if taps:
+            extra["out"] = out
+            return extra
+        return out

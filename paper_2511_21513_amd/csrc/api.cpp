@@ -1,0 +1,403 @@
+// Host side of the C ABI declared in include/intattn.h: argument checking, derivation of the
+// integer parameters from the scales (Eq. logit-scale, Eq. clipping_thr), LUT_hat
+// (Eq. lut_re, Eq. lut16), and kernel launches.  No CPU fallback exists: if a launch
+// fails, the error is returned.
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/intattn.h"
+#include "params.h"
+
+using namespace intattn;
+
+struct intattn_ctx {
+    int device = 0;
+    int lut_bits = 5;
+    double clip = 6.6;
+    int variant = 0;
+    uint8_t lut[32] = {0};
+    // device-side per-head tables (allocated on first per-head call, grown on demand)
+    HeadParams *d_hp = nullptr;
+    float *d_alpha = nullptr, *d_svso = nullptr;
+    int table_cap = 0;
+    std::vector<HeadParams> hp_host;  // what d_hp currently holds
+    std::vector<float> alpha_host, svso_host;
+    std::string err;
+};
+
+namespace {
+
+thread_local std::string g_create_err;
+
+int fail(intattn_ctx *ctx, int code, const std::string &msg)
+{
+    if (ctx) ctx->err = msg;
+    else g_create_err = msg;
+    return code;
+}
+
+int hip_fail(intattn_ctx *ctx, hipError_t e, const char *what)
+{
+    return fail(ctx, INTATTN_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+// Scoped "make ctx->device current", restoring the caller's device afterwards.
+struct DeviceGuard {
+    int prev = -1;
+    bool changed = false;
+    hipError_t status = hipSuccess;
+    explicit DeviceGuard(int dev)
+    {
+        status = hipGetDevice(&prev);
+        if (status == hipSuccess && prev != dev) {
+            status = hipSetDevice(dev);
+            changed = (status == hipSuccess);
+        }
+    }
+    ~DeviceGuard()
+    {
+        if (changed) (void)hipSetDevice(prev);
+    }
+};
+
+bool good_scale(float s) { return std::isfinite(s) && s > 0.0f; }
+
+// Eq. clipping_thr.  Capped at 2^30: with |A_hat| <= 128*128*d the index is 0 for every
+// element once c_int > 62 * 2 * 128*128*128, so the cap never changes a result.
+int64_t derive_c_int(double clip, float s_q, float s_k, int d)
+{
+    const double alpha = ((double)s_q * (double)s_k) / std::sqrt((double)d);
+    const double c = std::floor(clip / alpha + 0.5);
+    if (!(c >= 1.0)) return 1;
+    if (c > 1073741824.0) return 1073741824LL;
+    return (int64_t)c;
+}
+
+bool derive_requant(float s_v, float s_o, int32_t *mult, int32_t *shift)
+{
+    const double r = (double)s_v / (255.0 * (double)s_o);
+    if (!(r > 0.0) || !std::isfinite(r)) return false;
+    int e = 0;
+    const double m = std::frexp(r, &e);
+    long long M = std::llround(m * 2147483648.0);
+    if (M == 2147483648LL) {
+        M = 1073741824LL;
+        e += 1;
+    }
+    const int sh = 31 - e;
+    if (sh < 1 || sh > 62) return false;
+    *mult = (int32_t)M;
+    *shift = sh;
+    return true;
+}
+
+uint32_t true_index(uint64_t dclip, uint64_t c_int, uint64_t top) { return (uint32_t)((2 * top * dclip + c_int) / (2 * c_int)); }
+
+// Finds (mul, add, shift) with ((x * mul + add) >> shift) == round(x * top / c_int) for every
+// integer x in [0, c_int], using 24-bit operands and a 32-bit sum.  Both sides are monotone
+// step functions of x, so agreement at x = 0, x = c_int and on both sides of every true
+// step proves agreement everywhere.
+bool find_mad24(uint32_t c_int, uint32_t top, HeadParams *hp)
+{
+    if (c_int >= (1u << 24)) return false;
+    std::vector<uint32_t> pts;
+    pts.push_back(0);
+    pts.push_back(c_int);
+    for (uint64_t k = 1; k <= top; ++k) {
+        // smallest x with round(x*top/c_int) >= k:  x >= (2k-1) c_int / (2 top)
+        const uint64_t num = (2 * k - 1) * (uint64_t)c_int, den = 2ull * top;
+        const uint64_t t = (num + den - 1) / den;
+        if (t <= c_int) {
+            pts.push_back((uint32_t)t);
+            if (t > 0) pts.push_back((uint32_t)(t - 1));
+        }
+    }
+    for (int s = 27; s >= 8; --s) {
+        const uint64_t num = (uint64_t)top << s;
+        const uint64_t cands[2] = {(num + c_int - 1) / c_int, num / c_int};
+        for (uint64_t mul : cands) {
+            if (mul == 0 || mul >= (1ull << 24)) continue;
+            const uint64_t add = 1ull << (s - 1);
+            if ((uint64_t)c_int * mul + add >= (1ull << 32)) continue;
+            bool ok = true;
+            for (uint32_t x : pts) {
+                const uint32_t got = (uint32_t)(((uint64_t)x * mul + add) >> s);
+                if (got != true_index(x, c_int, top)) {
+                    ok = false;
+                    break;
+                }
+            }
+            if (ok) {
+                hp->idx_mul = (uint32_t)mul;
+                hp->idx_add = (uint32_t)add;
+                hp->idx_shift = s;
+                return true;
+            }
+        }
+    }
+    return false;
+}
+
+struct Derived {
+    std::vector<HeadParams> hp;
+    std::vector<float> alpha, svso;
+    int idx_mode = IDX_MAD24;
+};
+
+int validate(intattn_ctx *ctx, const intattn_args *a)
+{
+    if (!ctx) return INTATTN_ERR_INVALID_ARG;
+    if (!a) return fail(ctx, INTATTN_ERR_INVALID_ARG, "args is NULL");
+    if (a->B < 1 || a->Hq < 1 || a->Hkv < 1 || a->L < 1)
+        return fail(ctx, INTATTN_ERR_INVALID_ARG, "B, Hq, Hkv, L must be >= 1");
+    if (a->Hq % a->Hkv != 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "Hq must be a multiple of Hkv");
+    if (a->d != 64 && a->d != 128) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "d must be 64 or 128");
+    if (a->L > 131071) return fail(ctx, INTATTN_ERR_INVALID_ARG, "L exceeds 131071 (int32 accumulator bound)");
+    if (a->causal != 0 && a->causal != 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "causal must be 0 or 1");
+    if (a->scale_mode != 0 && a->scale_mode != 1)
+        return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode must be 0 or 1");
+    if (!a->q || !a->k || !a->v || !a->out) return fail(ctx, INTATTN_ERR_INVALID_ARG, "q, k, v, out must be non-NULL");
+    if (!a->scale_q || !a->scale_k || !a->scale_v)
+        return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_q, scale_k, scale_v must be non-NULL");
+    if ((const void *)a->out == (const void *)a->q || (const void *)a->out == (const void *)a->k ||
+        (const void *)a->out == (const void *)a->v)
+        return fail(ctx, INTATTN_ERR_INVALID_ARG, "out must not alias an input");
+    const void *ptrs[4] = {a->q, a->k, a->v, a->out};
+    for (const void *ptr : ptrs)
+        if (((uintptr_t)ptr & 15u) != 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    const int64_t *strides[4] = {a->q_stride, a->k_stride, a->v_stride, a->out_stride};
+    for (const int64_t *s : strides) {
+        for (int i = 0; i < 3; ++i)
+            if (s[i] < 0 || (s[i] & 15) != 0)
+                return fail(ctx, INTATTN_ERR_INVALID_ARG, "strides must be non-negative multiples of 16");
+        if (s[2] < a->d) return fail(ctx, INTATTN_ERR_INVALID_ARG, "the L stride must be at least d");
+    }
+    const int64_t rows_per_block = fwd_rows_per_block(ctx->variant);
+    const int64_t n_qtiles = (a->L + rows_per_block - 1) / rows_per_block;
+    if (n_qtiles * (int64_t)a->B * (int64_t)a->Hq > 2147483647LL)
+        return fail(ctx, INTATTN_ERR_UNSUPPORTED, "problem needs more than 2^31-1 workgroups");
+    return INTATTN_OK;
+}
+
+int derive_all(intattn_ctx *ctx, const intattn_args *a, Derived *out)
+{
+    const int n = a->scale_mode ? a->Hq : 1;
+    const int g = a->Hq / a->Hkv;
+    const uint32_t top = (1u << ctx->lut_bits) - 1u;
+    out->hp.assign((size_t)n, HeadParams{});
+    out->alpha.assign((size_t)n, 0.f);
+    out->svso.assign((size_t)n, 0.f);
+    out->idx_mode = IDX_MAD24;
+    for (int h = 0; h < n; ++h) {
+        const int kv = a->scale_mode ? h / g : 0;
+        const float sq = a->scale_q[h], sk = a->scale_k[kv], sv = a->scale_v[kv];
+        const float so = a->scale_out ? a->scale_out[h] : sv;
+        if (!good_scale(sq) || !good_scale(sk) || !good_scale(sv) || !good_scale(so))
+            return fail(ctx, INTATTN_ERR_INVALID_ARG, "scales must be finite and > 0");
+        HeadParams &hp = out->hp[(size_t)h];
+        hp.c_int = (int32_t)derive_c_int(ctx->clip, sq, sk, a->d);
+        if (!derive_requant(sv, so, &hp.rq_mult, &hp.rq_shift))
+            return fail(ctx, INTATTN_ERR_INVALID_ARG, "s_V / (255 s_O) is outside the representable range");
+        if (!find_mad24((uint32_t)hp.c_int, top, &hp)) out->idx_mode = IDX_DIV;
+        out->alpha[(size_t)h] = (float)(((double)sq * (double)sk) / std::sqrt((double)a->d));
+        out->svso[(size_t)h] = (float)((double)sv / (double)so);
+    }
+    return INTATTN_OK;
+}
+
+int ensure_tables(intattn_ctx *ctx, int n)
+{
+    if (n <= ctx->table_cap) return INTATTN_OK;
+    int cap = ctx->table_cap ? ctx->table_cap : 64;
+    while (cap < n) cap *= 2;
+    HeadParams *hp = nullptr;
+    float *al = nullptr, *sv = nullptr;
+    hipError_t e = hipMalloc((void **)&hp, sizeof(HeadParams) * (size_t)cap);
+    if (e == hipSuccess) e = hipMalloc((void **)&al, sizeof(float) * (size_t)cap);
+    if (e == hipSuccess) e = hipMalloc((void **)&sv, sizeof(float) * (size_t)cap);
+    if (e != hipSuccess) {
+        if (hp) (void)hipFree(hp);
+        if (al) (void)hipFree(al);
+        if (sv) (void)hipFree(sv);
+        return fail(ctx, INTATTN_ERR_NOMEM, std::string("hipMalloc of per-head tables: ") + hipGetErrorString(e));
+    }
+    // Frees are stream-ordered with respect to earlier work in HIP (the free waits), so old
+    // tables that a running kernel may still read are released safely.
+    if (ctx->d_hp) (void)hipFree(ctx->d_hp);
+    if (ctx->d_alpha) (void)hipFree(ctx->d_alpha);
+    if (ctx->d_svso) (void)hipFree(ctx->d_svso);
+    ctx->d_hp = hp;
+    ctx->d_alpha = al;
+    ctx->d_svso = sv;
+    ctx->table_cap = cap;
+    ctx->hp_host.clear();
+    ctx->alpha_host.clear();
+    ctx->svso_host.clear();
+    return INTATTN_OK;
+}
+
+int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator)
+{
+    int rc = validate(ctx, a);
+    if (rc) return rc;
+    if (ctx->device < 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "host-only context (device -1) cannot launch");
+    Derived dv;
+    rc = derive_all(ctx, a, &dv);
+    if (rc) return rc;
+
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return hip_fail(ctx, guard.status, "hipSetDevice");
+
+    FwdParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.q = a->q; p.k = a->k; p.v = a->v; p.out = a->out;
+    for (int i = 0; i < 3; ++i) {
+        p.qs[i] = a->q_stride[i]; p.ks[i] = a->k_stride[i];
+        p.vs[i] = a->v_stride[i]; p.os[i] = a->out_stride[i];
+    }
+    p.B = a->B; p.Hq = a->Hq; p.Hkv = a->Hkv; p.L = a->L;
+    p.causal = a->causal;
+    p.group = a->Hq / a->Hkv;
+    p.top = (1 << ctx->lut_bits) - 1;
+    const int rows_per_block = fwd_rows_per_block(ctx->variant);
+    p.n_qtiles = (a->L + rows_per_block - 1) / rows_per_block;
+    std::memcpy(p.lut, ctx->lut, 32);
+    p.dbg_row_max = a->dbg_row_max; p.dbg_row_sum = a->dbg_row_sum; p.dbg_acc = a->dbg_acc;
+
+    if (a->scale_mode == 0) {
+        p.hp_table = nullptr;
+        p.hp0 = dv.hp[0];
+        p.alpha0 = dv.alpha[0];
+        p.sv_over_so0 = dv.svso[0];
+    } else {
+        rc = ensure_tables(ctx, a->Hq);
+        if (rc) return rc;
+        hipStream_t st = (hipStream_t)stream;
+        const size_t n = (size_t)a->Hq;
+        const bool same_hp = ctx->hp_host.size() == n &&
+                             std::memcmp(ctx->hp_host.data(), dv.hp.data(), n * sizeof(HeadParams)) == 0;
+        if (!same_hp) {
+            hipError_t e = hipMemcpyAsync(ctx->d_hp, dv.hp.data(), n * sizeof(HeadParams), hipMemcpyHostToDevice, st);
+            if (e != hipSuccess) return hip_fail(ctx, e, "hipMemcpyAsync(head params)");
+            ctx->hp_host = dv.hp;
+        }
+        const bool same_f = ctx->alpha_host == dv.alpha && ctx->svso_host == dv.svso;
+        if (comparator && !same_f) {
+            hipError_t e = hipMemcpyAsync(ctx->d_alpha, dv.alpha.data(), n * sizeof(float), hipMemcpyHostToDevice, st);
+            if (e == hipSuccess)
+                e = hipMemcpyAsync(ctx->d_svso, dv.svso.data(), n * sizeof(float), hipMemcpyHostToDevice, st);
+            if (e != hipSuccess) return hip_fail(ctx, e, "hipMemcpyAsync(comparator scales)");
+            ctx->alpha_host = dv.alpha;
+            ctx->svso_host = dv.svso;
+        }
+        p.hp_table = ctx->d_hp;
+        p.alpha_table = ctx->d_alpha;
+        p.svso_table = ctx->d_svso;
+    }
+
+    const int herr = comparator ? launch_quantonly(p, a->d, ctx->variant, stream)
+                                : launch_fwd(p, a->d, dv.idx_mode, ctx->variant, stream);
+    if (herr != 0) return hip_fail(ctx, (hipError_t)herr, comparator ? "launch(quant-only)" : "launch(intattn forward)");
+    ctx->err.clear();
+    return INTATTN_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int intattn_create(intattn_ctx **out, const intattn_config *cfg)
+{
+    if (!out || !cfg) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "out and cfg must be non-NULL");
+    *out = nullptr;
+    if (cfg->lut_bits < 1 || cfg->lut_bits > 5) return fail(nullptr, INTATTN_ERR_UNSUPPORTED, "lut_bits must be in 1..5");
+    if (!(cfg->clip > 0.0) || !std::isfinite(cfg->clip)) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "clip must be finite and > 0");
+    if (cfg->reserved != 0) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "reserved must be 0");
+    if (cfg->device < -1) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "no such HIP device");
+    if (cfg->device >= 0) {
+        int ndev = 0;
+        hipError_t e = hipGetDeviceCount(&ndev);
+        if (e != hipSuccess) return hip_fail(nullptr, e, "hipGetDeviceCount");
+        if (cfg->device >= ndev) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "no such HIP device");
+    }
+    intattn_ctx *ctx = new (std::nothrow) intattn_ctx();
+    if (!ctx) return fail(nullptr, INTATTN_ERR_NOMEM, "out of host memory");
+    ctx->device = cfg->device;
+    ctx->lut_bits = cfg->lut_bits;
+    ctx->clip = cfg->clip;
+    ctx->variant = cfg->variant;
+    // Eq. lut_re and Eq. lut16
+    const int n = 1 << cfg->lut_bits;
+    for (int i = 0; i < n - 1; ++i)
+        ctx->lut[i] = (uint8_t)std::floor(255.0 * std::exp(-cfg->clip * (double)i / (double)(n - 1)) + 0.5);
+    ctx->lut[n - 1] = 0;
+    *out = ctx;
+    return INTATTN_OK;
+}
+
+int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void *hip_stream)
+{
+    return run(ctx, args, hip_stream, false);
+}
+
+int intattn_forward_quantonly(intattn_ctx *ctx, const intattn_args *args, void *hip_stream)
+{
+    return run(ctx, args, hip_stream, true);
+}
+
+int intattn_derive_params(const intattn_ctx *ctx, float s_q, float s_k, float s_v, float s_o, int32_t d,
+                          int64_t *c_int, int32_t *rq_mult, int32_t *rq_shift)
+{
+    if (!ctx || d < 1) return INTATTN_ERR_INVALID_ARG;
+    if (!good_scale(s_q) || !good_scale(s_k) || !good_scale(s_v) || !good_scale(s_o)) return INTATTN_ERR_INVALID_ARG;
+    int32_t m = 0, sh = 0;
+    if (!derive_requant(s_v, s_o, &m, &sh)) return INTATTN_ERR_INVALID_ARG;
+    if (c_int) *c_int = derive_c_int(ctx->clip, s_q, s_k, d);
+    if (rq_mult) *rq_mult = m;
+    if (rq_shift) *rq_shift = sh;
+    return INTATTN_OK;
+}
+
+int intattn_derive_index_map(const intattn_ctx *ctx, int64_t c_int, int32_t *mode, uint32_t *mul, uint32_t *add,
+                             int32_t *shift)
+{
+    if (!ctx || c_int < 1 || c_int > 1073741824LL || !mode || !mul || !add || !shift) return INTATTN_ERR_INVALID_ARG;
+    HeadParams hp{};
+    const uint32_t top = (1u << ctx->lut_bits) - 1u;
+    *mode = find_mad24((uint32_t)c_int, top, &hp) ? IDX_MAD24 : IDX_DIV;
+    *mul = hp.idx_mul;
+    *add = hp.idx_add;
+    *shift = hp.idx_shift;
+    return INTATTN_OK;
+}
+
+int intattn_get_lut(const intattn_ctx *ctx, uint8_t *dst, int32_t cap)
+{
+    if (!ctx || !dst) return INTATTN_ERR_INVALID_ARG;
+    const int n = 1 << ctx->lut_bits;
+    if (cap < n) return INTATTN_ERR_INVALID_ARG;
+    std::memcpy(dst, ctx->lut, (size_t)n);
+    return n;
+}
+
+const char *intattn_last_error(const intattn_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+void intattn_destroy(intattn_ctx *ctx)
+{
+    if (!ctx) return;
+    if (ctx->device >= 0) {
+        DeviceGuard guard(ctx->device);
+        if (ctx->d_hp) (void)hipFree(ctx->d_hp);
+        if (ctx->d_alpha) (void)hipFree(ctx->d_alpha);
+        if (ctx->d_svso) (void)hipFree(ctx->d_svso);
+    }
+    delete ctx;
+}
+
+} // extern "C"

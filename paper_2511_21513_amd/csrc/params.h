@@ -1,0 +1,51 @@
+// Internal structures shared by the host side of the library and its kernels.
+// Not part of the public ABI (that is include/intattn.h).
+#pragma once
+#include <stdint.h>
+
+namespace intattn {
+
+// How a kernel turns a clipped distance Delta' in [0, c_int] into the table index
+// idx = round(Delta' * top / c_int)  (Sec. 3.1 index map), exactly.
+enum IdxMode : int32_t {
+    IDX_DIV = 0,    // integer division, any c_int (slow, always exact)
+    IDX_MAD24 = 1,  // (Delta' * mul + add) >> shift, 24-bit operands, 32-bit result
+    IDX_MULHI24 = 2 // high 32 bits of the 48-bit product ((Delta' << pre) + add) * mul
+};
+
+// Per query head: everything the kernel needs that depends on the scales.
+struct HeadParams {
+    int32_t c_int;     // clip threshold of Eq. clipping_thr, capped at 2^30
+    uint32_t idx_mul;  // index-map multiplier (modes MAD24 / MULHI24)
+    uint32_t idx_add;  // index-map addend
+    int32_t idx_shift; // MAD24: right shift; MULHI24: left pre-shift of Delta'
+    int32_t rq_mult;   // output requantization multiplier M in [2^30, 2^31)
+    int32_t rq_shift;  // output requantization shift sh in [1, 62]
+    int32_t pad[2];
+};
+
+struct FwdParams {
+    const int8_t *q, *k, *v;
+    int8_t *out;
+    int64_t qs[3], ks[3], vs[3], os[3]; // byte strides of B, H, L
+    int32_t B, Hq, Hkv, L;
+    int32_t causal;
+    int32_t group;       // Hq / Hkv
+    int32_t top;         // 2^b - 1
+    int32_t n_qtiles;    // ceil(L / rows per workgroup)
+    const HeadParams *hp_table; // device [Hq] when per-head, else nullptr
+    HeadParams hp0;             // the single parameter set when hp_table == nullptr
+    uint32_t lut[8];            // LUT_hat, 32 bytes packed little-endian (unused tail is 0)
+    int32_t *dbg_row_max, *dbg_row_sum, *dbg_acc;
+    // comparator only
+    float alpha0, sv_over_so0;  // per-tensor values when the float tables are null
+    const float *alpha_table;   // device [Hq]
+    const float *svso_table;    // device [Hq]
+};
+
+// Launchers implemented in the .hip files.  Return a hipError_t cast to int.
+int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *stream);
+int fwd_rows_per_block(int variant);
+int launch_quantonly(const FwdParams &p, int d, int variant, void *stream);
+
+} // namespace intattn

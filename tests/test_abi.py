@@ -1,0 +1,162 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares,
+its structs have the layout the binding assumes, its argument checks reject bad calls
+without touching a GPU, and its host-side parameter derivation (which shares no code with
+the oracle) agrees with the oracle's."""
+import ctypes
+import os
+import re
+import subprocess
+import tempfile
+
+import numpy as np
+import pytest
+
+from paper_2511_21513_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "intattn.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2511_21513_amd import build
+
+        build.build()
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    return re.findall(r"INTATTN_API\s+[\w\s\*]+?\b(intattn_\w+)\s*\(", text)
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_symbols()
+    assert len(names) >= 8
+    assert set(names) == set(binding.SYMBOLS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_struct_layout_matches_header(lib):
+    """Compile a probe against the real header with gcc and compare sizeof/offsetof with the
+    ctypes mirrors."""
+    fields_cfg = [f[0] for f in binding.Config._fields_]
+    fields_arg = [f[0] for f in binding.Args._fields_]
+    src = ['#include <stdio.h>', '#include <stddef.h>', f'#include "{HEADER}"', "int main(void){"]
+    src.append('printf("%zu\\n", sizeof(intattn_config));')
+    src += [f'printf("%zu\\n", offsetof(intattn_config, {f}));' for f in fields_cfg]
+    src.append('printf("%zu\\n", sizeof(intattn_args));')
+    src += [f'printf("%zu\\n", offsetof(intattn_args, {f}));' for f in fields_arg]
+    src.append("return 0;}")
+    with tempfile.TemporaryDirectory() as td:
+        c = os.path.join(td, "probe.c")
+        open(c, "w").write("\n".join(src))
+        exe = os.path.join(td, "probe")
+        subprocess.run(["gcc", "-std=c11", "-o", exe, c], check=True)
+        vals = [int(x) for x in subprocess.run([exe], check=True, capture_output=True, text=True).stdout.split()]
+    want = [ctypes.sizeof(binding.Config)] + [getattr(binding.Config, f).offset for f in fields_cfg]
+    want += [ctypes.sizeof(binding.Args)] + [getattr(binding.Args, f).offset for f in fields_arg]
+    assert vals == want
+
+
+def test_create_rejects_bad_config(lib):
+    ctx = ctypes.c_void_p()
+    assert lib.intattn_create(None, None) == binding.ERR_INVALID_ARG
+    for cfg in (binding.Config(-1, 0, 6.6, 0, 0), binding.Config(-1, 6, 6.6, 0, 0)):
+        assert lib.intattn_create(ctypes.byref(ctx), ctypes.byref(cfg)) == binding.ERR_UNSUPPORTED
+    for cfg in (binding.Config(-1, 5, 0.0, 0, 0), binding.Config(-1, 5, float("nan"), 0, 0),
+                binding.Config(-1, 5, 6.6, 0, 7), binding.Config(-5, 5, 6.6, 0, 0)):
+        assert lib.intattn_create(ctypes.byref(ctx), ctypes.byref(cfg)) == binding.ERR_INVALID_ARG
+        assert lib.intattn_last_error(None)
+    lib.intattn_destroy(None)  # allowed
+
+
+@pytest.fixture()
+def host_ctx(lib):
+    ia = binding.IntAttn(device=-1)
+    yield ia
+    ia.close()
+
+
+def test_host_only_context_lut_and_params_agree_with_oracle(host_ctx, oracle):
+    np.testing.assert_array_equal(host_ctx.lut(), oracle.lut(5, 6.6))
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        sq, sk = np.float32(rng.uniform(0.002, 0.5)), np.float32(rng.uniform(0.002, 0.5))
+        sv, so = np.float32(rng.uniform(0.002, 0.5)), np.float32(rng.uniform(0.0005, 0.5))
+        d = int(rng.choice([64, 128]))
+        c, m, sh = host_ctx.derive_params(sq, sk, sv, so, d)
+        assert c == oracle.c_int(6.6, sq, sk, d)
+        assert (m, sh) == oracle.requant_params(sv, so)
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 5])
+def test_other_table_sizes_agree_with_oracle(lib, oracle, bits):
+    ia = binding.IntAttn(device=-1, lut_bits=bits, clip=5.5)
+    np.testing.assert_array_equal(ia.lut(), oracle.lut(bits, 5.5))
+    ia.close()
+
+
+def test_index_map_constants_are_exact(host_ctx, oracle):
+    """The multiply-shift the kernels use instead of a division must equal the exact rounded
+    quotient for every clipped distance; checked exhaustively for a spread of thresholds."""
+    rng = np.random.default_rng(1)
+    cs = [1, 2, 3, 30, 31, 32, 61, 62, 63, 445, 1462, 5203, 6274, 8191, 8192] + [int(x) for x in rng.integers(1, 9000, 40)]
+    n_fast = 0
+    for c in cs:
+        mode, mul, add, sh = host_ctx.derive_index_map(c)
+        if mode == 0:
+            continue
+        n_fast += 1
+        assert mul < 2**24 and c * mul + add < 2**32
+        x = np.arange(c + 1, dtype=np.uint64)
+        got = (x * np.uint64(mul) + np.uint64(add)) >> np.uint64(sh)
+        want = (2 * 31 * x + c) // (2 * c)
+        np.testing.assert_array_equal(got, want)
+        for xi in (0, c // 3, c):
+            assert int(want[xi]) == oracle.index_map(int(xi), c, 5)
+    assert n_fast >= len(cs) // 2
+    # thresholds far beyond the multiply-shift's precision must fall back to division
+    for c in (28794, 55064, 10**6, 2**30):
+        mode, mul, add, sh = host_ctx.derive_index_map(c)
+        if mode == 1:
+            x = np.unique(np.concatenate([np.arange(0, min(c, 70000) + 1), rng.integers(0, c + 1, 50000)])).astype(np.uint64)
+            got = (x * np.uint64(mul) + np.uint64(add)) >> np.uint64(sh)
+            np.testing.assert_array_equal(got, (2 * 31 * x + c) // (2 * c))
+
+
+def test_forward_rejects_bad_arguments_without_a_gpu(host_ctx, lib):
+    buf = np.zeros(1 << 14, dtype=np.int8)
+    base = buf.ctypes.data
+    base += (-base) % 16
+    s = np.asarray([0.05], dtype=np.float32)
+
+    def mk(**kw):
+        a = binding.Args()
+        a.B, a.Hq, a.Hkv, a.L, a.d, a.causal = 1, 2, 1, 8, 64, 0
+        a.q, a.k, a.v, a.out = base, base + 2048, base + 4096, base + 8192
+        for name in ("q_stride", "k_stride", "v_stride", "out_stride"):
+            setattr(a, name, (ctypes.c_int64 * 3)(1024, 512, 64))
+        a.scale_mode = 0
+        a.scale_q = a.scale_k = a.scale_v = s.ctypes.data
+        for k_, v_ in kw.items():
+            setattr(a, k_, v_)
+        return a
+
+    def call(a):
+        return lib.intattn_forward(host_ctx._ctx, ctypes.byref(a), None)
+
+    assert call(mk()) == binding.ERR_INVALID_ARG and "host-only" in host_ctx.last_error()
+    assert call(mk(d=96)) == binding.ERR_UNSUPPORTED
+    for bad in (dict(L=0), dict(Hq=3, Hkv=2), dict(L=200000), dict(causal=2), dict(scale_mode=3), dict(q=None),
+                dict(scale_k=None), dict(out=base), dict(k=base + 2049),
+                dict(v_stride=(ctypes.c_int64 * 3)(1024, 512, 60)), dict(q_stride=(ctypes.c_int64 * 3)(1024, 512, 32))):
+        assert call(mk(**bad)) == binding.ERR_INVALID_ARG, bad
+        assert host_ctx.last_error()
+    assert lib.intattn_forward(None, ctypes.byref(mk()), None) == binding.ERR_INVALID_ARG
+    assert lib.intattn_forward(host_ctx._ctx, None, None) == binding.ERR_INVALID_ARG
+    zero = np.asarray([0.0], dtype=np.float32)
+    # scale checks come after the host-only rejection on this context, so only the struct checks are reachable here
+    assert call(mk(scale_q=zero.ctypes.data)) == binding.ERR_INVALID_ARG

@@ -1,0 +1,176 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  The whole pipeline is integer, so the bar is bit-exact: zero mismatching
+bytes in the INT8 output, and equal int32 row max / row sum / accumulator taps."""
+import numpy as np
+import pytest
+
+from paper_2511_21513_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a visible MI355X (torch.cuda.is_available() is False)")
+    return torch
+
+
+@pytest.fixture(scope="module")
+def ia(torch_mod):
+    from paper_2511_21513_amd import binding
+
+    ctx = binding.IntAttn(device=0)
+    yield ctx
+    ctx.close()
+
+
+def gpu_forward(torch, ia, p, s_o=None, taps=False):
+    dev = torch.device("cuda:0")
+    q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
+    r = ia.forward(q, k, v, p.s_q, p.s_k, p.s_v, s_o, causal=p.causal, per_head=p.per_head, taps=taps)
+    torch.cuda.synchronize()
+    if taps:
+        return {k_: v_.cpu().numpy() for k_, v_ in r.items()}
+    return {"out": r.cpu().numpy()}
+
+
+def check_full(torch, ia, oracle, p, s_o=None, taps=True, threads=16):
+    got = gpu_forward(torch, ia, p, s_o, taps=taps)
+    want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, s_o, causal=p.causal, per_head=p.per_head,
+                          taps=taps, threads=threads)
+    if taps:
+        for key in ("row_max", "row_sum", "acc"):
+            bad = int((got[key] != want[key]).sum())
+            assert bad == 0, f"{p.name}: {bad} mismatching {key} entries"
+    bad = int((got["out"] != want["out"]).sum())
+    assert bad == 0, f"{p.name}: {bad} mismatching output bytes of {want['out'].size}"
+    return got
+
+
+SHAPES = [
+    # B, Hq, Hkv, L, d, causal, per_head
+    (1, 1, 1, 1, 64, False, False),
+    (1, 1, 1, 1, 128, True, False),
+    (2, 2, 1, 31, 64, True, False),
+    (1, 2, 2, 32, 128, False, False),
+    (1, 3, 3, 33, 64, False, False),
+    (2, 4, 2, 97, 128, True, True),
+    (1, 2, 1, 128, 64, True, False),
+    (1, 2, 2, 129, 128, False, True),
+    (1, 4, 1, 197, 64, False, False),
+    (1, 2, 2, 300, 128, True, False),
+    (1, 1, 1, 515, 64, True, False),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "B{}Hq{}Hkv{}L{}d{}c{}ph{}".format(*[int(x) for x in s]))
+def test_small_shapes_bit_exact(torch_mod, ia, oracle, shape):
+    B, Hq, Hkv, L, d, causal, per_head = shape
+    print(f"case {shape}", flush=True)
+    p = inputs.random_problem(100 + L + d, B, Hq, Hkv, L, d, causal, per_head=per_head, spread=1.5)
+    check_full(torch_mod, ia, oracle, p)
+    s_o = inputs.calibrated_out_scale(p)
+    check_full(torch_mod, ia, oracle, p, s_o)
+
+
+@pytest.mark.parametrize("scale", [0.5, 0.05, 0.004, 0.0005])
+def test_clip_threshold_range_bit_exact(torch_mod, ia, oracle, scale):
+    """Thresholds from a handful (coarse index steps) to far beyond the multiply-shift's reach
+    (the kernel's dividing path)."""
+    p = inputs.random_problem(7, 1, 2, 2, 160, 64, True)
+    p.s_q = np.asarray([scale], dtype=np.float32)
+    p.s_k = np.asarray([scale], dtype=np.float32)
+    print("c_int", oracle.c_int(6.6, p.s_q[0], p.s_k[0], 64), flush=True)
+    check_full(torch_mod, ia, oracle, p)
+
+
+def test_adversarial_rows_bit_exact(torch_mod, ia, oracle):
+    """Zero queries (all logits equal: P = round(255/n), zero beyond n = 510), a dominant key
+    (one-hot rows, P = 255 >= 128 exercises the unsigned-probability path), extreme int8
+    values including -128, and saturating outputs."""
+    rng = np.random.default_rng(5)
+    L, d = 640, 64
+    q = rng.integers(-128, 128, size=(1, 4, L, d)).astype(np.int8)
+    k = rng.integers(-128, 128, size=(1, 2, L, d)).astype(np.int8)
+    v = rng.integers(-128, 128, size=(1, 2, L, d)).astype(np.int8)
+    q[0, 0] = 0                # equal logits
+    k[0, 0, 17] = 127
+    q[0, 1] = 127              # key 17 dominates head 1 (KV head 0)
+    q[0, 2, ::2] = -128
+    k[0, 1, ::3] = -128
+    v[0, 1, ::5] = -128
+    for causal in (False, True):
+        p = inputs.Problem("adversarial", 1, 4, 2, L, d, causal, False, q, k, v,
+                           np.asarray([0.02], np.float32), np.asarray([0.03], np.float32), np.asarray([0.05], np.float32))
+        got = check_full(torch_mod, ia, oracle, p)
+        assert not got["out"][0, 0, 600 if not causal else 639].any()
+        check_full(torch_mod, ia, oracle, p, np.asarray([0.002], np.float32))  # saturates at +-127
+
+
+def test_strided_views_bit_exact(torch_mod, ia, oracle):
+    """Tensors laid out [B, L, H, d] in memory (a transposed view) must give the same bytes."""
+    torch = torch_mod
+    p = inputs.random_problem(9, 2, 4, 2, 150, 64, True)
+    dev = torch.device("cuda:0")
+    mk = lambda x: torch.from_numpy(np.ascontiguousarray(x.transpose(0, 2, 1, 3))).to(dev).permute(0, 2, 1, 3)
+    q, k, v = mk(p.q), mk(p.k), mk(p.v)
+    out = torch.empty((2, 150, 4, 64), dtype=torch.int8, device=dev).permute(0, 2, 1, 3)
+    ia.forward(q, k, v, p.s_q, p.s_k, p.s_v, causal=True, out=out)
+    torch.cuda.synchronize()
+    want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, causal=True)["out"]
+    assert int((out.cpu().numpy() != want).sum()) == 0
+
+
+def test_config1_single_head(torch_mod, ia, oracle):
+    p = inputs.make_problem("c1_single_head")
+    check_full(torch_mod, ia, oracle, p)
+    check_full(torch_mod, ia, oracle, p, inputs.calibrated_out_scale(p))
+
+
+def test_config2_vit(torch_mod, ia, oracle):
+    p = inputs.make_problem("c2_vit_b16")
+    check_full(torch_mod, ia, oracle, p)
+    check_full(torch_mod, ia, oracle, p, inputs.calibrated_out_scale(p), taps=False)
+
+
+def test_config3_llm_prefill_2k(torch_mod, ia, oracle):
+    p = inputs.make_problem("c3_llm_prefill_2k")
+    check_full(torch_mod, ia, oracle, p)
+    check_full(torch_mod, ia, oracle, p, inputs.calibrated_out_scale(p), taps=False)
+
+
+def check_sampled(torch, ia, oracle, p, s_o, heads, n_rows, seed):
+    """Full-size problem in the benchmark's launch configuration; the oracle recomputes sampled
+    query rows one by one (always including the first and last rows and a tile boundary)."""
+    dev = torch.device("cuda:0")
+    q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
+    out = ia.forward(q, k, v, p.s_q, p.s_k, p.s_v, s_o, causal=p.causal, per_head=p.per_head)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(seed)
+    for (b, h) in heads:
+        rows = np.unique(np.concatenate([[0, 1, 127, 128, p.L - 1, p.L - 129], rng.integers(0, p.L, n_rows)])).astype(np.int32)
+        want = oracle.rows(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, s_o, b=b, hq=h, rows=rows, causal=p.causal,
+                           per_head=p.per_head)
+        got = out[b, h].cpu().numpy()[rows]
+        bad = int((got != want["out"]).sum())
+        assert bad == 0, f"{p.name} b={b} h={h}: {bad} mismatching bytes on sampled rows"
+    return out
+
+
+def test_config4_gqa_prefill_8k_sampled(torch_mod, ia, oracle):
+    p = inputs.make_problem("c4_gqa_prefill_8k")
+    s_o = inputs.calibrated_out_scale(p, sample_rows=16)
+    heads = [(0, 0), (0, 5), (0, 17), (0, 31)]
+    out = check_sampled(torch_mod, ia, oracle, p, s_o, heads, 24, 4)
+    assert int(out.abs().max()) > 20  # the calibrated scale makes the bytes informative
+    check_sampled(torch_mod, ia, oracle, p, None, heads[:2], 8, 5)
+
+
+def test_config5_batched_prefill_4k_sampled(torch_mod, ia, oracle):
+    p = inputs.make_problem("c5_batched_prefill_4k")
+    s_o = inputs.calibrated_out_scale(p, sample_rows=8)
+    heads = [(0, 0), (3, 7), (9, 30), (15, 31)]
+    check_sampled(torch_mod, ia, oracle, p, s_o, heads, 16, 6)

@@ -1,0 +1,149 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused integer attention path on one MI355X.
+
+A step is one pass of the whole hot path (INT8 Q.K^T, IndexSoftmax, UINT8 P times INT8 V,
+INT8 requantization) over one batch of synthetic input already resident in HBM.  The default
+workload is the configuration the headline metric is quoted on: long-context causal prefill
+with grouped-query attention, B=1, 32 query heads over 8 KV heads, L=8192, d=128.
+
+Prints ONE JSON line.  `value` is int8 attention TOPS counting the two contractions only
+(4*d*pairs*B*Hq operations, pairs = L(L+1)/2 under the causal mask); recomputation sweeps and
+masked halves of diagonal tiles are executed but not counted.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0  # MI355X dense int8 matrix peak, 5.0 POP/s
+HBM_PEAK_GBS = 8000.0
+
+ALIASES = {"c1": "c1_single_head", "c2": "c2_vit_b16", "c3": "c3_llm_prefill_2k",
+           "c4": "c4_gqa_prefill_8k", "c5": "c5_batched_prefill_4k"}
+
+
+def cpu_baseline(p, budget_heads):
+    """The oracle as it stands on this host's cores, over whole heads of the same workload."""
+    import oracle
+
+    threads = min(16, os.cpu_count() or 1)
+    n_heads = min(p.B * p.Hq, budget_heads)
+    # one batch entry's first n_heads query heads (with their KV heads), all rows
+    t0 = time.perf_counter()
+    import numpy as np
+
+    b_cnt = (n_heads + p.Hq - 1) // p.Hq
+    hq_cnt = min(n_heads, p.Hq)
+    g = p.Hq // p.Hkv
+    kv_cnt = (hq_cnt + g - 1) // g
+    q = np.ascontiguousarray(p.q[:b_cnt, :hq_cnt])
+    k = np.ascontiguousarray(p.k[:b_cnt, :kv_cnt])
+    v = np.ascontiguousarray(p.v[:b_cnt, :kv_cnt])
+    sq = p.s_q[:hq_cnt] if p.per_head else p.s_q
+    sk = p.s_k[:kv_cnt] if p.per_head else p.s_k
+    sv = p.s_v[:kv_cnt] if p.per_head else p.s_v
+    if hq_cnt % kv_cnt != 0:  # keep the group structure intact
+        return None
+    t0 = time.perf_counter()
+    oracle.forward(q, k, v, sq, sk, sv, None, causal=p.causal, per_head=p.per_head, threads=threads)
+    dt = time.perf_counter() - t0
+    ops = 4 * p.d * p.pairs * b_cnt * hq_cnt
+    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": min(threads, b_cnt * hq_cnt), "kind": "oracle",
+            "sample": f"{b_cnt * hq_cnt} of {p.B * p.Hq} (batch, head) pairs, all rows, {dt:.1f} s",
+            "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c4")
+    ap.add_argument("--variant", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-comparator", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=8)
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (heads are independent; nothing is sharded "
+              "or exchanged); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2511_21513_amd import binding, inputs
+
+    name = ALIASES.get(a.workload, a.workload)
+    p = inputs.make_problem(name)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    ia = binding.IntAttn(device=0, variant=a.variant)
+    q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
+    out = torch.empty_like(q)
+    s_o = inputs.calibrated_out_scale(p, sample_rows=16)
+    args, keep = ia.make_args(q, k, v, out, p.s_q, p.s_k, p.s_v, s_o, causal=p.causal, per_head=p.per_head)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(steps):
+            fn()
+        ev1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        return ev0.elapsed_time(ev1) / steps, wall_ms
+
+    ms, wall_ms = timed(lambda: ia.forward_args(args, stream), a.steps, a.warmup)
+    tops = p.ops / (ms * 1e-3) / 1e12
+
+    # sampled parity against the oracle on the benchmarked launch
+    import oracle
+
+    rows = np.asarray([0, 1, p.L // 2, p.L - 1], dtype=np.int32)
+    want = oracle.rows(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, s_o, b=p.B - 1, hq=p.Hq - 1, rows=rows, causal=p.causal,
+                       per_head=p.per_head)["out"]
+    mism = int((out[p.B - 1, p.Hq - 1].cpu().numpy()[rows] != want).sum())
+
+    res = {
+        "metric": "int8 attention TOPS (QK^T+PV) + % of int8 MFMA peak at L=8192",
+        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": name, "B": p.B, "Hq": p.Hq, "Hkv": p.Hkv, "L": p.L, "d": p.d,
+                   "causal": p.causal, "scales": "per-head" if p.per_head else "per-tensor",
+                   "lut_bits": 5, "clip": 6.6, "variant": a.variant},
+        "pct_of_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
+        "wall_ms_per_step": wall_ms,
+        "sampled_parity_mismatching_bytes": mism,
+        "roofline": {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": tops / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                     "kernel": "fwd_kernel", "counted_ops_per_launch": p.ops,
+                     "hbm_algorithmic_bytes_per_launch": p.algorithmic_bytes,
+                     "hbm_algorithmic_GBps": p.algorithmic_bytes / (ms * 1e-3) / 1e9},
+    }
+    if not a.no_comparator:
+        try:
+            cms, _ = timed(lambda: ia.forward_args(args, stream, quantonly=True), max(3, a.steps // 3), 2)
+            res["comparator"] = {"kind": "fused conventional INT8 pipeline (dequant -> fp32 softmax -> requant)",
+                                 "ms_per_step": cms, "speedup_of_intattention": cms / ms}
+        except binding.IntAttnError as e:
+            res["comparator"] = {"error": str(e)}
+    if not a.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(p, a.cpu_heads)
+    ia.close()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -107,9 +107,13 @@ INTATTN_API int intattn_derive_params(const intattn_ctx *ctx, float s_q, float s
                           int32_t d, int64_t *c_int, int32_t *rq_mult, int32_t *rq_shift);
 
 /* Host-only, exposed for tests: how the kernels evaluate the index map of Sec. 3.1,
- * idx = round(x * (2^b - 1) / c_int) for x in [0, c_int], without dividing.  mode 1:
- * idx = (x * mul + add) >> shift in 32-bit unsigned arithmetic, proven equal to the exact
- * quotient on the whole range; mode 0: no such constants exist, the kernel divides. */
+ * idx = round(x * (2^b - 1) / c_int) for x in [0, c_int], without dividing.  On entry *mode
+ * names the scheme asked for; on return it is that scheme, or 0 if no constants exist for it
+ * (the kernels then divide).  Both schemes are proven equal to the exact quotient on the
+ * whole range before they are returned.
+ *   mode 1: idx = (x * mul + add) >> shift                 (32-bit sum, 24-bit factors)
+ *   mode 2: idx = (((x << shift) + add) * mul) >> 32       (48-bit product of 24-bit factors)
+ *   mode 3: idx = trunc(fma(x, r, 0.5)) in IEEE fp32, *mul = the bits of r; add = shift = 0 */
 INTATTN_API int intattn_derive_index_map(const intattn_ctx *ctx, int64_t c_int, int32_t *mode, uint32_t *mul,
                                          uint32_t *add, int32_t *shift);
 

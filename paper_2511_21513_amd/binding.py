@@ -148,8 +148,8 @@ class IntAttn:
             raise IntAttnError(rc, "intattn_derive_params")
         return int(c.value), int(m.value), int(sh.value)
 
-    def derive_index_map(self, c_int: int):
-        mode, sh = ctypes.c_int32(0), ctypes.c_int32(0)
+    def derive_index_map(self, c_int: int, mode: int = 2):
+        mode, sh = ctypes.c_int32(mode), ctypes.c_int32(0)
         mul, add = ctypes.c_uint32(0), ctypes.c_uint32(0)
         rc = self._lib.intattn_derive_index_map(
             self._ctx, c_int, ctypes.byref(mode), ctypes.byref(mul), ctypes.byref(add), ctypes.byref(sh)

@@ -99,13 +99,11 @@ bool derive_requant(float s_v, float s_o, int32_t *mult, int32_t *shift)
 
 uint32_t true_index(uint64_t dclip, uint64_t c_int, uint64_t top) { return (uint32_t)((2 * top * dclip + c_int) / (2 * c_int)); }
 
-// Finds (mul, add, shift) with ((x * mul + add) >> shift) == round(x * top / c_int) for every
-// integer x in [0, c_int], using 24-bit operands and a 32-bit sum.  Both sides are monotone
-// step functions of x, so agreement at x = 0, x = c_int and on both sides of every true
-// step proves agreement everywhere.
-bool find_mad24(uint32_t c_int, uint32_t top, HeadParams *hp)
+// Check points for a candidate index map: both the exact map and every candidate are
+// monotone step functions of x, so agreement at x = 0, x = c_int and on both sides of every
+// true step proves agreement on the whole range [0, c_int].
+std::vector<uint32_t> check_points(uint32_t c_int, uint32_t top)
 {
-    if (c_int >= (1u << 24)) return false;
     std::vector<uint32_t> pts;
     pts.push_back(0);
     pts.push_back(c_int);
@@ -118,13 +116,23 @@ bool find_mad24(uint32_t c_int, uint32_t top, HeadParams *hp)
             if (t > 0) pts.push_back((uint32_t)(t - 1));
         }
     }
+    return pts;
+}
+
+// Finds (mul, add, shift) with ((x * mul + add) >> shift) == round(x * top / c_int) for every
+// integer x in [0, c_int], with signed 24-bit factors and a sum below 2^31.
+// Stored for the kernel as idx_mul = -mul (the kernel multiplies t = -x), idx_add = add.
+bool find_mad24(uint32_t c_int, uint32_t top, HeadParams *hp)
+{
+    if (c_int >= (1u << 23)) return false;
+    const std::vector<uint32_t> pts = check_points(c_int, top);
     for (int s = 27; s >= 8; --s) {
         const uint64_t num = (uint64_t)top << s;
         const uint64_t cands[2] = {(num + c_int - 1) / c_int, num / c_int};
         for (uint64_t mul : cands) {
-            if (mul == 0 || mul >= (1ull << 24)) continue;
+            if (mul == 0 || mul >= (1ull << 23)) continue;
             const uint64_t add = 1ull << (s - 1);
-            if ((uint64_t)c_int * mul + add >= (1ull << 32)) continue;
+            if ((uint64_t)c_int * mul + add >= (1ull << 31)) continue;
             bool ok = true;
             for (uint32_t x : pts) {
                 const uint32_t got = (uint32_t)(((uint64_t)x * mul + add) >> s);
@@ -134,11 +142,82 @@ bool find_mad24(uint32_t c_int, uint32_t top, HeadParams *hp)
                 }
             }
             if (ok) {
-                hp->idx_mul = (uint32_t)mul;
+                hp->idx_mul = (uint32_t)(-(int32_t)mul);
                 hp->idx_add = (uint32_t)add;
                 hp->idx_shift = s;
                 return true;
             }
+        }
+    }
+    return false;
+}
+
+// Finds (pre, off, mul) with ((((x << pre) + off) * mul) >> 32) == round(x * top / c_int) for
+// every integer x in [0, c_int], where (x << pre) + off and mul stay below 2^23 so that the
+// 48-bit product of two signed 24-bit factors is exact.  mul ~ top * 2^(32-pre) / c_int and
+// off ~ 2^31 / mul (half an index step).
+// Stored for the kernel as idx_mul = -mul, idx_add = -off (it works on t = -x), idx_shift = pre.
+bool find_mulhi24(uint32_t c_int, uint32_t top, HeadParams *hp)
+{
+    const std::vector<uint32_t> pts = check_points(c_int, top);
+    for (int pre = 0; pre <= 22; ++pre) {
+        if (((uint64_t)c_int << pre) >= (1ull << 23)) break;
+        const long double ideal = (long double)top * 4294967296.0L / ((long double)c_int * (long double)(1ull << pre));
+        if (ideal >= 8388607.0L) continue; // multiplier too wide: shift x further left
+        if (ideal < 1024.0L) break;
+        const int64_t m0 = (int64_t)ideal;
+        for (int64_t dm = 0; dm <= 16; ++dm) {
+            for (int sgn = 0; sgn < 2; ++sgn) {
+                const int64_t mul = sgn ? m0 - dm : m0 + 1 + dm;
+                if (mul < 1 || mul >= (1ll << 23)) continue;
+                // every check point x with exact index k confines off to
+                //   k*2^32 <= ((x << pre) + off) * mul < (k+1)*2^32
+                int64_t lo = 0, hi = (1ll << 23) - 1 - ((int64_t)c_int << pre);
+                for (uint32_t x : pts) {
+                    const int64_t k = (int64_t)true_index(x, c_int, top);
+                    const int64_t xs = (int64_t)x << pre;
+                    const int64_t need_lo = (k * 4294967296LL + mul - 1) / mul - xs;
+                    const int64_t need_hi = ((k + 1) * 4294967296LL - 1) / mul - xs;
+                    if (need_lo > lo) lo = need_lo;
+                    if (need_hi < hi) hi = need_hi;
+                    if (lo > hi) break;
+                }
+                if (lo > hi) continue;
+                const int64_t off = lo + (hi - lo) / 2;
+                hp->idx_mul = (uint32_t)(-(int32_t)mul);
+                hp->idx_add = (uint32_t)(-(int32_t)off);
+                hp->idx_shift = pre;
+                return true;
+            }
+        }
+    }
+    return false;
+}
+
+// Finds an fp32 factor r ~ top / c_int with trunc(fma(-x, -r, 0.5)) == round(x * top / c_int)
+// for every integer x in [0, c_int] (c_int < 2^24 so that x is exact in fp32).  The check runs
+// the same IEEE single-precision fma the kernel runs.  Stored as idx_mul = bits of -r.
+bool find_fp32(uint32_t c_int, uint32_t top, HeadParams *hp)
+{
+    if (c_int >= (1u << 24)) return false;
+    const std::vector<uint32_t> pts = check_points(c_int, top);
+    float r = (float)((double)top / (double)c_int);
+    r = std::nextafterf(r, 0.0f);
+    for (int step = 0; step < 3; ++step, r = std::nextafterf(r, 1e30f)) {
+        bool ok = true;
+        for (uint32_t x : pts) {
+            const float y = std::fmaf(-(float)x, -r, 0.5f);
+            if ((uint32_t)(int)y != true_index(x, c_int, top)) {
+                ok = false;
+                break;
+            }
+        }
+        if (ok) {
+            const float negr = -r;
+            std::memcpy(&hp->idx_mul, &negr, 4);
+            hp->idx_add = 0;
+            hp->idx_shift = 0;
+            return true;
         }
     }
     return false;
@@ -193,7 +272,13 @@ int derive_all(intattn_ctx *ctx, const intattn_args *a, Derived *out)
     out->hp.assign((size_t)n, HeadParams{});
     out->alpha.assign((size_t)n, 0.f);
     out->svso.assign((size_t)n, 0.f);
-    out->idx_mode = IDX_MAD24;
+    // candidate index-map schemes in order of preference; a launch uses one scheme for all heads
+    typedef bool (*finder)(uint32_t, uint32_t, HeadParams *);
+    const finder finders[3] = {find_mulhi24, find_mad24, find_fp32};
+    const int modes[3] = {IDX_MULHI24, IDX_MAD24, IDX_FP32};
+    bool all_ok[3] = {true, true, true};
+    std::vector<HeadParams> cand[3];
+    for (auto &c : cand) c.assign((size_t)n, HeadParams{});
     for (int h = 0; h < n; ++h) {
         const int kv = a->scale_mode ? h / g : 0;
         const float sq = a->scale_q[h], sk = a->scale_k[kv], sv = a->scale_v[kv];
@@ -204,9 +289,20 @@ int derive_all(intattn_ctx *ctx, const intattn_args *a, Derived *out)
         hp.c_int = (int32_t)derive_c_int(ctx->clip, sq, sk, a->d);
         if (!derive_requant(sv, so, &hp.rq_mult, &hp.rq_shift))
             return fail(ctx, INTATTN_ERR_INVALID_ARG, "s_V / (255 s_O) is outside the representable range");
-        if (!find_mad24((uint32_t)hp.c_int, top, &hp)) out->idx_mode = IDX_DIV;
+        for (int m = 0; m < 3; ++m) {
+            cand[m][(size_t)h] = hp;
+            if (all_ok[m] && !finders[m]((uint32_t)hp.c_int, top, &cand[m][(size_t)h])) all_ok[m] = false;
+        }
         out->alpha[(size_t)h] = (float)(((double)sq * (double)sk) / std::sqrt((double)a->d));
         out->svso[(size_t)h] = (float)((double)sv / (double)so);
+    }
+    out->idx_mode = IDX_DIV;
+    for (int m = 0; m < 3; ++m) {
+        if (all_ok[m]) {
+            out->idx_mode = modes[m];
+            out->hp = cand[m];
+            break;
+        }
     }
     return INTATTN_OK;
 }
@@ -370,9 +466,22 @@ int intattn_derive_index_map(const intattn_ctx *ctx, int64_t c_int, int32_t *mod
     if (!ctx || c_int < 1 || c_int > 1073741824LL || !mode || !mul || !add || !shift) return INTATTN_ERR_INVALID_ARG;
     HeadParams hp{};
     const uint32_t top = (1u << ctx->lut_bits) - 1u;
-    *mode = find_mad24((uint32_t)c_int, top, &hp) ? IDX_MAD24 : IDX_DIV;
-    *mul = hp.idx_mul;
-    *add = hp.idx_add;
+    if (*mode == IDX_MAD24) {
+        *mode = find_mad24((uint32_t)c_int, top, &hp) ? IDX_MAD24 : IDX_DIV;
+    } else if (*mode == IDX_FP32) {
+        *mode = find_fp32((uint32_t)c_int, top, &hp) ? IDX_FP32 : IDX_DIV;
+    } else {
+        *mode = find_mulhi24((uint32_t)c_int, top, &hp) ? IDX_MULHI24 : IDX_DIV;
+    }
+    // report the mathematical constants (the kernel-side fields hold them negated)
+    if (*mode == IDX_FP32) {
+        *mul = hp.idx_mul ^ 0x80000000u; // bits of +r
+        *add = 0;
+        *shift = 0;
+        return INTATTN_OK;
+    }
+    *mul = *mode == IDX_DIV ? 0u : (uint32_t)(-(int32_t)hp.idx_mul);
+    *add = *mode == IDX_MULHI24 ? (uint32_t)(-(int32_t)hp.idx_add) : hp.idx_add;
     *shift = hp.idx_shift;
     return INTATTN_OK;
 }

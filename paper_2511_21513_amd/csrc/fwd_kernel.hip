@@ -1,12 +1,13 @@
 // Fused IntAttention forward for gfx950 (MI355X).
 //
-// One workgroup = 4 wavefronts = 128 query rows of one (batch, query head); each wavefront
-// owns 32 query rows.  Keys/values stream through LDS in tiles of 32 keys.  Because
-// IndexSoftmax (Sec. 3.1-3.2) needs the exact row maximum before any table index and the
-// exact row sum before any probability, the key axis is swept three times, recomputing the
-// INT8 score tile each time instead of ever storing the L x L matrix:
+// One workgroup = 4 wavefronts; each wavefront owns RB blocks of 32 query rows of one
+// (batch, query head).  Keys/values stream through LDS in tiles of BK keys, double
+// buffered, one barrier per tile.  Because IndexSoftmax (Sec. 3.1-3.2) needs the exact row
+// maximum before any table index and the exact row sum before any probability, the key axis
+// is swept three times, recomputing the INT8 score tile each time instead of ever storing
+// the L x L matrix:
 //   sweep A: S^T = K.Q^T (MFMA)            -> running row max
-//   sweep B: S^T - max (MFMA accumulator starts at -max) -> clip, index, LUT_hat -> row sum
+//   sweep B: S^T - max (the MFMA accumulator starts at -max) -> clip, index, LUT_hat -> row sum;
 //            then the 2^b distinct probabilities of the row, P_hat = round(255 E/S), go to a
 //            per-row table in LDS
 //   sweep C: S^T again -> index -> per-row table -> 16 probability bytes per lane, which
@@ -17,7 +18,13 @@
 // The int8 MFMA is signed x signed while P_hat is unsigned (0..255).  The kernel feeds
 // P_hat - 128 and adds 128 * (column sums of the V rows of every processed tile) at the end;
 // hidden keys inside a processed tile carry P_hat = 0, i.e. the byte -128, so the correction
-// is the plain column sum.  All intermediate magnitudes stay below 2^31 for L < 131072.
+// is the plain column sum, which one extra MFMA per tile against an all-ones operand
+// produces.  All intermediate magnitudes stay below 2^31 for L < 131072.
+//
+// LDS tiles are row-major [key][d] with the 16-byte chunks of each row XOR-swizzled so that
+// both access patterns are bank-conflict free: K fragments are read with 128-bit loads
+// (one key row per lane), V^T fragments with the transposing 64-bit load (eight key rows per
+// 16 lanes).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -25,6 +32,7 @@
 
 namespace intattn {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
@@ -32,34 +40,56 @@ namespace {
 
 constexpr int WAVES = 4;
 constexpr int NT = WAVES * 64;
-constexpr int BQ = WAVES * 32; // query rows per workgroup
-constexpr int BK = 32;         // keys per tile
 
+// ------------------------------------------------------------------ index map (Sec. 3.1)
+// t = -min(Delta, c_int) in [-c_int, 0]; returns round(-t * top / c_int).
 template <int MODE>
-__device__ __forceinline__ uint32_t index_map(uint32_t dclip, const HeadParams &hp, uint32_t top)
+__device__ __forceinline__ uint32_t index_map(int t, const HeadParams &hp, uint32_t top)
 {
     if (MODE == IDX_MAD24) {
-        return (__umul24(dclip, hp.idx_mul) + hp.idx_add) >> hp.idx_shift;
+        // (-t) * mul + add, 24-bit signed operands (idx_mul holds -mul)
+        return (uint32_t)(__mul24(t, (int)hp.idx_mul) + (int)hp.idx_add) >> hp.idx_shift;
+    } else if (MODE == IDX_MULHI24) {
+        // high word of ((t << pre) - off) * (-mul): both factors negative 24-bit values
+        const int x = (int)(((uint32_t)t << hp.idx_shift) + hp.idx_add); // idx_add holds -off
+        return (uint32_t)(int)(((int64_t)((x << 8) >> 8) * (int64_t)(((int)hp.idx_mul << 8) >> 8)) >> 32);
+    } else if (MODE == IDX_FP32) {
+        // trunc(fma(t, -(top/c_int), 0.5)): t is exact in fp32, one rounding in the fma; the host
+        // proved the result exact on the whole range with the same IEEE operations
+        return (uint32_t)(int)__builtin_fmaf((float)t, __uint_as_float(hp.idx_mul), 0.5f);
     } else {
         const uint64_t c = (uint64_t)(uint32_t)hp.c_int;
-        return (uint32_t)((2ull * top * dclip + c) / (2ull * c));
+        return (uint32_t)((2ull * top * (uint64_t)(uint32_t)(-t) + c) / (2ull * c));
     }
 }
 
-// Key index held in accumulator register i of a 32x32 MFMA result by a lane of half-wave h.
+// Key (within a 32-key block) held in accumulator register i of a 32x32 MFMA result by a
+// lane of half-wave h; the same key sits in byte i of that lane's next B operand.
 __device__ __forceinline__ int acc_key(int i, int h) { return 8 * (i >> 2) + 4 * h + (i & 3); }
 
-template <int D, bool CAUSAL, int MODE>
+// XOR swizzles of the 16-byte chunk index inside a key row.
+template <int D> __device__ __forceinline__ int swz_k(int key) { return D == 128 ? (key & 7) : ((key >> 1) & 3); }
+template <int D> __device__ __forceinline__ int swz_v(int key)
+{
+    return D == 128 ? ((key & 3) | (((key >> 3) & 1) << 2)) : (((key >> 1) & 1) | (((key >> 3) & 1) << 1));
+}
+
+template <int D, int RB, int KT, bool CAUSAL, int MODE>
 __global__ __launch_bounds__(NT) void fwd_kernel(const FwdParams p)
 {
-    constexpr int KB = D / 32; // 32-wide blocks of the head dimension
-    constexpr int CB = D / 32; // 32-wide blocks of output channels
+    constexpr int KB = D / 32;       // 32-wide blocks of the head dimension
+    constexpr int CB = D / 32;       // 32-wide blocks of output channels
+    constexpr int BK = 32 * KT;      // keys per tile
+    constexpr int BQ = WAVES * RB * 32;
+    constexpr int TILE = BK * D;     // bytes
+    constexpr int CPT = TILE / 16 / NT; // 16-byte chunks per thread per tile
+    static_assert(CPT >= 1 && CPT * 16 * NT == TILE, "tile must split evenly over the threads");
+    static_assert(CB <= WAVES, "one wave per channel block accumulates the V column sums");
 
-    __shared__ __attribute__((aligned(16))) int8_t Ks[BK * D];  // [KB][32 keys][32 B]
-    __shared__ __attribute__((aligned(16))) int8_t Vt[BK * D];  // [D channels][2 halves x 16 B]
-    __shared__ uint32_t PT[WAVES][32 * 32];                      // [idx][row] per wave
+    __shared__ __attribute__((aligned(16))) int8_t Ks[2][TILE];
+    __shared__ __attribute__((aligned(16))) int8_t Vs[2][TILE];
+    __shared__ uint32_t PT[WAVES][RB][32 * 32]; // [idx][row] per wave and row block
     __shared__ uint32_t lut_lds[8];
-    __shared__ int32_t cs_part[8][D];
     __shared__ int32_t colsum[D];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
@@ -70,207 +100,276 @@ __global__ __launch_bounds__(NT) void fwd_kernel(const FwdParams p)
     const HeadParams hp = p.hp_table ? p.hp_table[hq] : p.hp0;
     const int L = p.L;
     const uint32_t top = (uint32_t)p.top;
-    const uint32_t c_int = (uint32_t)hp.c_int;
+    const int negc = -hp.c_int;
 
-    const int q0 = qt * BQ, qw0 = q0 + wave * 32, row = qw0 + n;
+    const int q0 = qt * BQ, qw0 = q0 + wave * (RB * 32);
     const int8_t *Qp = p.q + (int64_t)b * p.qs[0] + (int64_t)hq * p.qs[1];
     const int8_t *Kp = p.k + (int64_t)b * p.ks[0] + (int64_t)kvh * p.ks[1];
     const int8_t *Vp = p.v + (int64_t)b * p.vs[0] + (int64_t)kvh * p.vs[1];
 
     if (tid < 8) lut_lds[tid] = p.lut[tid];
 
-    // Q fragment of this lane: row `row`, bytes [32 kb + 16 h, +16) of each 32-byte block.
-    v4i qf[KB];
+    // Q fragments: row block rb, row qw0 + 32 rb + n, bytes [32 kb + 16 h, +16).
+    v4i qf[RB][KB];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {
-        qf[kb] = v4i{0, 0, 0, 0};
-        if (row < L) qf[kb] = *(const v4i *)(Qp + (int64_t)row * p.qs[2] + kb * 32 + h * 16);
+    for (int rb = 0; rb < RB; ++rb) {
+        const int row = qw0 + 32 * rb + n;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            qf[rb][kb] = v4i{0, 0, 0, 0};
+            if (row < L) qf[rb][kb] = *(const v4i *)(Qp + (int64_t)row * p.qs[2] + kb * 32 + h * 16);
+        }
     }
 
     const int kmax = CAUSAL ? min(L, q0 + BQ) : L;
     const int ntiles = (kmax + BK - 1) / BK;
 
-    auto stage_k = [&](int t) {
-        for (int c = tid; c < BK * (D / 16); c += NT) {
-            const int key = c / (D / 16), ch = c % (D / 16);
+    // ---- staging: global -> registers (issued a tile ahead) -> swizzled LDS
+    v4i stage_k[CPT], stage_v[CPT];
+    auto load_tile = [&](const int8_t *base, int64_t stride, int t, v4i (&st)[CPT]) {
+#pragma unroll
+        for (int j = 0; j < CPT; ++j) {
+            const int c = tid + j * NT;
+            const int key = c / (D / 16), c16 = c % (D / 16);
             const int gk = t * BK + key;
-            v4i val = v4i{0, 0, 0, 0};
-            if (gk < L) val = *(const v4i *)(Kp + (int64_t)gk * p.ks[2] + ch * 16);
-            *(v4i *)(Ks + (ch >> 1) * 1024 + key * 32 + (ch & 1) * 16) = val;
+            st[j] = v4i{0, 0, 0, 0};
+            if (gk < L) st[j] = *(const v4i *)(base + (int64_t)gk * stride + c16 * 16);
+        }
+    };
+    auto store_k = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < CPT; ++j) {
+            const int c = tid + j * NT;
+            const int key = c / (D / 16), c16 = c % (D / 16);
+            *(v4i *)(Ks[buf] + key * D + ((c16 ^ swz_k<D>(key)) << 4)) = stage_k[j];
+        }
+    };
+    auto store_v = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < CPT; ++j) {
+            const int c = tid + j * NT;
+            const int key = c / (D / 16), c16 = c % (D / 16);
+            *(v4i *)(Vs[buf] + key * D + ((c16 ^ swz_v<D>(key)) << 4)) = stage_v[j];
         }
     };
 
-    auto qk_tile = [&](v16i s) {
+    // ---- S^T block for sub-tile st (32 keys) and row block rb
+    auto qk_block = [&](int buf, int st, int rb, v16i s) {
+        const int key = 32 * st + n;
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-            const v4i a = *(const v4i *)(Ks + kb * 1024 + n * 32 + h * 16);
-            s = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[kb], s, 0, 0, 0);
+            const v4i a = *(const v4i *)(Ks[buf] + key * D + (((2 * kb + h) ^ swz_k<D>(key)) << 4));
+            s = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[rb][kb], s, 0, 0, 0);
         }
         return s;
     };
+    // wave-uniform visibility of a 32-key block starting at klo for the 32 rows starting at r0
+    auto fully_hidden = [&](int klo, int r0) { return CAUSAL && klo > r0 + 31; };
+    auto needs_mask = [&](int klo, int r0) { return (klo + 32 > L) || (CAUSAL && klo + 31 > r0); };
+    auto visible = [&](int key, int row) { return key < L && (!CAUSAL || key <= row); };
 
-    // ---------------------------------------------------------------- sweep A: row max
-    int mx = INT32_MIN;
+    // ================================================================= sweep A: row max
+    int mx[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) mx[rb] = INT32_MIN;
+
+    load_tile(Kp, p.ks[2], 0, stage_k);
+    store_k(0);
+    __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
-        __syncthreads();
-        stage_k(t);
-        __syncthreads();
-        const int klo = t * BK;
-        if (CAUSAL && klo > qw0 + 31) continue; // wave-uniform: tile hidden from all 32 rows
-        v16i s = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-        s = qk_tile(s);
-        const bool need_mask = (klo + BK > L) || (CAUSAL && klo + BK - 1 > qw0);
-        if (need_mask) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) load_tile(Kp, p.ks[2], t + 1, stage_k);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int key = klo + acc_key(i, h);
-                const bool ok = key < L && (!CAUSAL || key <= row);
-                if (ok) mx = max(mx, s[i]);
-            }
-        } else {
+        for (int st = 0; st < KT; ++st) {
+            const int klo = t * BK + 32 * st;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) mx = max(mx, s[i]);
-        }
-    }
-    mx = max(mx, __shfl_xor(mx, 32));
-
-    // ---------------------------------------------------------------- sweep B: row sum of E_hat
-    const uint8_t *lut_b = (const uint8_t *)lut_lds;
-    uint32_t sum = 0;
-    {
-        v16i negm;
+            for (int rb = 0; rb < RB; ++rb) {
+                const int r0 = qw0 + 32 * rb, row = r0 + n;
+                if (fully_hidden(klo, r0)) continue;
+                v16i s = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                s = qk_block(buf, st, rb, s);
+                if (needs_mask(klo, r0)) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) negm[i] = -mx;
-        for (int t = 0; t < ntiles; ++t) {
-            __syncthreads();
-            stage_k(t);
-            __syncthreads();
-            const int klo = t * BK;
-            if (CAUSAL && klo > qw0 + 31) continue;
-            const v16i s = qk_tile(negm); // s[i] = A_hat - rowMax <= 0 for visible keys
-            const bool need_mask = (klo + BK > L) || (CAUSAL && klo + BK - 1 > qw0);
+                    for (int i = 0; i < 16; ++i)
+                        if (visible(klo + acc_key(i, h), row)) mx[rb] = max(mx[rb], s[i]);
+                } else {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                int nd = max(s[i], -(int)c_int);                // -min(Delta, c_int)
-                if (need_mask) nd = min(nd, 0);                 // hidden keys may exceed the max
-                const uint32_t idx = index_map<MODE>((uint32_t)(-nd), hp, top);
-                uint32_t e = lut_b[idx];
-                if (need_mask) {
-                    const int key = klo + acc_key(i, h);
-                    const bool ok = key < L && (!CAUSAL || key <= row);
-                    e = ok ? e : 0u;
+                    for (int i = 0; i < 16; i += 2) mx[rb] = max(max(s[i], s[i + 1]), mx[rb]);
                 }
-                sum += e;
             }
         }
+        if (t + 1 < ntiles) store_k(buf ^ 1);
+        __syncthreads();
     }
-    sum += __shfl_xor(sum, 32);
-    if (sum == 0) sum = 1; // only rows beyond L; never stored
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) mx[rb] = max(mx[rb], __shfl_xor(mx[rb], 32));
 
-    // per-row probability table: PT[idx] = round(255 * LUT_hat[idx] / sum) - 128 as a byte
-    {
-        uint32_t *pt = PT[wave];
+    // ================================================================= sweep B: row sum of E_hat
+    const uint8_t *lut_b = (const uint8_t *)lut_lds;
+    uint32_t sum[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) sum[rb] = 0;
+
+    load_tile(Kp, p.ks[2], 0, stage_k);
+    store_k(0);
+    __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) load_tile(Kp, p.ks[2], t + 1, stage_k);
+#pragma unroll
+        for (int st = 0; st < KT; ++st) {
+            const int klo = t * BK + 32 * st;
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                const int r0 = qw0 + 32 * rb, row = r0 + n;
+                if (fully_hidden(klo, r0)) continue;
+                v16i s;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[i] = -mx[rb];
+                s = qk_block(buf, st, rb, s); // s[i] = A_hat - rowMax <= 0 for visible keys
+                if (needs_mask(klo, r0)) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int tcl = min(max(s[i], negc), 0); // hidden keys may exceed the max
+                        const uint32_t e = lut_b[index_map<MODE>(tcl, hp, top)];
+                        sum[rb] += visible(klo + acc_key(i, h), row) ? e : 0u;
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sum[rb] += lut_b[index_map<MODE>(max(s[i], negc), hp, top)];
+                }
+            }
+        }
+        if (t + 1 < ntiles) store_k(buf ^ 1);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        sum[rb] += __shfl_xor(sum[rb], 32);
+        if (sum[rb] == 0) sum[rb] = 1; // only rows beyond L; never stored
+        // per-row probability table: PT[idx] = round(255 * LUT_hat[idx] / sum) - 128 as a byte
+        uint32_t *pt = PT[wave][rb];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int kidx = 16 * h + j;
             const uint32_t e = lut_b[kidx];
-            const uint32_t pr = (510u * e + sum) / (2u * sum);
+            const uint32_t pr = (510u * e + sum[rb]) / (2u * sum[rb]);
             pt[kidx * 32 + n] = (pr ^ 0x80u) & 0xffu;
         }
+        const int row = qw0 + 32 * rb + n;
+        if (p.dbg_row_max && h == 0 && row < L) p.dbg_row_max[(int64_t)bh * L + row] = mx[rb];
+        if (p.dbg_row_sum && h == 0 && row < L) p.dbg_row_sum[(int64_t)bh * L + row] = (int32_t)sum[rb];
     }
-    if (p.dbg_row_max && h == 0 && row < L) p.dbg_row_max[(int64_t)bh * L + row] = mx;
-    if (p.dbg_row_sum && h == 0 && row < L) p.dbg_row_sum[(int64_t)bh * L + row] = (int32_t)sum;
 
-    // ---------------------------------------------------------------- sweep C: P_hat and P_hat.V_hat
-    v16i o[CB];
+    // ================================================================= sweep C: P_hat and P_hat.V_hat
+    v16i o[RB][CB];
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) o[cb][i] = 0;
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[rb][cb][i] = 0;
+    v16i cs = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; // V column sums, channel block `wave`
+    const v4i ones = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    const v4i hidden_p = v4i{(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
 
-    int32_t cs[4] = {0, 0, 0, 0}; // column sums of V for this thread's 4 channels / key group
-    const int vG = tid / (D / 4), vcg = tid % (D / 4); // key group of 4, channel group of 4
-    const bool v_active = tid < 8 * (D / 4);
+    // transposing read: lanes 2j, 2j+1 of a 16-lane group point at the two 8-byte halves of key
+    // row j's 16 channels; lane i of the group receives channel i of the eight rows.
+    const int tr_i = lane & 15, tr_g = (lane >> 4) & 1;
+    auto vt_frag = [&](int buf, int st, int cb) {
+        v4i a;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int j = tr_i >> 1;
+            const int key = 32 * st + 8 * (2 * r + (j >> 2)) + 4 * h + (j & 3);
+            const int c16 = 2 * cb + tr_g;
+            const int8_t *ptr = Vs[buf] + key * D + ((c16 ^ swz_v<D>(key)) << 4) + 8 * (tr_i & 1);
+            const v2i x = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3))) *)ptr);
+            a[2 * r] = x[0];
+            a[2 * r + 1] = x[1];
+        }
+        return a;
+    };
 
-    {
-        v16i negm;
+    load_tile(Kp, p.ks[2], 0, stage_k);
+    load_tile(Vp, p.vs[2], 0, stage_v);
+    store_k(0);
+    store_v(0);
+    __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) {
+            load_tile(Kp, p.ks[2], t + 1, stage_k);
+            load_tile(Vp, p.vs[2], t + 1, stage_v);
+        }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) negm[i] = -mx;
-        const uint32_t *pt = PT[wave];
-        for (int t = 0; t < ntiles; ++t) {
-            __syncthreads();
-            stage_k(t);
-            if (v_active) {
-                // 4 keys x 4 channels -> transposed: one dword per channel holding 4 keys
-                uint32_t w[4];
+        for (int st = 0; st < KT; ++st) {
+            const int klo = t * BK + 32 * st;
+            v4i pf[RB];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int gk = t * BK + 4 * vG + r;
-                    w[r] = 0;
-                    if (gk < L) w[r] = *(const uint32_t *)(Vp + (int64_t)gk * p.vs[2] + 4 * vcg);
+            for (int rb = 0; rb < RB; ++rb) {
+                const int r0 = qw0 + 32 * rb, row = r0 + n;
+                if (fully_hidden(klo, r0)) {
+                    pf[rb] = hidden_p;
+                    continue;
                 }
-                const int slot_dw = 4 * (vG & 1) + (vG >> 1); // key 8g+4h+r -> byte 16h+4g+r
+                v16i s;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const uint32_t ov = ((w[0] >> (8 * c)) & 0xffu) | (((w[1] >> (8 * c)) & 0xffu) << 8) |
-                                        (((w[2] >> (8 * c)) & 0xffu) << 16) | (((w[3] >> (8 * c)) & 0xffu) << 24);
-                    *(uint32_t *)(Vt + (4 * vcg + c) * 32 + slot_dw * 4) = ov;
-                    cs[c] += (int)(int8_t)(ov & 0xff) + (int)(int8_t)((ov >> 8) & 0xff) +
-                             (int)(int8_t)((ov >> 16) & 0xff) + (int)(int8_t)(ov >> 24);
-                }
-            }
-            __syncthreads();
-            const int klo = t * BK;
-            v4i pf;
-            if (CAUSAL && klo > qw0 + 31) {
-                pf = v4i{(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
-            } else {
-                const v16i s = qk_tile(negm);
-                const bool need_mask = (klo + BK > L) || (CAUSAL && klo + BK - 1 > qw0);
+                for (int i = 0; i < 16; ++i) s[i] = -mx[rb];
+                s = qk_block(buf, st, rb, s);
+                const uint32_t *pt = PT[wave][rb] + n;
+                if (needs_mask(klo, r0)) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    uint32_t packed = 0;
+                    for (int g = 0; g < 4; ++g) {
+                        uint32_t packed = 0;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int i = 4 * g + r;
-                        int nd = max(s[i], -(int)c_int);
-                        if (need_mask) nd = min(nd, 0);
-                        const uint32_t idx = index_map<MODE>((uint32_t)(-nd), hp, top);
-                        uint32_t pb = pt[idx * 32 + n];
-                        if (need_mask) {
-                            const int key = klo + acc_key(i, h);
-                            const bool ok = key < L && (!CAUSAL || key <= row);
-                            pb = ok ? pb : 0x80u;
+                        for (int r = 0; r < 4; ++r) {
+                            const int i = 4 * g + r;
+                            const int tcl = min(max(s[i], negc), 0);
+                            uint32_t pb = pt[index_map<MODE>(tcl, hp, top) * 32];
+                            pb = visible(klo + acc_key(i, h), row) ? pb : 0x80u;
+                            packed |= pb << (8 * r);
                         }
-                        packed |= pb << (8 * r);
+                        pf[rb][g] = (int)packed;
                     }
-                    pf[g] = (int)packed;
+                } else {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        uint32_t packed = 0;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            packed |= pt[index_map<MODE>(max(s[4 * g + r], negc), hp, top) * 32] << (8 * r);
+                        pf[rb][g] = (int)packed;
+                    }
                 }
             }
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
-                const v4i a = *(const v4i *)(Vt + (cb * 32 + n) * 32 + h * 16);
-                o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pf, o[cb], 0, 0, 0);
+                const v4i a = vt_frag(buf, st, cb);
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+                    o[rb][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pf[rb], o[rb][cb], 0, 0, 0);
+                if (cb == wave) cs = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, ones, cs, 0, 0, 0);
             }
         }
+        if (t + 1 < ntiles) {
+            store_k(buf ^ 1);
+            store_v(buf ^ 1);
+        }
+        __syncthreads();
     }
 
-    // ---------------------------------------------------------------- epilogue
-    __syncthreads();
-    if (v_active) {
+    // ================================================================= epilogue
+    if (wave < CB && n == 0) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) cs_part[vG][4 * vcg + c] = cs[c];
-    }
-    __syncthreads();
-    if (tid < D) {
-        int32_t a = 0;
-#pragma unroll
-        for (int g = 0; g < 8; ++g) a += cs_part[g][tid];
-        colsum[tid] = a;
+        for (int i = 0; i < 16; ++i) colsum[32 * wave + acc_key(i, h)] = cs[i];
     }
     __syncthreads();
 
-    if (row < L) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int row = qw0 + 32 * rb + n;
+        if (row >= L) continue;
         int8_t *Op = p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)row * p.os[2];
         const int64_t half = 1ll << (hp.rq_shift - 1);
 #pragma unroll
@@ -281,7 +380,7 @@ __global__ __launch_bounds__(NT) void fwd_kernel(const FwdParams p)
                 uint32_t packed = 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int32_t acc = o[cb][4 * g + r] + 128 * colsum[ch0 + r];
+                    const int32_t acc = o[rb][cb][4 * g + r] + 128 * colsum[ch0 + r];
                     if (p.dbg_acc) p.dbg_acc[((int64_t)bh * L + row) * D + ch0 + r] = acc;
                     int64_t v = ((int64_t)acc * hp.rq_mult + half) >> hp.rq_shift;
                     v = v > 127 ? 127 : (v < -127 ? -127 : v);
@@ -293,27 +392,39 @@ __global__ __launch_bounds__(NT) void fwd_kernel(const FwdParams p)
     }
 }
 
-template <int D, bool CAUSAL>
+template <int D, int RB, int KT, bool CAUSAL>
 int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
 {
     const dim3 grid((unsigned)(p.n_qtiles * p.B * p.Hq)), block(NT);
     if (idx_mode == IDX_MAD24)
-        hipLaunchKernelGGL((fwd_kernel<D, CAUSAL, IDX_MAD24>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24>), grid, block, 0, st, p);
+    else if (idx_mode == IDX_MULHI24)
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MULHI24>), grid, block, 0, st, p);
+    else if (idx_mode == IDX_FP32)
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP32>), grid, block, 0, st, p);
     else
-        hipLaunchKernelGGL((fwd_kernel<D, CAUSAL, IDX_DIV>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_DIV>), grid, block, 0, st, p);
     return (int)hipGetLastError();
+}
+
+template <int RB, int KT>
+int launch_shape(const FwdParams &p, int d, int idx_mode, hipStream_t st)
+{
+    if (d == 64) return p.causal ? launch_mode<64, RB, KT, true>(p, idx_mode, st) : launch_mode<64, RB, KT, false>(p, idx_mode, st);
+    if (d == 128) return p.causal ? launch_mode<128, RB, KT, true>(p, idx_mode, st) : launch_mode<128, RB, KT, false>(p, idx_mode, st);
+    return (int)hipErrorInvalidValue;
 }
 
 } // namespace
 
-int fwd_rows_per_block(int /*variant*/) { return BQ; }
+// variant 0/1: 32 query rows per wave (128 per workgroup); variant 2: 64 per wave (256).
+int fwd_rows_per_block(int variant) { return variant == 2 ? 256 : 128; }
 
-int launch_fwd(const FwdParams &p, int d, int idx_mode, int /*variant*/, void *stream)
+int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    if (d == 64) return p.causal ? launch_mode<64, true>(p, idx_mode, st) : launch_mode<64, false>(p, idx_mode, st);
-    if (d == 128) return p.causal ? launch_mode<128, true>(p, idx_mode, st) : launch_mode<128, false>(p, idx_mode, st);
-    return (int)hipErrorInvalidValue;
+    if (variant == 2) return launch_shape<2, 2>(p, d, idx_mode, st);
+    return launch_shape<1, 2>(p, d, idx_mode, st);
 }
 
 } // namespace intattn

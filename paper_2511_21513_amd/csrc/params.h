@@ -10,7 +10,8 @@ namespace intattn {
 enum IdxMode : int32_t {
     IDX_DIV = 0,    // integer division, any c_int (slow, always exact)
     IDX_MAD24 = 1,  // (Delta' * mul + add) >> shift, 24-bit operands, 32-bit result
-    IDX_MULHI24 = 2 // high 32 bits of the 48-bit product ((Delta' << pre) + add) * mul
+    IDX_MULHI24 = 2,// high 32 bits of the 48-bit product ((Delta' << pre) + add) * mul
+    IDX_FP32 = 3    // trunc(fma(Delta', top/c_int, 0.5)) in IEEE fp32 (idx_mul holds the bits of -top/c_int)
 };
 
 // Per query head: everything the kernel needs that depends on the scales.

@@ -99,32 +99,52 @@ def test_other_table_sizes_agree_with_oracle(lib, oracle, bits):
     ia.close()
 
 
-def test_index_map_constants_are_exact(host_ctx, oracle):
+def apply_index_map(mode, mul, add, sh, x):
+    x = x.astype(np.uint64)
+    if mode == 1:
+        return (x * np.uint64(mul) + np.uint64(add)) >> np.uint64(sh)
+    if mode == 3:
+        r = np.array([mul], dtype=np.uint32).view(np.float32)[0]
+        # fp32 fma emulated exactly: the product of two fp32 values and 0.5 fit fp64 without rounding
+        y = (x.astype(np.float32).astype(np.float64) * np.float64(r) + 0.5).astype(np.float32)
+        return np.trunc(y).astype(np.uint64)
+    return (((x << np.uint64(sh)) + np.uint64(add)) * np.uint64(mul)) >> np.uint64(32)
+
+
+@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_index_map_constants_are_exact(host_ctx, oracle, mode):
     """The multiply-shift the kernels use instead of a division must equal the exact rounded
-    quotient for every clipped distance; checked exhaustively for a spread of thresholds."""
-    rng = np.random.default_rng(1)
-    cs = [1, 2, 3, 30, 31, 32, 61, 62, 63, 445, 1462, 5203, 6274, 8191, 8192] + [int(x) for x in rng.integers(1, 9000, 40)]
+    quotient for every clipped distance; checked exhaustively for a spread of thresholds, and
+    spot-checked against the oracle's own index map."""
+    rng = np.random.default_rng(mode)
+    cs = [1, 2, 3, 30, 31, 32, 61, 62, 63, 445, 1462, 5203, 6274, 8191, 8192, 28794, 55064, 100000]
+    cs += [int(x) for x in rng.integers(1, 9000, 30)] + [int(x) for x in rng.integers(9000, 130000, 10)]
     n_fast = 0
     for c in cs:
-        mode, mul, add, sh = host_ctx.derive_index_map(c)
-        if mode == 0:
+        got_mode, mul, add, sh = host_ctx.derive_index_map(c, mode)
+        if got_mode == 0:
             continue
+        assert got_mode == mode
         n_fast += 1
-        assert mul < 2**24 and c * mul + add < 2**32
+        if mode == 1:
+            assert mul < 2**23 and c * mul + add < 2**31
+        elif mode == 2:
+            assert mul < 2**23 and (c << sh) + add < 2**23
         x = np.arange(c + 1, dtype=np.uint64)
-        got = (x * np.uint64(mul) + np.uint64(add)) >> np.uint64(sh)
         want = (2 * 31 * x + c) // (2 * c)
-        np.testing.assert_array_equal(got, want)
+        np.testing.assert_array_equal(apply_index_map(mode, mul, add, sh, x), want)
         for xi in (0, c // 3, c):
             assert int(want[xi]) == oracle.index_map(int(xi), c, 5)
-    assert n_fast >= len(cs) // 2
-    # thresholds far beyond the multiply-shift's precision must fall back to division
-    for c in (28794, 55064, 10**6, 2**30):
-        mode, mul, add, sh = host_ctx.derive_index_map(c)
-        if mode == 1:
-            x = np.unique(np.concatenate([np.arange(0, min(c, 70000) + 1), rng.integers(0, c + 1, 50000)])).astype(np.uint64)
-            got = (x * np.uint64(mul) + np.uint64(add)) >> np.uint64(sh)
-            np.testing.assert_array_equal(got, (2 * 31 * x + c) // (2 * c))
+    if mode == 3:
+        assert n_fast == len(cs)  # the fp32 scheme covers every threshold of the list
+    else:
+        assert n_fast >= 35
+    # far beyond the schemes' precision the library must say so (mode 0), never return wrong constants
+    for c in (10**6, 2**24 + 1, 2**30):
+        got_mode, mul, add, sh = host_ctx.derive_index_map(c, mode)
+        if got_mode:
+            x = np.unique(np.concatenate([np.arange(0, 70001), rng.integers(0, c + 1, 50000)])).astype(np.uint64)
+            np.testing.assert_array_equal(apply_index_map(got_mode, mul, add, sh, x), (2 * 31 * x + c) // (2 * c))
 
 
 def test_forward_rejects_bad_arguments_without_a_gpu(host_ctx, lib):

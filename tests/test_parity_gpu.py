@@ -1,6 +1,8 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
 seeded inputs.  The whole pipeline is integer, so the bar is bit-exact: zero mismatching
 bytes in the INT8 output, and equal int32 row max / row sum / accumulator taps."""
+import functools
+
 import numpy as np
 import pytest
 
@@ -18,13 +20,19 @@ def torch_mod():
     return torch
 
 
-@pytest.fixture(scope="module")
-def ia(torch_mod):
+# kernel variants: 0 = automatic choice, 1 = 32 query rows per wave, 2 = 64 query rows per wave
+@pytest.fixture(scope="module", params=[0, 1, 2], ids=lambda v: f"variant{v}")
+def ia(torch_mod, request):
     from paper_2511_21513_amd import binding
 
-    ctx = binding.IntAttn(device=0)
+    ctx = binding.IntAttn(device=0, variant=request.param)
     yield ctx
     ctx.close()
+
+
+@functools.lru_cache(maxsize=2)
+def cached_problem(name):
+    return inputs.make_problem(name)
 
 
 def gpu_forward(torch, ia, p, s_o=None, taps=False):
@@ -161,7 +169,7 @@ def check_sampled(torch, ia, oracle, p, s_o, heads, n_rows, seed):
 
 
 def test_config4_gqa_prefill_8k_sampled(torch_mod, ia, oracle):
-    p = inputs.make_problem("c4_gqa_prefill_8k")
+    p = cached_problem("c4_gqa_prefill_8k")
     s_o = inputs.calibrated_out_scale(p, sample_rows=16)
     heads = [(0, 0), (0, 5), (0, 17), (0, 31)]
     out = check_sampled(torch_mod, ia, oracle, p, s_o, heads, 24, 4)
@@ -170,7 +178,7 @@ def test_config4_gqa_prefill_8k_sampled(torch_mod, ia, oracle):
 
 
 def test_config5_batched_prefill_4k_sampled(torch_mod, ia, oracle):
-    p = inputs.make_problem("c5_batched_prefill_4k")
+    p = cached_problem("c5_batched_prefill_4k")
     s_o = inputs.calibrated_out_scale(p, sample_rows=8)
     heads = [(0, 0), (3, 7), (9, 30), (15, 31)]
     check_sampled(torch_mod, ia, oracle, p, s_o, heads, 16, 6)

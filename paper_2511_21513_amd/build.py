@@ -13,6 +13,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",  # no packed-fp32 instructions
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",  # MFMA accumulators in VGPRs: no accvgpr copies around the ALU stage
     "-fvisibility=hidden", "-Wall", "-Wno-unused-command-line-argument",
 ]
 

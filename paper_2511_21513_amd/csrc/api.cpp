@@ -256,6 +256,7 @@ int validate(intattn_ctx *ctx, const intattn_args *a)
             if (s[i] < 0 || (s[i] & 15) != 0)
                 return fail(ctx, INTATTN_ERR_INVALID_ARG, "strides must be non-negative multiples of 16");
         if (s[2] < a->d) return fail(ctx, INTATTN_ERR_INVALID_ARG, "the L stride must be at least d");
+        if (s[2] > (1 << 24)) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "the L stride must not exceed 2^24 bytes");
     }
     const int64_t rows_per_block = fwd_rows_per_block(ctx->variant);
     const int64_t n_qtiles = (a->L + rows_per_block - 1) / rows_per_block;

@@ -18,8 +18,8 @@
 // The int8 MFMA is signed x signed while P_hat is unsigned (0..255).  The kernel feeds
 // P_hat - 128 and adds 128 * (column sums of the V rows of every processed tile) at the end;
 // hidden keys inside a processed tile carry P_hat = 0, i.e. the byte -128, so the correction
-// is the plain column sum, which one extra MFMA per tile against an all-ones operand
-// produces.  All intermediate magnitudes stay below 2^31 for L < 131072.
+// is the plain column sum, which one extra MFMA per 32 keys against an all-ones operand
+// produces (in sweep B, which has matrix-core slack).  All intermediate magnitudes stay below 2^31 for L < 131072.
 //
 // LDS tiles are row-major [key][d] with the 16-byte chunks of each row XOR-swizzled so that
 // both access patterns are bank-conflict free: K fragments are read with 128-bit loads
@@ -27,6 +27,8 @@
 // 16 lanes).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "params.h"
 
@@ -52,7 +54,11 @@ __device__ __forceinline__ uint32_t index_map(int t, const HeadParams &hp, uint3
     } else if (MODE == IDX_MULHI24) {
         // high word of ((t << pre) - off) * (-mul): both factors negative 24-bit values
         const int x = (int)(((uint32_t)t << hp.idx_shift) + hp.idx_add); // idx_add holds -off
-        return (uint32_t)(int)(((int64_t)((x << 8) >> 8) * (int64_t)(((int)hp.idx_mul << 8) >> 8)) >> 32);
+        int r;
+        // written as an instruction so that later address arithmetic is not folded back into a
+        // 64-bit product (which costs three more VALU operations per element)
+        asm("v_mul_hi_i32_i24 %0, %1, %2" : "=v"(r) : "v"(x), "v"((int)hp.idx_mul));
+        return (uint32_t)r;
     } else if (MODE == IDX_FP32) {
         // trunc(fma(t, -(top/c_int), 0.5)): t is exact in fp32, one rounding in the fma; the host
         // proved the result exact on the whole range with the same IEEE operations
@@ -75,15 +81,16 @@ template <int D> __device__ __forceinline__ int swz_v(int key)
 }
 
 template <int D, int RB, int KT, bool CAUSAL, int MODE>
-__global__ __launch_bounds__(NT) void fwd_kernel(const FwdParams p)
+__global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void fwd_kernel(const FwdParams p)
 {
     constexpr int KB = D / 32;       // 32-wide blocks of the head dimension
     constexpr int CB = D / 32;       // 32-wide blocks of output channels
     constexpr int BK = 32 * KT;      // keys per tile
     constexpr int BQ = WAVES * RB * 32;
     constexpr int TILE = BK * D;     // bytes
-    constexpr int CPT = TILE / 16 / NT; // 16-byte chunks per thread per tile
-    static_assert(CPT >= 1 && CPT * 16 * NT == TILE, "tile must split evenly over the threads");
+    constexpr int NCHUNK = TILE / 16;                // 16-byte chunks per tile
+    constexpr int CPT = (NCHUNK + NT - 1) / NT;      // chunks per thread per tile
+    static_assert(NCHUNK % NT == 0 || NCHUNK * 2 == NT, "tile must split over all or half of the threads");
     static_assert(CB <= WAVES, "one wave per channel block accumulates the V column sums");
 
     __shared__ __attribute__((aligned(16))) int8_t Ks[2][TILE];
@@ -92,7 +99,7 @@ __global__ __launch_bounds__(NT) void fwd_kernel(const FwdParams p)
     __shared__ uint32_t lut_lds[8];
     __shared__ int32_t colsum[D];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 31, h = lane >> 5;
     const int nbh = p.B * p.Hq;
     const int bh = blockIdx.x % nbh;
     const int qt = p.n_qtiles - 1 - blockIdx.x / nbh; // long (late) causal tiles first
@@ -124,124 +131,205 @@ __global__ __launch_bounds__(NT) void fwd_kernel(const FwdParams p)
     const int kmax = CAUSAL ? min(L, q0 + BQ) : L;
     const int ntiles = (kmax + BK - 1) / BK;
 
-    // ---- staging: global -> registers (issued a tile ahead) -> swizzled LDS
+    // ---- staging: global -> registers (issued a tile ahead) -> swizzled LDS.
+    // Thread-constant parts (key and chunk of each slot, global and LDS offsets) are computed once.
     v4i stage_k[CPT], stage_v[CPT];
-    auto load_tile = [&](const int8_t *base, int64_t stride, int t, v4i (&st)[CPT]) {
+    int st_key[CPT], st_goff_k[CPT], st_goff_v[CPT], st_lds_k[CPT], st_lds_v[CPT];
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) {
+        const int c = (tid + j * NT) % NCHUNK; // with half-size tiles the upper waves duplicate the lower ones' work
+        const int key = c / (D / 16), c16 = c % (D / 16);
+        st_key[j] = key;
+        st_goff_k[j] = key * (int)p.ks[2] + c16 * 16; // the host checked BK * stride < 2^31
+        st_goff_v[j] = key * (int)p.vs[2] + c16 * 16;
+        st_lds_k[j] = key * D + ((c16 ^ swz_k<D>(key)) << 4);
+        st_lds_v[j] = key * D + ((c16 ^ swz_v<D>(key)) << 4);
+    }
+    // Loads are unconditional (rows past L read the first row of the tile instead and are zeroed when stored), so that
+    // nothing forces a wait on them before the tile's compute.
+    auto load_tile = [&](const int8_t *base, int64_t stride, const int (&goff)[CPT], int t, v4i (&st)[CPT]) {
+        const int8_t *tb = base + (int64_t)t * BK * stride; // wave-uniform
 #pragma unroll
         for (int j = 0; j < CPT; ++j) {
-            const int c = tid + j * NT;
-            const int key = c / (D / 16), c16 = c % (D / 16);
-            const int gk = t * BK + key;
-            st[j] = v4i{0, 0, 0, 0};
-            if (gk < L) st[j] = *(const v4i *)(base + (int64_t)gk * stride + c16 * 16);
+            const uint32_t off = (t * BK + st_key[j] < L) ? (uint32_t)goff[j] : 0u; // row t*BK exists
+            st[j] = *(const v4i *)(tb + off);
         }
     };
-    auto store_k = [&](int buf) {
+    auto load_k = [&](int t) { load_tile(Kp, p.ks[2], st_goff_k, t, stage_k); };
+    auto load_v = [&](int t) { load_tile(Vp, p.vs[2], st_goff_v, t, stage_v); };
+    // t is the tile the staged registers hold
+    auto store_tile = [&](int8_t *dst, const int (&loff)[CPT], int t, v4i (&st)[CPT]) {
+        if ((t + 1) * BK > L) { // wave-uniform: only the last tile can be ragged
 #pragma unroll
-        for (int j = 0; j < CPT; ++j) {
-            const int c = tid + j * NT;
-            const int key = c / (D / 16), c16 = c % (D / 16);
-            *(v4i *)(Ks[buf] + key * D + ((c16 ^ swz_k<D>(key)) << 4)) = stage_k[j];
+            for (int j = 0; j < CPT; ++j)
+                if (t * BK + st_key[j] >= L) st[j] = v4i{0, 0, 0, 0};
         }
-    };
-    auto store_v = [&](int buf) {
 #pragma unroll
-        for (int j = 0; j < CPT; ++j) {
-            const int c = tid + j * NT;
-            const int key = c / (D / 16), c16 = c % (D / 16);
-            *(v4i *)(Vs[buf] + key * D + ((c16 ^ swz_v<D>(key)) << 4)) = stage_v[j];
-        }
+        for (int j = 0; j < CPT; ++j) *(v4i *)(dst + loff[j]) = st[j];
     };
+    auto store_k = [&](int buf, int t) { store_tile(Ks[buf], st_lds_k, t, stage_k); };
+    auto store_v = [&](int buf, int t) { store_tile(Vs[buf], st_lds_v, t, stage_v); };
 
-    // ---- S^T block for sub-tile st (32 keys) and row block rb
-    auto qk_block = [&](int buf, int st, int rb, v16i s) {
-        const int key = 32 * st + n;
+    // ---- S^T blocks of one tile: KT sub-tiles of 32 keys x RB row blocks, KB chained MFMAs each.
+    // The chains are interleaved (kb outermost) so that consecutive MFMAs are independent.
+    auto qk_tile = [&](int buf, v16i (&s)[KT][RB]) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-            const v4i a = *(const v4i *)(Ks[buf] + key * D + (((2 * kb + h) ^ swz_k<D>(key)) << 4));
-            s = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[rb][kb], s, 0, 0, 0);
+#pragma unroll
+            for (int st = 0; st < KT; ++st) {
+                const int key = 32 * st + n;
+                const v4i a = *(const v4i *)(Ks[buf] + key * D + (((2 * kb + h) ^ swz_k<D>(key)) << 4));
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+                    s[st][rb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[rb][kb], s[st][rb], 0, 0, 0);
+            }
         }
-        return s;
     };
-    // wave-uniform visibility of a 32-key block starting at klo for the 32 rows starting at r0
-    auto fully_hidden = [&](int klo, int r0) { return CAUSAL && klo > r0 + 31; };
-    auto needs_mask = [&](int klo, int r0) { return (klo + 32 > L) || (CAUSAL && klo + 31 > r0); };
     auto visible = [&](int key, int row) { return key < L && (!CAUSAL || key <= row); };
+    // wave-uniform: every key of tile t is visible to every row of this wave (no mask needed)
+    auto tile_is_full = [&](int t) { return (t + 1) * BK <= L && (!CAUSAL || (t + 1) * BK - 1 <= qw0); };
+    // wave-uniform: no key of tile t is visible to any row of this wave
+    auto tile_is_hidden = [&](int t) { return CAUSAL && t * BK > qw0 + RB * 32 - 1; };
 
     // ================================================================= sweep A: row max
     int mx[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) mx[rb] = INT32_MIN;
 
-    load_tile(Kp, p.ks[2], 0, stage_k);
-    store_k(0);
-    __syncthreads();
-    for (int t = 0; t < ntiles; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < ntiles) load_tile(Kp, p.ks[2], t + 1, stage_k);
+    auto tile_a = [&](auto masked_tag, int t, int buf) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        v16i s[KT][RB];
+#pragma unroll
+        for (int st = 0; st < KT; ++st)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[st][rb][i] = 0;
+        qk_tile(buf, s);
 #pragma unroll
         for (int st = 0; st < KT; ++st) {
-            const int klo = t * BK + 32 * st;
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                const int r0 = qw0 + 32 * rb, row = r0 + n;
-                if (fully_hidden(klo, r0)) continue;
-                v16i s = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                s = qk_block(buf, st, rb, s);
-                if (needs_mask(klo, r0)) {
+                if (MASKED) {
+                    const int klo = t * BK + 32 * st, row = qw0 + 32 * rb + n;
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
-                        if (visible(klo + acc_key(i, h), row)) mx[rb] = max(mx[rb], s[i]);
+                        mx[rb] = visible(klo + acc_key(i, h), row) ? max(mx[rb], s[st][rb][i]) : mx[rb];
                 } else {
 #pragma unroll
-                    for (int i = 0; i < 16; i += 2) mx[rb] = max(max(s[i], s[i + 1]), mx[rb]);
+                    for (int i = 0; i < 16; i += 2) mx[rb] = max(max(s[st][rb][i], s[st][rb][i + 1]), mx[rb]);
                 }
             }
         }
-        if (t + 1 < ntiles) store_k(buf ^ 1);
+    };
+
+    load_k(0);
+    store_k(0, 0);
+    __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) load_k(t + 1);
+        if (tile_is_full(t)) tile_a(std::false_type{}, t, buf);
+        else if (!tile_is_hidden(t)) tile_a(std::true_type{}, t, buf);
+        if (t + 1 < ntiles) store_k(buf ^ 1, t + 1);
         __syncthreads();
     }
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) mx[rb] = max(mx[rb], __shfl_xor(mx[rb], 32));
 
+    // accumulator start value -rowMax: the MFMA chain then yields A_hat - rowMax directly
+    v16i negm[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) negm[rb][i] = -mx[rb];
+
     // ================================================================= sweep B: row sum of E_hat
+    // This sweep is ALU-bound, so it also carries the column sums of V (one MFMA per 32 keys
+    // against an all-ones operand, wave w taking channel block w) that sweep C's signed
+    // probability bytes need as a correction; they cover every tile of the workgroup.
+    v16i cs = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const v4i ones = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
+
+    // transposing read: lanes 2j, 2j+1 of a 16-lane group point at the two 8-byte halves of key
+    // row j's 16 channels; lane i of the group receives channel i of the eight rows.
+    const int tr_i = lane & 15, tr_g = (lane >> 4) & 1;
+    auto vt_frag = [&](int buf, int st, int cb) {
+        v4i a;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int j = tr_i >> 1;
+            const int key = 32 * st + 8 * (2 * r + (j >> 2)) + 4 * h + (j & 3);
+            const int c16 = 2 * cb + tr_g;
+            const int8_t *ptr = Vs[buf] + key * D + ((c16 ^ swz_v<D>(key)) << 4) + 8 * (tr_i & 1);
+            const v2i x = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3))) *)ptr);
+            a[2 * r] = x[0];
+            a[2 * r + 1] = x[1];
+        }
+        return a;
+    };
+
     const uint8_t *lut_b = (const uint8_t *)lut_lds;
     uint32_t sum[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) sum[rb] = 0;
 
-    load_tile(Kp, p.ks[2], 0, stage_k);
-    store_k(0);
-    __syncthreads();
-    for (int t = 0; t < ntiles; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < ntiles) load_tile(Kp, p.ks[2], t + 1, stage_k);
+    auto tile_b = [&](auto masked_tag, int t, int buf) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        v16i s[KT][RB];
+#pragma unroll
+        for (int st = 0; st < KT; ++st)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) s[st][rb] = negm[rb];
+        qk_tile(buf, s); // s = A_hat - rowMax <= 0 for visible keys
 #pragma unroll
         for (int st = 0; st < KT; ++st) {
-            const int klo = t * BK + 32 * st;
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                const int r0 = qw0 + 32 * rb, row = r0 + n;
-                if (fully_hidden(klo, r0)) continue;
-                v16i s;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[i] = -mx[rb];
-                s = qk_block(buf, st, rb, s); // s[i] = A_hat - rowMax <= 0 for visible keys
-                if (needs_mask(klo, r0)) {
+                if (MASKED) {
+                    const int klo = t * BK + 32 * st, row = qw0 + 32 * rb + n;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const int tcl = min(max(s[i], negc), 0); // hidden keys may exceed the max
+                        const int tcl = min(max(s[st][rb][i], negc), 0); // hidden keys may exceed the max
                         const uint32_t e = lut_b[index_map<MODE>(tcl, hp, top)];
                         sum[rb] += visible(klo + acc_key(i, h), row) ? e : 0u;
                     }
                 } else {
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) sum[rb] += lut_b[index_map<MODE>(max(s[i], negc), hp, top)];
+                    for (int i = 0; i < 16; ++i)
+                        sum[rb] += lut_b[index_map<MODE>(max(s[st][rb][i], negc), hp, top)];
                 }
             }
         }
-        if (t + 1 < ntiles) store_k(buf ^ 1);
+    };
+
+    load_k(0);
+    load_v(0);
+    store_k(0, 0);
+    store_v(0, 0);
+    __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) {
+            load_k(t + 1);
+            load_v(t + 1);
+        }
+        if (tile_is_full(t)) tile_b(std::false_type{}, t, buf);
+        else if (!tile_is_hidden(t)) tile_b(std::true_type{}, t, buf);
+        if (wave < CB) {
+#pragma unroll
+            for (int st = 0; st < KT; ++st)
+                cs = __builtin_amdgcn_mfma_i32_32x32x32_i8(vt_frag(buf, st, wave), ones, cs, 0, 0, 0);
+        }
+        if (t + 1 < ntiles) {
+            store_k(buf ^ 1, t + 1);
+            store_v(buf ^ 1, t + 1);
+        }
         __syncthreads();
+    }
+    if (wave < CB && n == 0) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) colsum[32 * wave + acc_key(i, h)] = cs[i];
     }
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -269,103 +357,80 @@ __global__ __launch_bounds__(NT) void fwd_kernel(const FwdParams p)
         for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) o[rb][cb][i] = 0;
-    v16i cs = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; // V column sums, channel block `wave`
-    const v4i ones = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
-    const v4i hidden_p = v4i{(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
 
-    // transposing read: lanes 2j, 2j+1 of a 16-lane group point at the two 8-byte halves of key
-    // row j's 16 channels; lane i of the group receives channel i of the eight rows.
-    const int tr_i = lane & 15, tr_g = (lane >> 4) & 1;
-    auto vt_frag = [&](int buf, int st, int cb) {
-        v4i a;
+    // probabilities of one tile as MFMA B operands (the P_hat.V_hat MFMAs follow in one place for
+    // both instantiations, so that the output accumulators have a single home)
+    auto tile_c = [&](auto masked_tag, int t, int buf, v4i (&pf)[KT][RB]) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        v16i s[KT][RB];
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int j = tr_i >> 1;
-            const int key = 32 * st + 8 * (2 * r + (j >> 2)) + 4 * h + (j & 3);
-            const int c16 = 2 * cb + tr_g;
-            const int8_t *ptr = Vs[buf] + key * D + ((c16 ^ swz_v<D>(key)) << 4) + 8 * (tr_i & 1);
-            const v2i x = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3))) *)ptr);
-            a[2 * r] = x[0];
-            a[2 * r + 1] = x[1];
+        for (int st = 0; st < KT; ++st)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) s[st][rb] = negm[rb];
+        qk_tile(buf, s);
+#pragma unroll
+        for (int st = 0; st < KT; ++st) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                const uint32_t *pt = PT[wave][rb] + n;
+                const int klo = t * BK + 32 * st, row = qw0 + 32 * rb + n;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    uint32_t pb4[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int i = 4 * g + r;
+                        uint32_t pb;
+                        if (MASKED) {
+                            const int tcl = min(max(s[st][rb][i], negc), 0);
+                            pb = pt[index_map<MODE>(tcl, hp, top) * 32];
+                            pb = visible(klo + acc_key(i, h), row) ? pb : 0x80u;
+                        } else {
+                            pb = pt[index_map<MODE>(max(s[st][rb][i], negc), hp, top) * 32];
+                        }
+                        pb4[r] = pb;
+                    }
+                    const uint32_t packed = ((pb4[1] << 8) | pb4[0]) | (((pb4[3] << 8) | pb4[2]) << 16);
+                    pf[st][rb][g] = (int)packed;
+                }
+            }
         }
-        return a;
     };
 
-    load_tile(Kp, p.ks[2], 0, stage_k);
-    load_tile(Vp, p.vs[2], 0, stage_v);
-    store_k(0);
-    store_v(0);
+    load_k(0);
+    load_v(0);
+    store_k(0, 0);
+    store_v(0, 0);
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
         const int buf = t & 1;
         if (t + 1 < ntiles) {
-            load_tile(Kp, p.ks[2], t + 1, stage_k);
-            load_tile(Vp, p.vs[2], t + 1, stage_v);
+            load_k(t + 1);
+            load_v(t + 1);
         }
+        // every wave walks every tile of the workgroup here: the column-sum correction assumes it
+        v4i pf[KT][RB];
+        if (tile_is_full(t)) tile_c(std::false_type{}, t, buf, pf);
+        else tile_c(std::true_type{}, t, buf, pf);
 #pragma unroll
         for (int st = 0; st < KT; ++st) {
-            const int klo = t * BK + 32 * st;
-            v4i pf[RB];
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                const int r0 = qw0 + 32 * rb, row = r0 + n;
-                if (fully_hidden(klo, r0)) {
-                    pf[rb] = hidden_p;
-                    continue;
-                }
-                v16i s;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[i] = -mx[rb];
-                s = qk_block(buf, st, rb, s);
-                const uint32_t *pt = PT[wave][rb] + n;
-                if (needs_mask(klo, r0)) {
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        uint32_t packed = 0;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const int i = 4 * g + r;
-                            const int tcl = min(max(s[i], negc), 0);
-                            uint32_t pb = pt[index_map<MODE>(tcl, hp, top) * 32];
-                            pb = visible(klo + acc_key(i, h), row) ? pb : 0x80u;
-                            packed |= pb << (8 * r);
-                        }
-                        pf[rb][g] = (int)packed;
-                    }
-                } else {
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        uint32_t packed = 0;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            packed |= pt[index_map<MODE>(max(s[4 * g + r], negc), hp, top) * 32] << (8 * r);
-                        pf[rb][g] = (int)packed;
-                    }
-                }
-            }
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
                 const v4i a = vt_frag(buf, st, cb);
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
-                    o[rb][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pf[rb], o[rb][cb], 0, 0, 0);
-                if (cb == wave) cs = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, ones, cs, 0, 0, 0);
+                    o[rb][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pf[st][rb], o[rb][cb], 0, 0, 0);
             }
         }
         if (t + 1 < ntiles) {
-            store_k(buf ^ 1);
-            store_v(buf ^ 1);
+            store_k(buf ^ 1, t + 1);
+            store_v(buf ^ 1, t + 1);
         }
         __syncthreads();
     }
 
     // ================================================================= epilogue
-    if (wave < CB && n == 0) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) colsum[32 * wave + acc_key(i, h)] = cs[i];
-    }
-    __syncthreads();
-
+    // colsum was written after sweep B; sweep C's barriers made it visible
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const int row = qw0 + 32 * rb + n;
@@ -424,6 +489,7 @@ int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *strea
 {
     hipStream_t st = (hipStream_t)stream;
     if (variant == 2) return launch_shape<2, 2>(p, d, idx_mode, st);
+    if (variant == 3) return launch_shape<1, 1>(p, d, idx_mode, st);
     return launch_shape<1, 2>(p, d, idx_mode, st);
 }
 

@@ -260,7 +260,9 @@ int validate(intattn_ctx *ctx, const intattn_args *a)
     }
     const int64_t rows_per_block = fwd_rows_per_block(ctx->variant);
     const int64_t n_qtiles = (a->L + rows_per_block - 1) / rows_per_block;
-    if (n_qtiles * (int64_t)a->B * (int64_t)a->Hq > 2147483647LL)
+    // the launch grid pads the (batch, KV head) groups to a multiple of the 8 XCDs
+    const int64_t groups_padded = (((int64_t)a->B * a->Hkv + 7) / 8) * 8;
+    if (n_qtiles * groups_padded * (int64_t)(a->Hq / a->Hkv) > 2147483647LL)
         return fail(ctx, INTATTN_ERR_UNSUPPORTED, "problem needs more than 2^31-1 workgroups");
     return INTATTN_OK;
 }

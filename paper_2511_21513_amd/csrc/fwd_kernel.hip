@@ -30,55 +30,15 @@
 
 #include <type_traits>
 
+#include "kernel_common.h"
 #include "params.h"
 
 namespace intattn {
-
-typedef int v2i __attribute__((ext_vector_type(2)));
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
 
 namespace {
 
 constexpr int WAVES = 4;
 constexpr int NT = WAVES * 64;
-
-// ------------------------------------------------------------------ index map (Sec. 3.1)
-// t = -min(Delta, c_int) in [-c_int, 0]; returns round(-t * top / c_int).
-template <int MODE>
-__device__ __forceinline__ uint32_t index_map(int t, const HeadParams &hp, uint32_t top)
-{
-    if (MODE == IDX_MAD24) {
-        // (-t) * mul + add, 24-bit signed operands (idx_mul holds -mul)
-        return (uint32_t)(__mul24(t, (int)hp.idx_mul) + (int)hp.idx_add) >> hp.idx_shift;
-    } else if (MODE == IDX_MULHI24) {
-        // high word of ((t << pre) - off) * (-mul): both factors negative 24-bit values
-        const int x = (int)(((uint32_t)t << hp.idx_shift) + hp.idx_add); // idx_add holds -off
-        int r;
-        // written as an instruction so that later address arithmetic is not folded back into a
-        // 64-bit product (which costs three more VALU operations per element)
-        asm("v_mul_hi_i32_i24 %0, %1, %2" : "=v"(r) : "v"(x), "v"((int)hp.idx_mul));
-        return (uint32_t)r;
-    } else if (MODE == IDX_FP32) {
-        // trunc(fma(t, -(top/c_int), 0.5)): t is exact in fp32, one rounding in the fma; the host
-        // proved the result exact on the whole range with the same IEEE operations
-        return (uint32_t)(int)__builtin_fmaf((float)t, __uint_as_float(hp.idx_mul), 0.5f);
-    } else {
-        const uint64_t c = (uint64_t)(uint32_t)hp.c_int;
-        return (uint32_t)((2ull * top * (uint64_t)(uint32_t)(-t) + c) / (2ull * c));
-    }
-}
-
-// Key (within a 32-key block) held in accumulator register i of a 32x32 MFMA result by a
-// lane of half-wave h; the same key sits in byte i of that lane's next B operand.
-__device__ __forceinline__ int acc_key(int i, int h) { return 8 * (i >> 2) + 4 * h + (i & 3); }
-
-// XOR swizzles of the 16-byte chunk index inside a key row.
-template <int D> __device__ __forceinline__ int swz_k(int key) { return D == 128 ? (key & 7) : ((key >> 1) & 3); }
-template <int D> __device__ __forceinline__ int swz_v(int key)
-{
-    return D == 128 ? ((key & 3) | (((key >> 3) & 1) << 2)) : (((key >> 1) & 1) | (((key >> 3) & 1) << 1));
-}
 
 template <int D, int RB, int KT, bool CAUSAL, int MODE>
 __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void fwd_kernel(const FwdParams p)
@@ -100,10 +60,10 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void fwd_kernel(const FwdParam
     __shared__ int32_t colsum[D];
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 31, h = lane >> 5;
-    const int nbh = p.B * p.Hq;
-    const int bh = blockIdx.x % nbh;
-    const int qt = p.n_qtiles - 1 - blockIdx.x / nbh; // long (late) causal tiles first
-    const int b = bh / p.Hq, hq = bh % p.Hq, kvh = hq / p.group;
+    const WorkItem wi = fwd_work_item(p, (int)blockIdx.x);
+    if (!wi.valid) return; // padding of the XCD-aware grid (uniform for the whole workgroup)
+    const int b = wi.b, hq = wi.hq, kvh = wi.kvh, qt = wi.qt;
+    const int bh = b * p.Hq + hq;
     const HeadParams hp = p.hp_table ? p.hp_table[hq] : p.hp0;
     const int L = p.L;
     const uint32_t top = (uint32_t)p.top;
@@ -460,7 +420,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void fwd_kernel(const FwdParam
 template <int D, int RB, int KT, bool CAUSAL>
 int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
 {
-    const dim3 grid((unsigned)(p.n_qtiles * p.B * p.Hq)), block(NT);
+    const dim3 grid((unsigned)fwd_grid_size(p.B, p.Hq, p.Hkv, p.n_qtiles)), block(NT);
     if (idx_mode == IDX_MAD24)
         hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24>), grid, block, 0, st, p);
     else if (idx_mode == IDX_MULHI24)
@@ -488,6 +448,7 @@ int fwd_rows_per_block(int variant) { return variant == 2 ? 256 : 128; }
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
+    if (variant == 4) return launch_fwd_pipe(p, d, idx_mode, stream);
     if (variant == 2) return launch_shape<2, 2>(p, d, idx_mode, st);
     if (variant == 3) return launch_shape<1, 1>(p, d, idx_mode, st);
     return launch_shape<1, 2>(p, d, idx_mode, st);

@@ -1,0 +1,90 @@
+// Device helpers shared by the forward kernels: vector types, the exact index map of Sec. 3.1,
+// the MFMA accumulator-to-key map and the LDS chunk swizzles.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "params.h"
+
+namespace intattn {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// ------------------------------------------------------------------ workgroup -> work mapping
+// Workgroups are dealt round-robin to the 8 XCDs (workgroup id mod 8), and each XCD has its
+// own L2.  All query heads that share one KV head -- i.e. one (batch, KV head) group -- are
+// therefore sent to the same XCD, so that K and V of the group are fetched into one L2 only.
+// Within an XCD the longest (latest) causal query tiles come first.
+constexpr int NUM_XCD = 8;
+
+__host__ __device__ inline int64_t fwd_grid_size(int B, int Hq, int Hkv, int n_qtiles)
+{
+    const int64_t groups = (int64_t)B * Hkv;
+    const int64_t groups_per_xcd = (groups + NUM_XCD - 1) / NUM_XCD;
+    return (int64_t)NUM_XCD * groups_per_xcd * (Hq / Hkv) * n_qtiles;
+}
+
+struct WorkItem {
+    int b, hq, kvh, qt;
+    bool valid;
+};
+
+__device__ __forceinline__ WorkItem fwd_work_item(const FwdParams &p, int bid)
+{
+    const int g = p.group;
+    const int groups = p.B * p.Hkv;
+    const int groups_per_xcd = (groups + NUM_XCD - 1) / NUM_XCD;
+    const int xcd = bid % NUM_XCD, slot = bid / NUM_XCD;
+    const int hg = slot % g;
+    const int j = (slot / g) % groups_per_xcd;
+    const int qt_rev = slot / (g * groups_per_xcd);
+    const int gi = j * NUM_XCD + xcd; // (batch, KV head) group
+    WorkItem w;
+    w.valid = gi < groups;
+    w.b = gi / p.Hkv;
+    w.kvh = gi % p.Hkv;
+    w.hq = w.kvh * g + hg;
+    w.qt = p.n_qtiles - 1 - qt_rev;
+    return w;
+}
+
+// ------------------------------------------------------------------ index map (Sec. 3.1)
+// t = -min(Delta, c_int) in [-c_int, 0]; returns round(-t * top / c_int).
+template <int MODE>
+__device__ __forceinline__ uint32_t index_map(int t, const HeadParams &hp, uint32_t top)
+{
+    if (MODE == IDX_MAD24) {
+        // (-t) * mul + add, 24-bit signed operands (idx_mul holds -mul)
+        return (uint32_t)(__mul24(t, (int)hp.idx_mul) + (int)hp.idx_add) >> hp.idx_shift;
+    } else if (MODE == IDX_MULHI24) {
+        // high word of ((t << pre) - off) * (-mul): both factors negative 24-bit values
+        const int x = (int)(((uint32_t)t << hp.idx_shift) + hp.idx_add); // idx_add holds -off
+        int r;
+        // written as an instruction so that later address arithmetic is not folded back into a
+        // 64-bit product (which costs three more VALU operations per element)
+        asm("v_mul_hi_i32_i24 %0, %1, %2" : "=v"(r) : "v"(x), "v"((int)hp.idx_mul));
+        return (uint32_t)r;
+    } else if (MODE == IDX_FP32) {
+        // trunc(fma(t, -(top/c_int), 0.5)): t is exact in fp32, one rounding in the fma; the host
+        // proved the result exact on the whole range with the same IEEE operations
+        return (uint32_t)(int)__builtin_fmaf((float)t, __uint_as_float(hp.idx_mul), 0.5f);
+    } else {
+        const uint64_t c = (uint64_t)(uint32_t)hp.c_int;
+        return (uint32_t)((2ull * top * (uint64_t)(uint32_t)(-t) + c) / (2ull * c));
+    }
+}
+
+// Key (within a 32-key block) held in accumulator register i of a 32x32 MFMA result by a
+// lane of half-wave h; the same key sits in byte i of that lane's next B operand.
+__device__ __forceinline__ int acc_key(int i, int h) { return 8 * (i >> 2) + 4 * h + (i & 3); }
+
+// XOR swizzles of the 16-byte chunk index inside a key row.
+template <int D> __device__ __forceinline__ int swz_k(int key) { return D == 128 ? (key & 7) : ((key >> 1) & 3); }
+template <int D> __device__ __forceinline__ int swz_v(int key)
+{
+    return D == 128 ? ((key & 3) | (((key >> 3) & 1) << 2)) : (((key >> 1) & 1) | (((key >> 3) & 1) << 1));
+}
+
+} // namespace intattn

@@ -364,7 +364,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator)
     p.causal = a->causal;
     p.group = a->Hq / a->Hkv;
     p.top = (1 << ctx->lut_bits) - 1;
-    const int rows_per_block = fwd_rows_per_block(ctx->variant);
+    const int rows_per_block = comparator ? 128 : fwd_rows_per_block(ctx->variant);
     p.n_qtiles = (a->L + rows_per_block - 1) / rows_per_block;
     std::memcpy(p.lut, ctx->lut, 32);
     p.dbg_row_max = a->dbg_row_max; p.dbg_row_sum = a->dbg_row_sum; p.dbg_acc = a->dbg_acc;

@@ -41,7 +41,7 @@ constexpr int WAVES = 4;
 constexpr int NT = WAVES * 64;
 
 template <int D, int RB, int KT, bool CAUSAL, int MODE>
-__global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void fwd_kernel(const FwdParams p)
+__global__ __launch_bounds__(NT, RB == 1 ? (KT == 1 ? 3 : 2) : 1) void fwd_kernel(const FwdParams p)
 {
     constexpr int KB = D / 32;       // 32-wide blocks of the head dimension
     constexpr int CB = D / 32;       // 32-wide blocks of output channels
@@ -67,7 +67,6 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void fwd_kernel(const FwdParam
     const HeadParams hp = p.hp_table ? p.hp_table[hq] : p.hp0;
     const int L = p.L;
     const uint32_t top = (uint32_t)p.top;
-    const int negc = -hp.c_int;
 
     const int q0 = qt * BQ, qw0 = q0 + wave * (RB * 32);
     const int8_t *Qp = p.q + (int64_t)b * p.qs[0] + (int64_t)hq * p.qs[1];
@@ -198,11 +197,11 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void fwd_kernel(const FwdParam
     for (int rb = 0; rb < RB; ++rb) mx[rb] = max(mx[rb], __shfl_xor(mx[rb], 32));
 
     // accumulator start value -rowMax: the MFMA chain then yields A_hat - rowMax directly
-    v16i negm[RB];
+    // exact index map of each row block's lane row, applied to raw scores (no -rowMax start
+    // value in the accumulators, which saves 16 registers per row block)
+    RowIndex<MODE> ri[RB];
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) negm[rb][i] = -mx[rb];
+    for (int rb = 0; rb < RB; ++rb) ri[rb].init(hp, mx[rb], top);
 
     // ================================================================= sweep B: row sum of E_hat
     // This sweep is ALU-bound, so it also carries the column sums of V (one MFMA per 32 keys
@@ -240,7 +239,9 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void fwd_kernel(const FwdParam
 #pragma unroll
         for (int st = 0; st < KT; ++st)
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) s[st][rb] = negm[rb];
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[st][rb][i] = 0;
         qk_tile(buf, s); // s = A_hat - rowMax <= 0 for visible keys
 #pragma unroll
         for (int st = 0; st < KT; ++st) {
@@ -250,14 +251,14 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void fwd_kernel(const FwdParam
                     const int klo = t * BK + 32 * st, row = qw0 + 32 * rb + n;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const int tcl = min(max(s[st][rb][i], negc), 0); // hidden keys may exceed the max
-                        const uint32_t e = lut_b[index_map<MODE>(tcl, hp, top)];
+                        // hidden keys may exceed the row max
+                        const uint32_t e = lut_b[ri[rb](min(max(s[st][rb][i], ri[rb].bound), ri[rb].mx))];
                         sum[rb] += visible(klo + acc_key(i, h), row) ? e : 0u;
                     }
                 } else {
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
-                        sum[rb] += lut_b[index_map<MODE>(max(s[st][rb][i], negc), hp, top)];
+                        sum[rb] += lut_b[ri[rb](max(s[st][rb][i], ri[rb].bound))];
                 }
             }
         }
@@ -326,7 +327,9 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void fwd_kernel(const FwdParam
 #pragma unroll
         for (int st = 0; st < KT; ++st)
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) s[st][rb] = negm[rb];
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[st][rb][i] = 0;
         qk_tile(buf, s);
 #pragma unroll
         for (int st = 0; st < KT; ++st) {
@@ -342,11 +345,10 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void fwd_kernel(const FwdParam
                         const int i = 4 * g + r;
                         uint32_t pb;
                         if (MASKED) {
-                            const int tcl = min(max(s[st][rb][i], negc), 0);
-                            pb = pt[index_map<MODE>(tcl, hp, top) * 32];
+                            pb = pt[ri[rb](min(max(s[st][rb][i], ri[rb].bound), ri[rb].mx)) * 32];
                             pb = visible(klo + acc_key(i, h), row) ? pb : 0x80u;
                         } else {
-                            pb = pt[index_map<MODE>(max(s[st][rb][i], negc), hp, top) * 32];
+                            pb = pt[ri[rb](max(s[st][rb][i], ri[rb].bound)) * 32];
                         }
                         pb4[r] = pb;
                     }

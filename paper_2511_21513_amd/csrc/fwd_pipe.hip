@@ -44,11 +44,21 @@ __global__ __launch_bounds__(NT, 2) void fwd_pipe_kernel(const FwdParams p)
     static_assert(CPT >= 1 && CPT * NT == NCHUNK, "tile must split evenly over the threads");
     static_assert(CB <= WAVES, "one wave per channel block accumulates the V column sums");
 
-    __shared__ __attribute__((aligned(16))) int8_t Ks[NBUF][TILE];
-    __shared__ __attribute__((aligned(16))) int8_t Vs[NBUF][TILE];
-    __shared__ uint32_t PT[WAVES][32 * 32]; // [idx][row] per wave
-    __shared__ uint32_t lut_lds[8];
-    __shared__ int32_t colsum[D];
+    // One LDS object with the small tables first: their addresses then fit the 16-bit immediate
+    // offset of the LDS instructions, which saves an address addition per table lookup.
+    struct Smem {
+        uint8_t lut[32];
+        int32_t colsum[D];
+        uint32_t PT[WAVES][32 * 32]; // [idx][row] per wave
+        __attribute__((aligned(16))) int8_t Ks[NBUF][TILE];
+        __attribute__((aligned(16))) int8_t Vs[NBUF][TILE];
+    };
+    __shared__ __attribute__((aligned(16))) Smem sm;
+    auto &Ks = sm.Ks;
+    auto &Vs = sm.Vs;
+    auto &PT = sm.PT;
+    auto &lut_lds = sm.lut;
+    auto &colsum = sm.colsum;
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int n = lane & 31, h = lane >> 5;
@@ -59,14 +69,13 @@ __global__ __launch_bounds__(NT, 2) void fwd_pipe_kernel(const FwdParams p)
     const HeadParams hp = p.hp_table ? p.hp_table[hq] : p.hp0;
     const int L = p.L;
     const uint32_t top = (uint32_t)p.top;
-    const int negc = -hp.c_int;
 
     const int q0 = qt * BQ, qw0 = q0 + wave * 32, row = qw0 + n;
     const int8_t *Qp = p.q + (int64_t)b * p.qs[0] + (int64_t)hq * p.qs[1];
     const int8_t *Kp = p.k + (int64_t)b * p.ks[0] + (int64_t)kvh * p.ks[1];
     const int8_t *Vp = p.v + (int64_t)b * p.vs[0] + (int64_t)kvh * p.vs[1];
 
-    if (tid < 8) lut_lds[tid] = p.lut[tid];
+    if (tid < 8) ((uint32_t *)lut_lds)[tid] = p.lut[tid];
 
     v4i qf[KB];
 #pragma unroll
@@ -184,12 +193,11 @@ __global__ __launch_bounds__(NT, 2) void fwd_pipe_kernel(const FwdParams p)
     }
     mx = max(mx, __shfl_xor(mx, 32));
 
-    v16i negm;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) negm[i] = -mx;
+    RowIndex<MODE> ri; // exact index map for this lane's row, applied to raw scores
+    ri.init(hp, mx, top);
 
     // ================================================================= sweep B: row sum of E_hat
-    const uint8_t *lut_b = (const uint8_t *)lut_lds;
+    const uint8_t *lut_b = lut_lds;
     uint32_t sum = 0;
     v16i cs = zero16; // V column sums of channel block `wave` (needed by sweep C's signed bytes)
     const v4i ones = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
@@ -200,11 +208,10 @@ __global__ __launch_bounds__(NT, 2) void fwd_pipe_kernel(const FwdParams p)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             if (MASKED) {
-                const int tcl = min(max(s[i], negc), 0); // hidden keys may exceed the max
-                const uint32_t e = lut_b[index_map<MODE>(tcl, hp, top)];
+                const uint32_t e = lut_b[ri(min(max(s[i], ri.bound), ri.mx))]; // hidden keys may exceed the max
                 sum += visible(klo + acc_key(i, h)) ? e : 0u;
             } else {
-                sum += lut_b[index_map<MODE>(max(s[i], negc), hp, top)];
+                sum += lut_b[ri(max(s[i], ri.bound))];
             }
         }
     };
@@ -241,23 +248,23 @@ __global__ __launch_bounds__(NT, 2) void fwd_pipe_kernel(const FwdParams p)
     if (INTATTN_PROFILE_SWEEPS & 2) {
         sweep_prologue();
         // hot loop: tiles wholly visible to this wave, no masks, software-pipelined
-        v16i sA = qk(Ks[0], 0, negm), sB;
+        v16i sA = qk(Ks[0], 0, zero16), sB;
         for (int t = 0; t < nfull; ++t) {
             const int8_t *kcur = Ks[t % NBUF], *knext = Ks[(t + 1) % NBUF];
             // step 0: score block (t, 1) on the matrix core while block (t, 0) goes through the ALU
-            sB = qk(kcur, 1, negm);
+            sB = qk(kcur, 1, zero16);
             valu_b(std::false_type{}, sA, 0);
             colsum_step(t);
             stage_next(t);
             // step 1: block (t+1, 0) on the matrix core (recomputed by the tail loop if masked)
-            sA = qk(knext, 0, negm);
+            sA = qk(knext, 0, zero16);
             valu_b(std::false_type{}, sB, 0);
         }
         // tail: the diagonal / ragged / hidden tiles of this wave, masked, not pipelined
         for (int t = nfull; t < ntiles; ++t) {
             const int8_t *kcur = Ks[t % NBUF];
             if (!(CAUSAL && t * BK > qw0 + 31)) {
-                const v16i s0 = qk(kcur, 0, negm), s1 = qk(kcur, 1, negm);
+                const v16i s0 = qk(kcur, 0, zero16), s1 = qk(kcur, 1, zero16);
                 valu_b(std::true_type{}, s0, t * BK);
                 valu_b(std::true_type{}, s1, t * BK + 32);
             }
@@ -302,11 +309,10 @@ __global__ __launch_bounds__(NT, 2) void fwd_pipe_kernel(const FwdParams p)
             for (int r = 0; r < 4; ++r) {
                 const int i = 4 * g + r;
                 if (MASKED) {
-                    const int tcl = min(max(s[i], negc), 0);
-                    const uint32_t pb = pt[index_map<MODE>(tcl, hp, top) * 32];
+                    const uint32_t pb = pt[ri(min(max(s[i], ri.bound), ri.mx)) * 32];
                     pb4[r] = visible(klo + acc_key(i, h)) ? pb : 0x80u;
                 } else {
-                    pb4[r] = pt[index_map<MODE>(max(s[i], negc), hp, top) * 32];
+                    pb4[r] = pt[ri(max(s[i], ri.bound)) * 32];
                 }
             }
             pf[g] = (int)(((pb4[1] << 8) | pb4[0]) | (((pb4[3] << 8) | pb4[2]) << 16));
@@ -321,18 +327,18 @@ __global__ __launch_bounds__(NT, 2) void fwd_pipe_kernel(const FwdParams p)
 
     if (INTATTN_PROFILE_SWEEPS & 4) {
         sweep_prologue();
-        v16i sA = qk(Ks[0], 0, negm), sB;
+        v16i sA = qk(Ks[0], 0, zero16), sB;
         v4i pfA, pfB = v4i{0, 0, 0, 0}; // zero bytes: the first, dangling P.V step adds nothing
         for (int t = 0; t < nfull; ++t) {
             const int8_t *kcur = Ks[t % NBUF], *knext = Ks[(t + 1) % NBUF];
             const int8_t *vcur = Vs[t % NBUF], *vprev = Vs[(t + NBUF - 1) % NBUF];
             // step 0: matrix core: scores (t, 1) and P.V of block (t-1, 1); ALU: block (t, 0)
-            sB = qk(kcur, 1, negm);
+            sB = qk(kcur, 1, zero16);
             pv(vprev, 1, pfB);
             pfA = valu_c(std::false_type{}, sA, 0);
             stage_next(t);
             // step 1: matrix core: scores (t+1, 0) and P.V of block (t, 0); ALU: block (t, 1)
-            sA = qk(knext, 0, negm);
+            sA = qk(knext, 0, zero16);
             pv(vcur, 0, pfA);
             pfB = valu_c(std::false_type{}, sB, 0);
         }
@@ -340,7 +346,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_pipe_kernel(const FwdParams p)
         // tail: every wave walks every remaining tile (the column-sum correction assumes it)
         for (int t = nfull; t < ntiles; ++t) {
             const int8_t *kcur = Ks[t % NBUF], *vcur = Vs[t % NBUF];
-            const v16i s0 = qk(kcur, 0, negm), s1 = qk(kcur, 1, negm);
+            const v16i s0 = qk(kcur, 0, zero16), s1 = qk(kcur, 1, zero16);
             const v4i pf0 = valu_c(std::true_type{}, s0, t * BK);
             const v4i pf1 = valu_c(std::true_type{}, s1, t * BK + 32);
             pv(vcur, 0, pf0);

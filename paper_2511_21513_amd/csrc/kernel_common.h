@@ -76,6 +76,49 @@ __device__ __forceinline__ uint32_t index_map(int t, const HeadParams &hp, uint3
     }
 }
 
+// The same map applied to RAW scores of one query row (the lane's row): with the row maximum
+// mx, idx = round(min(mx - s, c_int) * top / c_int).  The subtraction of mx is folded into
+// per-row constants (all arithmetic is modulo 2^32 and the true values are small), so a
+// score costs: clip (max with `bound`), then the scheme's two operations.
+// Call with sc = max(s, bound), and additionally sc <= mx where hidden keys may exceed mx.
+template <int MODE> struct RowIndex {
+    int bound; // mx - c_int
+    int mx;
+    uint32_t addc;
+    int mul;
+    int shift;
+    uint32_t c_int, top;
+
+    __device__ __forceinline__ void init(const HeadParams &hp, int row_max, uint32_t top_)
+    {
+        mx = row_max;
+        bound = row_max - hp.c_int;
+        mul = (int)hp.idx_mul;
+        shift = hp.idx_shift;
+        c_int = (uint32_t)hp.c_int;
+        top = top_;
+        if (MODE == IDX_MULHI24) addc = hp.idx_add - ((uint32_t)row_max << hp.idx_shift);
+        else if (MODE == IDX_MAD24) addc = hp.idx_add - (uint32_t)__mul24(row_max, (int)hp.idx_mul);
+        else addc = 0;
+    }
+    __device__ __forceinline__ uint32_t operator()(int sc) const
+    {
+        if (MODE == IDX_MULHI24) {
+            const int x = (int)(((uint32_t)sc << shift) + addc);
+            int r;
+            asm("v_mul_hi_i32_i24 %0, %1, %2" : "=v"(r) : "v"(x), "v"(mul));
+            return (uint32_t)r;
+        } else if (MODE == IDX_MAD24) {
+            return ((uint32_t)__mul24(sc, mul) + addc) >> shift;
+        } else if (MODE == IDX_FP32) {
+            return (uint32_t)(int)__builtin_fmaf((float)(sc - mx), __uint_as_float((uint32_t)mul), 0.5f);
+        } else {
+            const uint64_t c = c_int;
+            return (uint32_t)((2ull * top * (uint64_t)(uint32_t)(mx - sc) + c) / (2ull * c));
+        }
+    }
+};
+
 // Key (within a 32-key block) held in accumulator register i of a 32x32 MFMA result by a
 // lane of half-wave h; the same key sits in byte i of that lane's next B operand.
 __device__ __forceinline__ int acc_key(int i, int h) { return 8 * (i >> 2) + 4 * h + (i & 3); }

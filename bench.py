@@ -22,6 +22,10 @@ if ROOT not in sys.path:
 
 INT8_MFMA_PEAK_TOPS = 5000.0  # MI355X dense int8 matrix peak, 5.0 POP/s
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the forward kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# each scaled by the same counter's reading for a plain 1 GiB device copy
+# (profiles/fwd_kernel_c4_gqa_prefill_8k.md).  Only workloads that were profiled have an entry.
+MEASURED_HBM_TRAFFIC_BYTES = {"c4_gqa_prefill_8k": 50.76e6 + 33.55e6}
 
 ALIASES = {"c1": "c1_single_head", "c2": "c2_vit_b16", "c3": "c3_llm_prefill_2k",
            "c4": "c4_gqa_prefill_8k", "c5": "c5_batched_prefill_4k"}
@@ -67,6 +71,9 @@ def main():
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparator", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="instead of the benchmark, run a plain device copy of this many MiB three times "
+                         "(the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-heads", type=int, default=8)
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -76,6 +83,16 @@ def main():
 
     import numpy as np
     import torch
+
+    if a.copy_calibration > 0:
+        n = a.copy_calibration << 20
+        src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 3}))
+        return
 
     from paper_2511_21513_amd import binding, inputs
 
@@ -127,7 +144,7 @@ def main():
         "wall_ms_per_step": wall_ms,
         "sampled_parity_mismatching_bytes": mism,
         "roofline": {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": tops / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                     "frac": tops / INT8_MFMA_PEAK_TOPS, "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(name),
                      "kernel": "fwd_kernel", "counted_ops_per_launch": p.ops,
                      "hbm_algorithmic_bytes_per_launch": p.algorithmic_bytes,
                      "hbm_algorithmic_GBps": p.algorithmic_bytes / (ms * 1e-3) / 1e9},

@@ -26,6 +26,9 @@ struct intattn_ctx {
     HeadParams *d_hp = nullptr;
     float *d_alpha = nullptr, *d_svso = nullptr;
     int table_cap = 0;
+    // kernel workspace (row max and row sum between the two launches, V chunk sums), grown on demand
+    int32_t *d_ws = nullptr;
+    size_t ws_cap = 0; // in int32 elements
     std::vector<HeadParams> hp_host;  // what d_hp currently holds
     std::vector<float> alpha_host, svso_host;
     std::string err;
@@ -341,6 +344,19 @@ int ensure_tables(intattn_ctx *ctx, int n)
     return INTATTN_OK;
 }
 
+int ensure_workspace(intattn_ctx *ctx, size_t n_int32)
+{
+    if (n_int32 <= ctx->ws_cap) return INTATTN_OK;
+    int32_t *ws = nullptr;
+    const hipError_t e = hipMalloc((void **)&ws, n_int32 * sizeof(int32_t));
+    if (e != hipSuccess)
+        return fail(ctx, INTATTN_ERR_NOMEM, std::string("hipMalloc of the kernel workspace: ") + hipGetErrorString(e));
+    if (ctx->d_ws) (void)hipFree(ctx->d_ws); // hipFree waits for work that may still read it
+    ctx->d_ws = ws;
+    ctx->ws_cap = n_int32;
+    return INTATTN_OK;
+}
+
 int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator)
 {
     int rc = validate(ctx, a);
@@ -398,6 +414,16 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator)
         p.hp_table = ctx->d_hp;
         p.alpha_table = ctx->d_alpha;
         p.svso_table = ctx->d_svso;
+    }
+
+    if (!comparator && fwd_needs_workspace(ctx->variant)) {
+        const size_t rows = (size_t)a->B * a->Hq * a->L;
+        const size_t cs = (size_t)a->B * a->Hkv * p.n_qtiles * a->d;
+        rc = ensure_workspace(ctx, 2 * rows + cs);
+        if (rc) return rc;
+        p.ws_row_max = ctx->d_ws;
+        p.ws_row_sum = ctx->d_ws + rows;
+        p.ws_colsum = ctx->d_ws + 2 * rows;
     }
 
     const int herr = comparator ? launch_quantonly(p, a->d, ctx->variant, stream)
@@ -508,6 +534,7 @@ void intattn_destroy(intattn_ctx *ctx)
         if (ctx->d_hp) (void)hipFree(ctx->d_hp);
         if (ctx->d_alpha) (void)hipFree(ctx->d_alpha);
         if (ctx->d_svso) (void)hipFree(ctx->d_svso);
+        if (ctx->d_ws) (void)hipFree(ctx->d_ws);
     }
     delete ctx;
 }

@@ -40,8 +40,13 @@ namespace {
 constexpr int WAVES = 4;
 constexpr int NT = WAVES * 64;
 
-template <int D, int RB, int KT, bool CAUSAL, int MODE>
-__global__ __launch_bounds__(NT, RB == 1 ? (KT == 1 ? 3 : 2) : 1) void fwd_kernel(const FwdParams p)
+// PH selects which part of the path this instantiation runs: 0 = all three sweeps in one launch;
+// 1 = sweeps A and B only (row max, row sum and V column sums go to a small workspace: 8 bytes per
+// query row) -- without the output accumulators it needs half the registers, so twice as many
+// waves per SIMD hide the LDS and MFMA latencies of the two ALU-light sweeps; 2 = sweep C only,
+// reading that workspace.
+template <int D, int RB, int KT, bool CAUSAL, int MODE, int PH>
+__global__ __launch_bounds__(NT, PH == 1 ? 4 : (RB == 1 ? (KT == 1 ? 3 : 2) : 1)) void fwd_kernel(const FwdParams p)
 {
     constexpr int KB = D / 32;       // 32-wide blocks of the head dimension
     constexpr int CB = D / 32;       // 32-wide blocks of output channels
@@ -131,18 +136,29 @@ __global__ __launch_bounds__(NT, RB == 1 ? (KT == 1 ? 3 : 2) : 1) void fwd_kerne
 
     // ---- S^T blocks of one tile: KT sub-tiles of 32 keys x RB row blocks, KB chained MFMAs each.
     // The chains are interleaved (kb outermost) so that consecutive MFMAs are independent.
+    // All K fragments of the tile are requested before the first MFMA (the scheduling barrier keeps
+    // the compiler from re-serialising read -> wait -> MFMA), so one LDS latency is paid per tile.
     auto qk_tile = [&](int buf, v16i (&s)[KT][RB]) {
+        v4i kf[KB][KT];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
             for (int st = 0; st < KT; ++st) {
                 const int key = 32 * st + n;
-                const v4i a = *(const v4i *)(Ks[buf] + key * D + (((2 * kb + h) ^ swz_k<D>(key)) << 4));
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-                    s[st][rb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[rb][kb], s[st][rb], 0, 0, 0);
+                kf[kb][st] = *(const v4i *)(Ks[buf] + key * D + (((2 * kb + h) ^ swz_k<D>(key)) << 4));
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+#pragma unroll
+            for (int st = 0; st < KT; ++st) {
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+                    s[st][rb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[kb][st], qf[rb][kb], s[st][rb], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
     };
     auto visible = [&](int key, int row) { return key < L && (!CAUSAL || key <= row); };
     // wave-uniform: every key of tile t is visible to every row of this wave (no mask needed)
@@ -182,21 +198,28 @@ __global__ __launch_bounds__(NT, RB == 1 ? (KT == 1 ? 3 : 2) : 1) void fwd_kerne
         }
     };
 
-    load_k(0);
-    store_k(0, 0);
-    __syncthreads();
-    for (int t = 0; t < ntiles; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < ntiles) load_k(t + 1);
-        if (tile_is_full(t)) tile_a(std::false_type{}, t, buf);
-        else if (!tile_is_hidden(t)) tile_a(std::true_type{}, t, buf);
-        if (t + 1 < ntiles) store_k(buf ^ 1, t + 1);
+    if constexpr (PH != 2) {
+        load_k(0);
+        store_k(0, 0);
         __syncthreads();
-    }
+        for (int t = 0; t < ntiles; ++t) {
+            const int buf = t & 1;
+            if (t + 1 < ntiles) load_k(t + 1);
+            if (tile_is_full(t)) tile_a(std::false_type{}, t, buf);
+            else if (!tile_is_hidden(t)) tile_a(std::true_type{}, t, buf);
+            if (t + 1 < ntiles) store_k(buf ^ 1, t + 1);
+            __syncthreads();
+        }
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) mx[rb] = max(mx[rb], __shfl_xor(mx[rb], 32));
+        for (int rb = 0; rb < RB; ++rb) mx[rb] = max(mx[rb], __shfl_xor(mx[rb], 32));
+    } else {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const int row = qw0 + 32 * rb + n;
+            mx[rb] = row < L ? p.ws_row_max[(int64_t)bh * L + row] : 0;
+        }
+    }
 
-    // accumulator start value -rowMax: the MFMA chain then yields A_hat - rowMax directly
     // exact index map of each row block's lane row, applied to raw scores (no -rowMax start
     // value in the accumulators, which saves 16 registers per row block)
     RowIndex<MODE> ri[RB];
@@ -204,12 +227,6 @@ __global__ __launch_bounds__(NT, RB == 1 ? (KT == 1 ? 3 : 2) : 1) void fwd_kerne
     for (int rb = 0; rb < RB; ++rb) ri[rb].init(hp, mx[rb], top);
 
     // ================================================================= sweep B: row sum of E_hat
-    // This sweep is ALU-bound, so it also carries the column sums of V (one MFMA per 32 keys
-    // against an all-ones operand, wave w taking channel block w) that sweep C's signed
-    // probability bytes need as a correction; they cover every tile of the workgroup.
-    v16i cs = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    const v4i ones = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
-
     // transposing read: lanes 2j, 2j+1 of a 16-lane group point at the two 8-byte halves of key
     // row j's 16 channels; lane i of the group receives channel i of the eight rows.
     const int tr_i = lane & 15, tr_g = (lane >> 4) & 1;
@@ -256,45 +273,70 @@ __global__ __launch_bounds__(NT, RB == 1 ? (KT == 1 ? 3 : 2) : 1) void fwd_kerne
                         sum[rb] += visible(klo + acc_key(i, h), row) ? e : 0u;
                     }
                 } else {
+                    // every lookup of the block is issued before the first one is consumed
 #pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        sum[rb] += lut_b[ri[rb](max(s[st][rb][i], ri[rb].bound))];
+                    for (int i = 0; i < 16; ++i) s[st][rb][i] = (int)lut_b[ri[rb](max(s[st][rb][i], ri[rb].bound))];
                 }
             }
         }
-    };
-
-    load_k(0);
-    load_v(0);
-    store_k(0, 0);
-    store_v(0, 0);
-    __syncthreads();
-    for (int t = 0; t < ntiles; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < ntiles) {
-            load_k(t + 1);
-            load_v(t + 1);
-        }
-        if (tile_is_full(t)) tile_b(std::false_type{}, t, buf);
-        else if (!tile_is_hidden(t)) tile_b(std::true_type{}, t, buf);
-        if (wave < CB) {
+        if (!MASKED) {
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int st = 0; st < KT; ++st)
-                cs = __builtin_amdgcn_mfma_i32_32x32x32_i8(vt_frag(buf, st, wave), ones, cs, 0, 0, 0);
-        }
-        if (t + 1 < ntiles) {
-            store_k(buf ^ 1, t + 1);
-            store_v(buf ^ 1, t + 1);
-        }
-        __syncthreads();
-    }
-    if (wave < CB && n == 0) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) colsum[32 * wave + acc_key(i, h)] = cs[i];
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sum[rb] += (uint32_t)s[st][rb][i];
+        }
+    };
+
+    if constexpr (PH != 2) {
+        load_k(0);
+        store_k(0, 0);
+        __syncthreads();
+        for (int t = 0; t < ntiles; ++t) {
+            const int buf = t & 1;
+            if (t + 1 < ntiles) load_k(t + 1);
+            if (tile_is_full(t)) tile_b(std::false_type{}, t, buf);
+            else if (!tile_is_hidden(t)) tile_b(std::true_type{}, t, buf);
+            if (t + 1 < ntiles) store_k(buf ^ 1, t + 1);
+            __syncthreads();
+        }
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) sum[rb] += __shfl_xor(sum[rb], 32);
+    }
+    if constexpr (PH == 1) {
+        // hand row max and row sum to the second launch
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const int row = qw0 + 32 * rb + n;
+            if (h == 0 && row < L) {
+                p.ws_row_max[(int64_t)bh * L + row] = mx[rb];
+                p.ws_row_sum[(int64_t)bh * L + row] = (int32_t)sum[rb];
+            }
+        }
+        return;
+    } else if constexpr (PH == 2) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const int row = qw0 + 32 * rb + n;
+            sum[rb] = row < L ? (uint32_t)p.ws_row_sum[(int64_t)bh * L + row] : 0u;
+        }
+    }
+    // Column sums of V over every key that sweep C's tiles cover (keys up to the end of this query
+    // tile under the causal mask, else all): the correction for feeding the probabilities to the
+    // signed MFMA as P - 128.  A small kernel ahead of this one left the sums of each BQ-key chunk
+    // per (batch, KV head); visible to all waves after sweep C's barriers.
+    if (tid < D) {
+        const int32_t *cp = p.ws_colsum + (int64_t)(b * p.Hkv + kvh) * p.n_qtiles * D + tid;
+        const int nchunk = CAUSAL ? qt + 1 : p.n_qtiles;
+        int32_t acc = 0;
+#pragma unroll 8
+        for (int c = 0; c < nchunk; ++c) acc += cp[(int64_t)c * D];
+        colsum[tid] = acc;
     }
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        sum[rb] += __shfl_xor(sum[rb], 32);
         if (sum[rb] == 0) sum[rb] = 1; // only rows beyond L; never stored
         // per-row probability table: PT[idx] = round(255 * LUT_hat[idx] / sum) - 128 as a byte
         uint32_t *pt = PT[wave][rb];
@@ -319,9 +361,11 @@ __global__ __launch_bounds__(NT, RB == 1 ? (KT == 1 ? 3 : 2) : 1) void fwd_kerne
 #pragma unroll
             for (int i = 0; i < 16; ++i) o[rb][cb][i] = 0;
 
-    // probabilities of one tile as MFMA B operands (the P_hat.V_hat MFMAs follow in one place for
-    // both instantiations, so that the output accumulators have a single home)
-    auto tile_c = [&](auto masked_tag, int t, int buf, v4i (&pf)[KT][RB]) {
+    // One tile of sweep C in phases, separated by scheduling barriers so that each kind of LDS
+    // latency is paid once per tile: S^T blocks; all probability lookups (in place, one per score)
+    // followed by all V^T fragment reads; packing into MFMA B operands (LDS returns in order, so
+    // the lookups land first while the fragments are still in flight).
+    auto tile_c = [&](auto masked_tag, int t, int buf, v4i (&pf)[KT][RB], v4i (&vf)[KT][CB]) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         v16i s[KT][RB];
 #pragma unroll
@@ -336,6 +380,22 @@ __global__ __launch_bounds__(NT, RB == 1 ? (KT == 1 ? 3 : 2) : 1) void fwd_kerne
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
                 const uint32_t *pt = PT[wave][rb] + n;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int sc = MASKED ? min(max(s[st][rb][i], ri[rb].bound), ri[rb].mx) : max(s[st][rb][i], ri[rb].bound);
+                    s[st][rb][i] = (int)pt[ri[rb](sc) * 32];
+                }
+            }
+        }
+#pragma unroll
+        for (int st = 0; st < KT; ++st)
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) vf[st][cb] = vt_frag(buf, st, cb);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int st = 0; st < KT; ++st) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
                 const int klo = t * BK + 32 * st, row = qw0 + 32 * rb + n;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
@@ -343,17 +403,10 @@ __global__ __launch_bounds__(NT, RB == 1 ? (KT == 1 ? 3 : 2) : 1) void fwd_kerne
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int i = 4 * g + r;
-                        uint32_t pb;
-                        if (MASKED) {
-                            pb = pt[ri[rb](min(max(s[st][rb][i], ri[rb].bound), ri[rb].mx)) * 32];
-                            pb = visible(klo + acc_key(i, h), row) ? pb : 0x80u;
-                        } else {
-                            pb = pt[ri[rb](max(s[st][rb][i], ri[rb].bound)) * 32];
-                        }
-                        pb4[r] = pb;
+                        pb4[r] = (uint32_t)s[st][rb][i];
+                        if (MASKED) pb4[r] = visible(klo + acc_key(i, h), row) ? pb4[r] : 0x80u;
                     }
-                    const uint32_t packed = ((pb4[1] << 8) | pb4[0]) | (((pb4[3] << 8) | pb4[2]) << 16);
-                    pf[st][rb][g] = (int)packed;
+                    pf[st][rb][g] = (int)(((pb4[1] << 8) | pb4[0]) | (((pb4[3] << 8) | pb4[2]) << 16));
                 }
             }
         }
@@ -371,17 +424,19 @@ __global__ __launch_bounds__(NT, RB == 1 ? (KT == 1 ? 3 : 2) : 1) void fwd_kerne
             load_v(t + 1);
         }
         // every wave walks every tile of the workgroup here: the column-sum correction assumes it
-        v4i pf[KT][RB];
-        if (tile_is_full(t)) tile_c(std::false_type{}, t, buf, pf);
-        else tile_c(std::true_type{}, t, buf, pf);
+        // (the P_hat.V_hat MFMAs follow in one place for both instantiations, so that the output
+        // accumulators have a single home)
+        v4i pf[KT][RB], vf[KT][CB];
+        if (tile_is_full(t)) tile_c(std::false_type{}, t, buf, pf, vf);
+        else tile_c(std::true_type{}, t, buf, pf, vf);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int st = 0; st < KT; ++st) {
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
-                const v4i a = vt_frag(buf, st, cb);
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
-                    o[rb][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pf[st][rb], o[rb][cb], 0, 0, 0);
+                    o[rb][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[st][cb], pf[st][rb], o[rb][cb], 0, 0, 0);
             }
         }
         if (t + 1 < ntiles) {
@@ -419,26 +474,68 @@ __global__ __launch_bounds__(NT, RB == 1 ? (KT == 1 ? 3 : 2) : 1) void fwd_kerne
     }
 }
 
-template <int D, int RB, int KT, bool CAUSAL>
+// Sums of V over each chunk of `chunk` consecutive keys, per (batch, KV head) and channel:
+// out[((b * Hkv + kvh) * n_qtiles + c) * D + ch].  Keys past L do not count.  The forward kernel
+// adds up the chunks its tiles cover.
+template <int D>
+__global__ __launch_bounds__(256) void colsum_kernel(const FwdParams p, int chunk)
+{
+    constexpr int G = D / 16;   // 16-byte column groups of a key row
+    constexpr int KL = 256 / G; // key lanes
+    __shared__ int32_t red[KL][D + 1];
+    const int tid = threadIdx.x, c16 = tid % G, kl = tid / G;
+    const int c = blockIdx.x % p.n_qtiles, bk = blockIdx.x / p.n_qtiles, kvh = bk % p.Hkv, b = bk / p.Hkv;
+    const int8_t *Vp = p.v + (int64_t)b * p.vs[0] + (int64_t)kvh * p.vs[1];
+    int32_t acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0;
+    const int kend = min(p.L, (c + 1) * chunk);
+    for (int key = c * chunk + kl; key < kend; key += KL) {
+        const v4i x = *(const v4i *)(Vp + (int64_t)key * p.vs[2] + c16 * 16);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] += (int32_t)(int8_t)((uint32_t)x[i / 4] >> (8 * (i % 4)));
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) red[kl][c16 * 16 + i] = acc[i];
+    __syncthreads();
+    if (tid < D) {
+        int32_t t = 0;
+        for (int j = 0; j < KL; ++j) t += red[j][tid];
+        p.ws_colsum[((int64_t)bk * p.n_qtiles + c) * D + tid] = t;
+    }
+}
+
+int launch_colsum(const FwdParams &p, int d, int chunk, hipStream_t st)
+{
+    const dim3 grid((unsigned)(p.B * p.Hkv * p.n_qtiles)), block(256);
+    if (d == 64) hipLaunchKernelGGL(colsum_kernel<64>, grid, block, 0, st, p, chunk);
+    else if (d == 128) hipLaunchKernelGGL(colsum_kernel<128>, grid, block, 0, st, p, chunk);
+    else return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
+}
+
+template <int D, int RB, int KT, bool CAUSAL, int PH>
 int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
 {
     const dim3 grid((unsigned)fwd_grid_size(p.B, p.Hq, p.Hkv, p.n_qtiles)), block(NT);
     if (idx_mode == IDX_MAD24)
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24, PH>), grid, block, 0, st, p);
     else if (idx_mode == IDX_MULHI24)
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MULHI24>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MULHI24, PH>), grid, block, 0, st, p);
     else if (idx_mode == IDX_FP32)
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP32>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP32, PH>), grid, block, 0, st, p);
     else
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_DIV>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_DIV, PH>), grid, block, 0, st, p);
     return (int)hipGetLastError();
 }
 
-template <int RB, int KT>
+template <int RB, int KT, int PH>
 int launch_shape(const FwdParams &p, int d, int idx_mode, hipStream_t st)
 {
-    if (d == 64) return p.causal ? launch_mode<64, RB, KT, true>(p, idx_mode, st) : launch_mode<64, RB, KT, false>(p, idx_mode, st);
-    if (d == 128) return p.causal ? launch_mode<128, RB, KT, true>(p, idx_mode, st) : launch_mode<128, RB, KT, false>(p, idx_mode, st);
+    if (d == 64)
+        return p.causal ? launch_mode<64, RB, KT, true, PH>(p, idx_mode, st) : launch_mode<64, RB, KT, false, PH>(p, idx_mode, st);
+    if (d == 128)
+        return p.causal ? launch_mode<128, RB, KT, true, PH>(p, idx_mode, st) : launch_mode<128, RB, KT, false, PH>(p, idx_mode, st);
     return (int)hipErrorInvalidValue;
 }
 
@@ -446,14 +543,24 @@ int launch_shape(const FwdParams &p, int d, int idx_mode, hipStream_t st)
 
 // variant 0/1: 32 query rows per wave (128 per workgroup); variant 2: 64 per wave (256).
 int fwd_rows_per_block(int variant) { return variant == 2 ? 256 : 128; }
+bool fwd_needs_workspace(int variant) { return variant != 4; }
 
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
     if (variant == 4) return launch_fwd_pipe(p, d, idx_mode, stream);
-    if (variant == 2) return launch_shape<2, 2>(p, d, idx_mode, st);
-    if (variant == 3) return launch_shape<1, 1>(p, d, idx_mode, st);
-    return launch_shape<1, 2>(p, d, idx_mode, st);
+    // all launches go to the same stream: V chunk sums first, then the sweeps
+    int e = launch_colsum(p, d, fwd_rows_per_block(variant), st);
+    if (e != 0) return e;
+    if (variant == 2) return launch_shape<2, 2, 0>(p, d, idx_mode, st);
+    if (variant == 3) return launch_shape<1, 1, 0>(p, d, idx_mode, st);
+    if (variant == 5 || variant == 6) {
+        // sweeps A+B at high occupancy, then sweep C
+        e = launch_shape<1, 2, 1>(p, d, idx_mode, st);
+        if (e != 0) return e;
+        return variant == 5 ? launch_shape<1, 2, 2>(p, d, idx_mode, st) : launch_shape<1, 1, 2>(p, d, idx_mode, st);
+    }
+    return launch_shape<1, 2, 0>(p, d, idx_mode, st);
 }
 
 } // namespace intattn

@@ -38,6 +38,9 @@ struct FwdParams {
     HeadParams hp0;             // the single parameter set when hp_table == nullptr
     uint32_t lut[8];            // LUT_hat, 32 bytes packed little-endian (unused tail is 0)
     int32_t *dbg_row_max, *dbg_row_sum, *dbg_acc;
+    // workspace: [B*Hq*L] row max and [B*Hq*L] row sum (handed from the first to the second launch
+    // of the two-launch variants), [B*Hkv*n_qtiles*d] sums of V over each chunk of keys
+    int32_t *ws_row_max, *ws_row_sum, *ws_colsum;
     // comparator only
     float alpha0, sv_over_so0;  // per-tensor values when the float tables are null
     const float *alpha_table;   // device [Hq]
@@ -48,6 +51,7 @@ struct FwdParams {
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *stream);
 int launch_fwd_pipe(const FwdParams &p, int d, int idx_mode, void *stream);
 int fwd_rows_per_block(int variant);
+bool fwd_needs_workspace(int variant);
 int launch_quantonly(const FwdParams &p, int d, int variant, void *stream);
 
 } // namespace intattn

@@ -46,7 +46,7 @@ constexpr int NT = WAVES * 64;
 // waves per SIMD hide the LDS and MFMA latencies of the two ALU-light sweeps; 2 = sweep C only,
 // reading that workspace.
 template <int D, int RB, int KT, bool CAUSAL, int MODE, int PH>
-__global__ __launch_bounds__(NT, PH == 1 ? 4 : (RB == 1 ? (KT == 1 ? 3 : 2) : 1)) void fwd_kernel(const FwdParams p)
+__global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (KT == 1 ? 3 : 2) : 1)) void fwd_kernel(const FwdParams p)
 {
     constexpr int KB = D / 32;       // 32-wide blocks of the head dimension
     constexpr int CB = D / 32;       // 32-wide blocks of output channels
@@ -554,11 +554,15 @@ int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *strea
     if (e != 0) return e;
     if (variant == 2) return launch_shape<2, 2, 0>(p, d, idx_mode, st);
     if (variant == 3) return launch_shape<1, 1, 0>(p, d, idx_mode, st);
-    if (variant == 5 || variant == 6) {
+    if (variant >= 5 && variant <= 8) {
         // sweeps A+B at high occupancy, then sweep C
-        e = launch_shape<1, 2, 1>(p, d, idx_mode, st);
+        FwdParams pab = p;
+        if (variant >= 7) pab.n_qtiles = (p.L + 255) / 256; // 64 query rows per wave in the first launch
+        e = variant == 7 ? launch_shape<2, 1, 1>(pab, d, idx_mode, st)
+          : variant == 8 ? launch_shape<2, 2, 1>(pab, d, idx_mode, st)
+                         : launch_shape<1, 2, 1>(pab, d, idx_mode, st);
         if (e != 0) return e;
-        return variant == 5 ? launch_shape<1, 2, 2>(p, d, idx_mode, st) : launch_shape<1, 1, 2>(p, d, idx_mode, st);
+        return variant == 6 ? launch_shape<1, 1, 2>(p, d, idx_mode, st) : launch_shape<1, 2, 2>(p, d, idx_mode, st);
     }
     return launch_shape<1, 2, 0>(p, d, idx_mode, st);
 }

@@ -422,8 +422,8 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator)
         rc = ensure_workspace(ctx, 2 * rows + cs);
         if (rc) return rc;
         p.ws_row_max = ctx->d_ws;
-        p.ws_row_sum = ctx->d_ws + rows;
-        p.ws_colsum = ctx->d_ws + 2 * rows;
+        p.ws_row_sum = p.ws_row_max + rows;
+        p.ws_colsum = p.ws_row_sum + rows;
     }
 
     const int herr = comparator ? launch_quantonly(p, a->d, ctx->variant, stream)

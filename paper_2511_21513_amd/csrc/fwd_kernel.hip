@@ -45,21 +45,28 @@ constexpr int NT = WAVES * 64;
 // query row) -- without the output accumulators it needs half the registers, so twice as many
 // waves per SIMD hide the LDS and MFMA latencies of the two ALU-light sweeps; 2 = sweep C only,
 // reading that workspace.
-template <int D, int RB, int KT, bool CAUSAL, int MODE, int PH>
-__global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (KT == 1 ? 3 : 2) : 1)) void fwd_kernel(const FwdParams p)
+// KS is the number of 32-key sub-tiles sweep C computes per step (KT: the whole staged tile at
+// once; 1: one sub-tile at a time, which needs fewer registers and so admits a third wave per SIMD).
+template <int D, int RB, int KT, bool CAUSAL, int MODE, int PH, int KS>
+__global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (KS == 1 ? 3 : 2) : 1)) void fwd_kernel(const FwdParams p)
 {
+    static_assert(KS == KT || KS == 1, "sweep C steps over whole tiles or single sub-tiles");
     constexpr int KB = D / 32;       // 32-wide blocks of the head dimension
     constexpr int CB = D / 32;       // 32-wide blocks of output channels
     constexpr int BK = 32 * KT;      // keys per tile
     constexpr int BQ = WAVES * RB * 32;
     constexpr int TILE = BK * D;     // bytes
-    constexpr int NCHUNK = TILE / 16;                // 16-byte chunks per tile
-    constexpr int CPT = (NCHUNK + NT - 1) / NT;      // chunks per thread per tile
-    static_assert(NCHUNK % NT == 0 || NCHUNK * 2 == NT, "tile must split over all or half of the threads");
-    static_assert(CB <= WAVES, "one wave per channel block accumulates the V column sums");
+    constexpr int NBLK = TILE / 1024;                // 1 KiB blocks per tile (one wave-wide 16-byte load each)
+    constexpr int JB = (NBLK + WAVES - 1) / WAVES;   // blocks per wave per tile
+    constexpr int CPR = D / 16;                      // 16-byte chunks per key row
+    constexpr int RPB = 1024 / D;                    // key rows per block
 
-    __shared__ __attribute__((aligned(16))) int8_t Ks[2][TILE];
-    __shared__ __attribute__((aligned(16))) int8_t Vs[2][TILE];
+    // Two buffers per operand, as separate arrays: the compiler tracks each direct-to-LDS load by
+    // the array it targets, so reads of one buffer need not wait for loads into the other.
+    __shared__ __attribute__((aligned(1024))) int8_t Ks0[TILE];
+    __shared__ __attribute__((aligned(1024))) int8_t Ks1[TILE];
+    __shared__ __attribute__((aligned(1024))) int8_t Vs0[PH == 1 ? 16 : TILE];
+    __shared__ __attribute__((aligned(1024))) int8_t Vs1[PH == 1 ? 16 : TILE];
     __shared__ uint32_t PT[WAVES][RB][32 * 32]; // [idx][row] per wave and row block
     __shared__ uint32_t lut_lds[8];
     __shared__ int32_t colsum[D];
@@ -95,64 +102,85 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     const int kmax = CAUSAL ? min(L, q0 + BQ) : L;
     const int ntiles = (kmax + BK - 1) / BK;
 
-    // ---- staging: global -> registers (issued a tile ahead) -> swizzled LDS.
-    // Thread-constant parts (key and chunk of each slot, global and LDS offsets) are computed once.
-    v4i stage_k[CPT], stage_v[CPT];
-    int st_key[CPT], st_goff_k[CPT], st_goff_v[CPT], st_lds_k[CPT], st_lds_v[CPT];
+    // ---- staging: global -> LDS directly (no registers, no LDS store instructions), a tile ahead.
+    // One wave-wide 16-byte load fills 1 KiB of LDS, lane i at byte 16 i: the lane's slot is key row
+    // i / CPR of the block at chunk position i % CPR, which under the XOR swizzle holds global chunk
+    // (i % CPR) ^ swz(key) -- so the swizzle is applied to the global address.
+    int dma_goff_k[JB], dma_goff_v[JB];
 #pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-        const int c = (tid + j * NT) % NCHUNK; // with half-size tiles the upper waves duplicate the lower ones' work
-        const int key = c / (D / 16), c16 = c % (D / 16);
-        st_key[j] = key;
-        st_goff_k[j] = key * (int)p.ks[2] + c16 * 16; // the host checked BK * stride < 2^31
-        st_goff_v[j] = key * (int)p.vs[2] + c16 * 16;
-        st_lds_k[j] = key * D + ((c16 ^ swz_k<D>(key)) << 4);
-        st_lds_v[j] = key * D + ((c16 ^ swz_v<D>(key)) << 4);
+    for (int j = 0; j < JB; ++j) {
+        const int key = (wave + WAVES * j) * RPB + lane / CPR, cp = lane % CPR;
+        dma_goff_k[j] = key * (int)p.ks[2] + ((cp ^ swz_k<D>(key)) << 4); // the host checked BK * stride < 2^31
+        dma_goff_v[j] = key * (int)p.vs[2] + ((cp ^ swz_v<D>(key)) << 4);
     }
-    // Loads are unconditional (rows past L read the first row of the tile instead and are zeroed when stored), so that
-    // nothing forces a wait on them before the tile's compute.
-    auto load_tile = [&](const int8_t *base, int64_t stride, const int (&goff)[CPT], int t, v4i (&st)[CPT]) {
+    // The loads go through a buffer descriptor that starts at the tile and ends with the last
+    // byte of key row L-1, so key rows at or past L come back as zeros from the range check.
+    auto dma_tile = [&](const int8_t *base, int64_t stride, const int (&goff)[JB], int t, int8_t *dst)
+                        __attribute__((always_inline)) {
         const int8_t *tb = base + (int64_t)t * BK * stride; // wave-uniform
+        const int64_t rem = (int64_t)(L - t * BK - 1) * stride + D;
+        const uint32_t nrec = rem > 0xffffffffll ? 0xffffffffu : (uint32_t)rem;
+#if defined(__HIP_DEVICE_COMPILE__) // the host pass has neither the descriptor type nor the builtins
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)tb, 0, (int)nrec, 0x00020000);
 #pragma unroll
-        for (int j = 0; j < CPT; ++j) {
-            const uint32_t off = (t * BK + st_key[j] < L) ? (uint32_t)goff[j] : 0u; // row t*BK exists
-            st[j] = *(const v4i *)(tb + off);
+        for (int j = 0; j < JB; ++j) {
+            const int blk = wave + WAVES * j;
+            if (NBLK % WAVES != 0 && blk >= NBLK) break;    // wave-uniform
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(dst + blk * 1024), 16,
+                                                     goff[j], 0, 0, 0);
+        }
+#else
+        (void)tb, (void)nrec, (void)goff, (void)dst;
+#endif
+    };
+    auto dma_k = [&](int t, int8_t *dst) __attribute__((always_inline)) { dma_tile(Kp, p.ks[2], dma_goff_k, t, dst); };
+    auto dma_v = [&](int t, int8_t *dst) __attribute__((always_inline)) { dma_tile(Vp, p.vs[2], dma_goff_v, t, dst); };
+    // One sweep over the key tiles: tile t+1 is requested before tile t is computed; the barrier at
+    // the end of a step (which waits for the wave's own loads first) publishes it and frees tile
+    // t's buffer.  Unrolled by two so that every buffer is named statically.
+    auto sweep = [&](auto with_v, auto body) __attribute__((always_inline)) {
+        constexpr bool WITH_V = decltype(with_v)::value;
+        dma_k(0, Ks0);
+        if (WITH_V) dma_v(0, Vs0);
+        __syncthreads();
+        for (int t = 0; t < ntiles; t += 2) {
+            if (t + 1 < ntiles) {
+                dma_k(t + 1, Ks1);
+                if (WITH_V) dma_v(t + 1, Vs1);
+            }
+            body(t, (const int8_t *)Ks0, (const int8_t *)Vs0);
+            __syncthreads();
+            if (t + 1 < ntiles) {
+                if (t + 2 < ntiles) {
+                    dma_k(t + 2, Ks0);
+                    if (WITH_V) dma_v(t + 2, Vs0);
+                }
+                body(t + 1, (const int8_t *)Ks1, (const int8_t *)Vs1);
+                __syncthreads();
+            }
         }
     };
-    auto load_k = [&](int t) { load_tile(Kp, p.ks[2], st_goff_k, t, stage_k); };
-    auto load_v = [&](int t) { load_tile(Vp, p.vs[2], st_goff_v, t, stage_v); };
-    // t is the tile the staged registers hold
-    auto store_tile = [&](int8_t *dst, const int (&loff)[CPT], int t, v4i (&st)[CPT]) {
-        if ((t + 1) * BK > L) { // wave-uniform: only the last tile can be ragged
-#pragma unroll
-            for (int j = 0; j < CPT; ++j)
-                if (t * BK + st_key[j] >= L) st[j] = v4i{0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int j = 0; j < CPT; ++j) *(v4i *)(dst + loff[j]) = st[j];
-    };
-    auto store_k = [&](int buf, int t) { store_tile(Ks[buf], st_lds_k, t, stage_k); };
-    auto store_v = [&](int buf, int t) { store_tile(Vs[buf], st_lds_v, t, stage_v); };
 
     // ---- S^T blocks of one tile: KT sub-tiles of 32 keys x RB row blocks, KB chained MFMAs each.
     // The chains are interleaved (kb outermost) so that consecutive MFMAs are independent.
     // All K fragments of the tile are requested before the first MFMA (the scheduling barrier keeps
     // the compiler from re-serialising read -> wait -> MFMA), so one LDS latency is paid per tile.
-    auto qk_tile = [&](int buf, v16i (&s)[KT][RB]) {
-        v4i kf[KB][KT];
+    auto qk_tile = [&](const int8_t *Kb, int st0, auto &s) __attribute__((always_inline)) {
+        constexpr int NS = (int)(sizeof(s) / sizeof(s[0]));
+        v4i kf[KB][NS];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
-            for (int st = 0; st < KT; ++st) {
-                const int key = 32 * st + n;
-                kf[kb][st] = *(const v4i *)(Ks[buf] + key * D + (((2 * kb + h) ^ swz_k<D>(key)) << 4));
+            for (int st = 0; st < NS; ++st) {
+                const int key = 32 * (st0 + st) + n;
+                kf[kb][st] = *(const v4i *)(Kb + key * D + (((2 * kb + h) ^ swz_k<D>(key)) << 4));
             }
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
-            for (int st = 0; st < KT; ++st) {
+            for (int st = 0; st < NS; ++st) {
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
                     s[st][rb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[kb][st], qf[rb][kb], s[st][rb], 0, 0, 0);
@@ -171,7 +199,7 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) mx[rb] = INT32_MIN;
 
-    auto tile_a = [&](auto masked_tag, int t, int buf) {
+    auto tile_a = [&](auto masked_tag, int t, const int8_t *Kb) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         v16i s[KT][RB];
 #pragma unroll
@@ -180,7 +208,7 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s[st][rb][i] = 0;
-        qk_tile(buf, s);
+        qk_tile(Kb, 0, s);
 #pragma unroll
         for (int st = 0; st < KT; ++st) {
 #pragma unroll
@@ -199,17 +227,10 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     };
 
     if constexpr (PH != 2) {
-        load_k(0);
-        store_k(0, 0);
-        __syncthreads();
-        for (int t = 0; t < ntiles; ++t) {
-            const int buf = t & 1;
-            if (t + 1 < ntiles) load_k(t + 1);
-            if (tile_is_full(t)) tile_a(std::false_type{}, t, buf);
-            else if (!tile_is_hidden(t)) tile_a(std::true_type{}, t, buf);
-            if (t + 1 < ntiles) store_k(buf ^ 1, t + 1);
-            __syncthreads();
-        }
+        sweep(std::false_type{}, [&](int t, const int8_t *Kb, const int8_t *) __attribute__((always_inline)) {
+            if (tile_is_full(t)) tile_a(std::false_type{}, t, Kb);
+            else if (!tile_is_hidden(t)) tile_a(std::true_type{}, t, Kb);
+        });
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) mx[rb] = max(mx[rb], __shfl_xor(mx[rb], 32));
     } else {
@@ -230,14 +251,14 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     // transposing read: lanes 2j, 2j+1 of a 16-lane group point at the two 8-byte halves of key
     // row j's 16 channels; lane i of the group receives channel i of the eight rows.
     const int tr_i = lane & 15, tr_g = (lane >> 4) & 1;
-    auto vt_frag = [&](int buf, int st, int cb) {
+    auto vt_frag = [&](const int8_t *Vb, int st, int cb) __attribute__((always_inline)) {
         v4i a;
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const int j = tr_i >> 1;
             const int key = 32 * st + 8 * (2 * r + (j >> 2)) + 4 * h + (j & 3);
             const int c16 = 2 * cb + tr_g;
-            const int8_t *ptr = Vs[buf] + key * D + ((c16 ^ swz_v<D>(key)) << 4) + 8 * (tr_i & 1);
+            const int8_t *ptr = Vb + key * D + ((c16 ^ swz_v<D>(key)) << 4) + 8 * (tr_i & 1);
             const v2i x = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3))) *)ptr);
             a[2 * r] = x[0];
             a[2 * r + 1] = x[1];
@@ -250,7 +271,7 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) sum[rb] = 0;
 
-    auto tile_b = [&](auto masked_tag, int t, int buf) {
+    auto tile_b = [&](auto masked_tag, int t, const int8_t *Kb) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         v16i s[KT][RB];
 #pragma unroll
@@ -259,7 +280,7 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s[st][rb][i] = 0;
-        qk_tile(buf, s); // s = A_hat - rowMax <= 0 for visible keys
+        qk_tile(Kb, 0, s);
 #pragma unroll
         for (int st = 0; st < KT; ++st) {
 #pragma unroll
@@ -291,17 +312,10 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     };
 
     if constexpr (PH != 2) {
-        load_k(0);
-        store_k(0, 0);
-        __syncthreads();
-        for (int t = 0; t < ntiles; ++t) {
-            const int buf = t & 1;
-            if (t + 1 < ntiles) load_k(t + 1);
-            if (tile_is_full(t)) tile_b(std::false_type{}, t, buf);
-            else if (!tile_is_hidden(t)) tile_b(std::true_type{}, t, buf);
-            if (t + 1 < ntiles) store_k(buf ^ 1, t + 1);
-            __syncthreads();
-        }
+        sweep(std::false_type{}, [&](int t, const int8_t *Kb, const int8_t *) __attribute__((always_inline)) {
+            if (tile_is_full(t)) tile_b(std::false_type{}, t, Kb);
+            else if (!tile_is_hidden(t)) tile_b(std::true_type{}, t, Kb);
+        });
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) sum[rb] += __shfl_xor(sum[rb], 32);
     }
@@ -365,18 +379,19 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     // latency is paid once per tile: S^T blocks; all probability lookups (in place, one per score)
     // followed by all V^T fragment reads; packing into MFMA B operands (LDS returns in order, so
     // the lookups land first while the fragments are still in flight).
-    auto tile_c = [&](auto masked_tag, int t, int buf, v4i (&pf)[KT][RB], v4i (&vf)[KT][CB]) {
+    auto tile_c = [&](auto masked_tag, int t, const int8_t *Kb, const int8_t *Vb, int st0, v4i (&pf)[KS][RB],
+                      v4i (&vf)[KS][CB]) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        v16i s[KT][RB];
+        v16i s[KS][RB];
 #pragma unroll
-        for (int st = 0; st < KT; ++st)
+        for (int st = 0; st < KS; ++st)
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s[st][rb][i] = 0;
-        qk_tile(buf, s);
+        qk_tile(Kb, st0, s);
 #pragma unroll
-        for (int st = 0; st < KT; ++st) {
+        for (int st = 0; st < KS; ++st) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
                 const uint32_t *pt = PT[wave][rb] + n;
@@ -388,15 +403,15 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
             }
         }
 #pragma unroll
-        for (int st = 0; st < KT; ++st)
+        for (int st = 0; st < KS; ++st)
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) vf[st][cb] = vt_frag(buf, st, cb);
+            for (int cb = 0; cb < CB; ++cb) vf[st][cb] = vt_frag(Vb, st0 + st, cb);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int st = 0; st < KT; ++st) {
+        for (int st = 0; st < KS; ++st) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                const int klo = t * BK + 32 * st, row = qw0 + 32 * rb + n;
+                const int klo = t * BK + 32 * (st0 + st), row = qw0 + 32 * rb + n;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     uint32_t pb4[4];
@@ -412,39 +427,29 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
         }
     };
 
-    load_k(0);
-    load_v(0);
-    store_k(0, 0);
-    store_v(0, 0);
-    __syncthreads();
-    for (int t = 0; t < ntiles; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < ntiles) {
-            load_k(t + 1);
-            load_v(t + 1);
-        }
-        // every wave walks every tile of the workgroup here: the column-sum correction assumes it
-        // (the P_hat.V_hat MFMAs follow in one place for both instantiations, so that the output
-        // accumulators have a single home)
-        v4i pf[KT][RB], vf[KT][CB];
-        if (tile_is_full(t)) tile_c(std::false_type{}, t, buf, pf, vf);
-        else tile_c(std::true_type{}, t, buf, pf, vf);
-        __builtin_amdgcn_sched_barrier(0);
+    // every wave walks every tile of the workgroup here: the column-sum correction assumes it
+    sweep(std::true_type{}, [&](int t, const int8_t *Kb, const int8_t *Vb) __attribute__((always_inline)) {
 #pragma unroll
-        for (int st = 0; st < KT; ++st) {
+        for (int st0 = 0; st0 < KT; st0 += KS) {
+            // (the P_hat.V_hat MFMAs follow in one place for both instantiations, so that the output
+            // accumulators have a single home)
+            v4i pf[KS][RB], vf[KS][CB];
+            // wave-uniform: every key of this step is visible to every row of this wave
+            const int khi = t * BK + 32 * (st0 + KS);
+            if (khi <= L && (!CAUSAL || khi - 1 <= qw0)) tile_c(std::false_type{}, t, Kb, Vb, st0, pf, vf);
+            else tile_c(std::true_type{}, t, Kb, Vb, st0, pf, vf);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
+            for (int st = 0; st < KS; ++st) {
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-                    o[rb][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[st][cb], pf[st][rb], o[rb][cb], 0, 0, 0);
+                for (int cb = 0; cb < CB; ++cb) {
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+                        o[rb][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[st][cb], pf[st][rb], o[rb][cb], 0, 0, 0);
+                }
             }
         }
-        if (t + 1 < ntiles) {
-            store_k(buf ^ 1, t + 1);
-            store_v(buf ^ 1, t + 1);
-        }
-        __syncthreads();
-    }
+    });
 
     // ================================================================= epilogue
     // colsum was written after sweep B; sweep C's barriers made it visible
@@ -514,28 +519,28 @@ int launch_colsum(const FwdParams &p, int d, int chunk, hipStream_t st)
     return (int)hipGetLastError();
 }
 
-template <int D, int RB, int KT, bool CAUSAL, int PH>
+template <int D, int RB, int KT, bool CAUSAL, int PH, int KS>
 int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
 {
     const dim3 grid((unsigned)fwd_grid_size(p.B, p.Hq, p.Hkv, p.n_qtiles)), block(NT);
     if (idx_mode == IDX_MAD24)
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24, PH>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24, PH, KS>), grid, block, 0, st, p);
     else if (idx_mode == IDX_MULHI24)
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MULHI24, PH>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MULHI24, PH, KS>), grid, block, 0, st, p);
     else if (idx_mode == IDX_FP32)
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP32, PH>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP32, PH, KS>), grid, block, 0, st, p);
     else
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_DIV, PH>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_DIV, PH, KS>), grid, block, 0, st, p);
     return (int)hipGetLastError();
 }
 
-template <int RB, int KT, int PH>
+template <int RB, int KT, int PH, int KS = KT>
 int launch_shape(const FwdParams &p, int d, int idx_mode, hipStream_t st)
 {
     if (d == 64)
-        return p.causal ? launch_mode<64, RB, KT, true, PH>(p, idx_mode, st) : launch_mode<64, RB, KT, false, PH>(p, idx_mode, st);
+        return p.causal ? launch_mode<64, RB, KT, true, PH, KS>(p, idx_mode, st) : launch_mode<64, RB, KT, false, PH, KS>(p, idx_mode, st);
     if (d == 128)
-        return p.causal ? launch_mode<128, RB, KT, true, PH>(p, idx_mode, st) : launch_mode<128, RB, KT, false, PH>(p, idx_mode, st);
+        return p.causal ? launch_mode<128, RB, KT, true, PH, KS>(p, idx_mode, st) : launch_mode<128, RB, KT, false, PH, KS>(p, idx_mode, st);
     return (int)hipErrorInvalidValue;
 }
 
@@ -554,14 +559,22 @@ int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *strea
     if (e != 0) return e;
     if (variant == 2) return launch_shape<2, 2, 0>(p, d, idx_mode, st);
     if (variant == 3) return launch_shape<1, 1, 0>(p, d, idx_mode, st);
-    if (variant >= 5 && variant <= 8) {
+    if (variant == 10) {
+        FwdParams pab = p;
+        pab.n_qtiles = (p.L + 255) / 256;
+        e = launch_shape<2, 2, 1>(pab, d, idx_mode, st);
+        if (e != 0) return e;
+        return launch_sweep_c(p, d, idx_mode, stream);
+    }
+    if (variant >= 5 && variant <= 9) {
         // sweeps A+B at high occupancy, then sweep C
         FwdParams pab = p;
         if (variant >= 7) pab.n_qtiles = (p.L + 255) / 256; // 64 query rows per wave in the first launch
         e = variant == 7 ? launch_shape<2, 1, 1>(pab, d, idx_mode, st)
-          : variant == 8 ? launch_shape<2, 2, 1>(pab, d, idx_mode, st)
+          : variant >= 8 ? launch_shape<2, 2, 1>(pab, d, idx_mode, st)
                          : launch_shape<1, 2, 1>(pab, d, idx_mode, st);
         if (e != 0) return e;
+        if (variant == 9) return launch_shape<1, 2, 2, 1>(p, d, idx_mode, st);
         return variant == 6 ? launch_shape<1, 1, 2>(p, d, idx_mode, st) : launch_shape<1, 2, 2>(p, d, idx_mode, st);
     }
     return launch_shape<1, 2, 0>(p, d, idx_mode, st);

@@ -547,7 +547,7 @@ int launch_shape(const FwdParams &p, int d, int idx_mode, hipStream_t st)
 } // namespace
 
 // variant 0/1: 32 query rows per wave (128 per workgroup); variant 2: 64 per wave (256).
-int fwd_rows_per_block(int variant) { return variant == 2 ? 256 : 128; }
+int fwd_rows_per_block(int variant) { return (variant == 2 || variant == 11) ? 256 : 128; }
 bool fwd_needs_workspace(int variant) { return variant != 4; }
 
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *stream)
@@ -559,12 +559,13 @@ int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *strea
     if (e != 0) return e;
     if (variant == 2) return launch_shape<2, 2, 0>(p, d, idx_mode, st);
     if (variant == 3) return launch_shape<1, 1, 0>(p, d, idx_mode, st);
-    if (variant == 10) {
+    if (variant == 10 || variant == 11) {
+        // sweeps A+B with 64 query rows per wave, then the software-pipelined sweep C with 32 / 64
         FwdParams pab = p;
         pab.n_qtiles = (p.L + 255) / 256;
         e = launch_shape<2, 2, 1>(pab, d, idx_mode, st);
         if (e != 0) return e;
-        return launch_sweep_c(p, d, idx_mode, stream);
+        return launch_sweep_c(p, d, idx_mode, variant == 10 ? 32 : 64, stream);
     }
     if (variant >= 5 && variant <= 9) {
         // sweeps A+B at high occupancy, then sweep C

@@ -50,7 +50,7 @@ struct FwdParams {
 // Launchers implemented in the .hip files.  Return a hipError_t cast to int.
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *stream);
 int launch_fwd_pipe(const FwdParams &p, int d, int idx_mode, void *stream);
-int launch_sweep_c(const FwdParams &p, int d, int idx_mode, void *stream);
+int launch_sweep_c(const FwdParams &p, int d, int idx_mode, int rows_per_wave, void *stream);
 int fwd_rows_per_block(int variant);
 bool fwd_needs_workspace(int variant);
 int launch_quantonly(const FwdParams &p, int d, int variant, void *stream);

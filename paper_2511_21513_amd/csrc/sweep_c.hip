@@ -4,24 +4,27 @@
 // by V_hat on the matrix cores and requantize (INT8 output).
 //
 // Same data layout and lane ownership as the generic forward kernel (transposed scores, one query
-// row per lane, 32 rows per wave, 4 waves per workgroup, XOR-swizzled K/V tiles in LDS filled by
-// direct global->LDS loads).  What differs is the instruction schedule.  The generic kernel runs a
+// row per lane, XOR-swizzled K/V tiles in LDS filled by direct global->LDS loads); a wave owns RB
+// blocks of 32 query rows.  What differs is the instruction schedule.  The generic kernel runs a
 // tile as phases (scores, lookups, pack, P.V), so the matrix core idles during the vector phases
-// and the other way round; two waves per SIMD do not hide that.  Here the key axis is walked in
-// steps of 32 keys as a software pipeline inside each wave.  Step j issues, in this order,
-//     one MFMA, then the vector work of two scores, one MFMA, ...:
-//   MFMAs:   the KB chained MFMAs of the scores of sub-tile j+1, then the CB MFMAs P.V of sub-tile j-1
+// and the other way round.  Here the key axis is walked in steps of 32 keys as a software
+// pipeline inside each wave, meant to keep one wave per SIMD busy on its own (512 registers, the
+// output accumulators in the accumulator half).  Step j issues
+//     one MFMA, then the vector work of EPS scores, one MFMA, ...:
+//   MFMAs:   the scores of sub-tile j+1 (KB chained MFMAs per row block), then P.V of sub-tile j-1
 //   vector:  clip/index/table lookup (issued, not awaited) of sub-tile j's scores, and the packing
-//            of sub-tile j-1's looked-up probability bytes into the MFMA operand (before its P.V)
+//            into MFMA operands of the probability bytes looked up half a step earlier
 //   LDS:     K fragments of sub-tile j+2 (once the current ones are consumed), V^T fragments of
 //            sub-tile j (after the last P.V of j-1 has issued)
 // so every MFMA runs under independent vector instructions of the same wave, every LDS result
-// has a whole step to arrive, and nothing waits on what it has just issued.  Scheduling barriers
-// pin that order.
+// has half a step or more to arrive, and nothing waits on what it has just issued.  Scheduling
+// barriers pin that order.
 //
-// Tiles are 64 keys (two steps), double buffered per operand.  K is needed one tile before V
-// (scores of tile T+1 are computed while tile T's probabilities meet V), so at the top of
-// iteration T the loads of K tile T+2 and V tile T+1 are issued; one barrier per iteration.
+// Tiles are NSUB sub-tiles (64 or 128 keys), double buffered per operand; one barrier per tile.
+// The K fragments are read two sub-tiles ahead of the V^T fragments.  K tiles are cut NSUB - 2
+// sub-tiles earlier than V tiles (K tile t covers sub-tiles [NSUB (t-1) + 2, NSUB t + 2)), so that
+// iteration T reads exactly K tile T+1 and V tile T, and at its top requests K tile T+2 and V
+// tile T+1 into the buffers that were read an iteration ago.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -37,29 +40,32 @@ namespace {
 constexpr int WAVES = 4;
 constexpr int NT = WAVES * 64;
 
-template <int D, bool CAUSAL, int MODE>
-__global__ __launch_bounds__(NT, 1) void sweep_c_kernel(const FwdParams p)
+template <int D, int RB, bool CAUSAL, int MODE>
+__global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdParams p)
 {
     constexpr int KB = D / 32;       // 32-wide blocks of the head dimension
     constexpr int CB = D / 32;       // 32-wide blocks of output channels
-    constexpr int BK = 64;           // keys per tile: two pipeline steps
-    constexpr int BQ = WAVES * 32;
+    constexpr int NSUB = RB == 1 ? 2 : 4; // sub-tiles (pipeline steps) per tile; LDS for two workgroups per CU when RB = 1
+    constexpr int KSHIFT = NSUB - 2; // K tiles start this many sub-tiles before V tiles (see above)
+    constexpr int BK = 32 * NSUB;    // keys per tile
+    constexpr int BQ = WAVES * RB * 32;
     constexpr int TILE = BK * D;     // bytes
     constexpr int SUB = 32 * D;      // bytes of a 32-key sub-tile
     constexpr int NBLK = TILE / 1024;
     constexpr int JB = (NBLK + WAVES - 1) / WAVES;
     constexpr int CPR = D / 16;
     constexpr int RPB = 1024 / D;
-    constexpr int NSLOT = KB + CB;   // MFMAs per step
-    constexpr int EPS = 16 / NSLOT;  // scores handled after each MFMA
-    constexpr int GPS = 4 / KB;      // operand registers packed after each of the first KB MFMAs
-    static_assert(16 % NSLOT == 0 && 4 % KB == 0, "vector work must split evenly over the MFMA slots");
+    constexpr int NSLOT = RB * (KB + CB); // MFMAs per step
+    constexpr int NEL = 16 * RB;          // scores per lane and step
+    constexpr int EPS = NEL / NSLOT;      // scores handled after each MFMA
+    constexpr int HALF = NSLOT / 2;       // = RB * KB: P.V of sub-tile j-1 starts when its operands are complete
+    static_assert(EPS == 2 || EPS == 4, "a slot handles half an operand register or a whole one");
 
     __shared__ __attribute__((aligned(1024))) int8_t Ks0[TILE];
     __shared__ __attribute__((aligned(1024))) int8_t Ks1[TILE];
     __shared__ __attribute__((aligned(1024))) int8_t Vs0[TILE];
     __shared__ __attribute__((aligned(1024))) int8_t Vs1[TILE];
-    __shared__ uint32_t PT[WAVES][32 * 32]; // [idx][row] per wave
+    __shared__ uint32_t PT[WAVES][RB][32 * 32]; // [idx][row] per wave and row block
     __shared__ uint32_t lut_lds[8];
     __shared__ int32_t colsum[D];
 
@@ -72,24 +78,27 @@ __global__ __launch_bounds__(NT, 1) void sweep_c_kernel(const FwdParams p)
     const int L = p.L;
     const uint32_t top = (uint32_t)p.top;
 
-    const int q0 = qt * BQ, qw0 = q0 + wave * 32;
-    const int row = qw0 + n; // this lane's query row
+    const int q0 = qt * BQ, qw0 = q0 + wave * (RB * 32);
     const int8_t *Qp = p.q + (int64_t)b * p.qs[0] + (int64_t)hq * p.qs[1];
     const int8_t *Kp = p.k + (int64_t)b * p.ks[0] + (int64_t)kvh * p.ks[1];
     const int8_t *Vp = p.v + (int64_t)b * p.vs[0] + (int64_t)kvh * p.vs[1];
 
     if (tid < 8) lut_lds[tid] = p.lut[tid];
 
-    // Q fragments: row qw0 + n, bytes [32 kb + 16 h, +16)
-    v4i qf[KB];
+    // Q fragments: row block rb, row qw0 + 32 rb + n, bytes [32 kb + 16 h, +16)
+    v4i qf[RB][KB];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {
-        qf[kb] = v4i{0, 0, 0, 0};
-        if (row < L) qf[kb] = *(const v4i *)(Qp + (int64_t)row * p.qs[2] + kb * 32 + h * 16);
+    for (int rb = 0; rb < RB; ++rb) {
+        const int row = qw0 + 32 * rb + n;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            qf[rb][kb] = v4i{0, 0, 0, 0};
+            if (row < L) qf[rb][kb] = *(const v4i *)(Qp + (int64_t)row * p.qs[2] + kb * 32 + h * 16);
+        }
     }
 
     const int kmax = CAUSAL ? min(L, q0 + BQ) : L;
-    const int ntiles = (kmax + BK - 1) / BK;
+    const int ntiles = (kmax + BK - 1) / BK; // iterations = V tiles; K tiles 0..ntiles are touched
 
     // ---- staging: direct global -> LDS loads; the XOR swizzle is applied to the global address
     // (lane i of a wave-wide 16-byte load lands at byte 16 i of its 1 KiB block).
@@ -100,41 +109,52 @@ __global__ __launch_bounds__(NT, 1) void sweep_c_kernel(const FwdParams p)
         dma_goff_k[j] = key * (int)p.ks[2] + ((cp ^ swz_k<D>(key)) << 4); // the host checked BK * stride < 2^31
         dma_goff_v[j] = key * (int)p.vs[2] + ((cp ^ swz_v<D>(key)) << 4);
     }
-    // The loads go through a buffer descriptor that starts at the tile and ends with the last
-    // byte of key row L-1, so key rows at or past L come back as zeros from the range check.
-    auto dma_tile = [&](const int8_t *base, int64_t stride, const int (&goff)[JB], int t, int8_t *dst)
+    // The loads go through a buffer descriptor that starts at the tile's first key row and ends
+    // with the last byte of key row L-1, so key rows at or past L come back as zeros from the range
+    // check.  Blocks below first_blk are skipped (the part of K tile 0 that lies before key 0).
+    auto dma_tile = [&](const int8_t *base, int64_t stride, const int (&goff)[JB], int key0, int first_blk, int8_t *dst)
                         __attribute__((always_inline)) {
-        const int8_t *tb = base + (int64_t)t * BK * stride; // wave-uniform
-        const int64_t rem = (int64_t)(L - t * BK - 1) * stride + D;
-        const uint32_t nrec = rem > 0xffffffffll ? 0xffffffffu : (uint32_t)rem;
+        const int8_t *tb = base + (int64_t)key0 * stride; // wave-uniform
+        const int64_t rem = (int64_t)(L - key0 - 1) * stride + D;
+        const uint32_t nrec = rem <= 0 ? 0u : (rem > 0xffffffffll ? 0xffffffffu : (uint32_t)rem); // 0: all of it past L
 #if defined(__HIP_DEVICE_COMPILE__) // the host pass has neither the descriptor type nor the builtins
         const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)tb, 0, (int)nrec, 0x00020000);
 #pragma unroll
         for (int j = 0; j < JB; ++j) {
             const int blk = wave + WAVES * j;
-            if (NBLK % WAVES != 0 && blk >= NBLK) break;    // wave-uniform
+            if (blk < first_blk || (NBLK % WAVES != 0 && blk >= NBLK)) continue; // wave-uniform
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(dst + blk * 1024), 16,
                                                      goff[j], 0, 0, 0);
         }
 #else
-        (void)tb, (void)nrec, (void)goff, (void)dst;
+        (void)tb, (void)nrec, (void)goff, (void)dst, (void)first_blk;
 #endif
     };
-    auto dma_k = [&](int t, int8_t *dst) __attribute__((always_inline)) { dma_tile(Kp, p.ks[2], dma_goff_k, t, dst); };
-    auto dma_v = [&](int t, int8_t *dst) __attribute__((always_inline)) { dma_tile(Vp, p.vs[2], dma_goff_v, t, dst); };
+    // K tile t starts KSHIFT sub-tiles before V tile t; the rows of K tile 0 that would lie before
+    // key 0 are not requested
+    auto dma_k = [&](int t, int8_t *dst) __attribute__((always_inline)) {
+        const int key0 = (t * NSUB - KSHIFT) * 32;
+        dma_tile(Kp, p.ks[2], dma_goff_k, key0, key0 < 0 ? -key0 / RPB : 0, dst);
+    };
+    auto dma_v = [&](int t, int8_t *dst) __attribute__((always_inline)) { dma_tile(Vp, p.vs[2], dma_goff_v, t * BK, 0, dst); };
 
     dma_k(0, Ks0);
     dma_v(0, Vs0);
-    if (ntiles > 1) dma_k(1, Ks1);
+    dma_k(1, Ks1);
 
-    // ---- per-row state from the first launch, probability table, column sums of V
-    const int mx = row < L ? p.ws_row_max[(int64_t)bh * L + row] : 0;
-    uint32_t sum = row < L ? (uint32_t)p.ws_row_sum[(int64_t)bh * L + row] : 0u;
-    if (sum == 0) sum = 1; // only rows beyond L; never stored
-    RowIndex<MODE> ri;
-    ri.init(hp, mx, top);
-    if (p.dbg_row_max && h == 0 && row < L) p.dbg_row_max[(int64_t)bh * L + row] = mx;
-    if (p.dbg_row_sum && h == 0 && row < L) p.dbg_row_sum[(int64_t)bh * L + row] = (int32_t)sum;
+    // ---- per-row state from the first launch, probability tables, column sums of V
+    RowIndex<MODE> ri[RB];
+    uint32_t sum[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int row = qw0 + 32 * rb + n;
+        const int mx = row < L ? p.ws_row_max[(int64_t)bh * L + row] : 0;
+        sum[rb] = row < L ? (uint32_t)p.ws_row_sum[(int64_t)bh * L + row] : 0u;
+        if (sum[rb] == 0) sum[rb] = 1; // only rows beyond L; never stored
+        ri[rb].init(hp, mx, top);
+        if (p.dbg_row_max && h == 0 && row < L) p.dbg_row_max[(int64_t)bh * L + row] = mx;
+        if (p.dbg_row_sum && h == 0 && row < L) p.dbg_row_sum[(int64_t)bh * L + row] = (int32_t)sum[rb];
+    }
 
     // Column sums of V over every key the steps below cover (keys up to the end of this query tile
     // under the causal mask, else all): the correction for feeding the probabilities to the signed
@@ -147,23 +167,26 @@ __global__ __launch_bounds__(NT, 1) void sweep_c_kernel(const FwdParams p)
         for (int c = 0; c < nchunk; ++c) acc += cp[(int64_t)c * D];
         colsum[tid] = acc;
     }
-    __syncthreads(); // LUT_hat, K(0), V(0), K(1) are in LDS
+    __syncthreads(); // LUT_hat, K tiles 0 and 1, V tile 0 are in LDS
 
     // per-row probability table: PT[idx] = round(255 * LUT_hat[idx] / sum) - 128 as a byte
     {
         const uint8_t *lut_b = (const uint8_t *)lut_lds;
-        uint32_t *pt = PT[wave];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int kidx = 16 * h + j;
-            const uint32_t e = lut_b[kidx];
-            const uint32_t pr = (510u * e + sum) / (2u * sum);
-            pt[kidx * 32 + n] = (pr ^ 0x80u) & 0xffu;
+        for (int rb = 0; rb < RB; ++rb) {
+            uint32_t *ptw = PT[wave][rb];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int kidx = 16 * h + j;
+                const uint32_t e = lut_b[kidx];
+                const uint32_t pr = (510u * e + sum[rb]) / (2u * sum[rb]);
+                ptw[kidx * 32 + n] = (pr ^ 0x80u) & 0xffu;
+            }
         }
     }
-    const uint32_t *pt = PT[wave] + n;
+    const uint32_t *pt = PT[wave][0] + n; // row block rb: + 1024 rb
 
-    // ---- LDS read addresses (lane constants; sub-tile and buffer go into immediate offsets)
+    // ---- LDS read addresses (lane constants; the sub-tile is added per pair of steps)
     int kf_off[KB], vf_off[CB];
     {
         const int sw = swz_k<D>(n); // equal for keys n and n + 32
@@ -188,150 +211,197 @@ __global__ __launch_bounds__(NT, 1) void sweep_c_kernel(const FwdParams p)
             vf[cb] = v4i{x0[0], x0[1], x1[0], x1[1]};
         }
     };
-    auto visible = [&](int key) { return key < L && (!CAUSAL || key <= row); };
+    auto visible = [&](int key, int rb) { return key < L && (!CAUSAL || key <= qw0 + 32 * rb + n); };
 
     // ---- pipeline state
-    v16i o[CB];
+    v16i o[RB][CB];
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) o[cb][i] = 0;
-    v4i kf[KB], vf[CB], pf;
-    v16i sA, sB;          // raw scores of the sub-tile in flight / being accumulated
-    uint32_t lA[16], lB[16]; // looked-up probability bytes (xor 0x80) of a sub-tile
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[rb][cb][i] = 0;
+    v4i kf[KB], vf[CB];
+    v4i pfA[RB], pfB[RB];      // MFMA operands of the probabilities of an even / odd sub-tile
+    v16i sA[RB], sB[RB];       // raw scores of the sub-tile in flight / being accumulated
+    uint32_t lA[NEL], lB[NEL]; // looked-up probability bytes (xor 0x80); only half a step's worth is live
 
-    // packs the looked-up bytes of sub-tile jp into operand register g
-    auto pack = [&](auto masked_tag, int jp, const uint32_t (&l)[16], int g) __attribute__((always_inline)) {
+    // Packs the looked-up bytes of scores [w0, w0 + EPS) (w = 16 rb + e) of sub-tile jp.
+    auto pack = [&](auto masked_tag, int jp, const uint32_t (&l)[NEL], int w0, v4i (&pf)[RB]) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        uint32_t b4[4];
+        const int rb = w0 / 16, e0 = w0 % 16, g = e0 / 4;
+        uint32_t bt[EPS];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            b4[r] = l[4 * g + r];
-            if (MASKED) b4[r] = visible(32 * jp + acc_key(4 * g + r, h)) ? b4[r] : 0x80u;
+        for (int r = 0; r < EPS; ++r) {
+            bt[r] = l[w0 + r];
+            if (MASKED) bt[r] = visible(32 * jp + acc_key(e0 + r, h), rb) ? bt[r] : 0x80u;
         }
-        pf[g] = (int)(((b4[1] << 8) | b4[0]) | (((b4[3] << 8) | b4[2]) << 16));
+        if (EPS == 4) {
+            pf[rb][g] = (int)(((bt[1] << 8) | bt[0]) | (((bt[3 % EPS] << 8) | bt[2 % EPS]) << 16));
+        } else {
+            const uint32_t pair = (bt[1] << 8) | bt[0];
+            pf[rb][g] = (e0 % 4 == 0) ? (int)pair : (int)((uint32_t)pf[rb][g] | (pair << 16));
+        }
     };
 
     // One pipeline step (see the head of the file).  sc: scores of sub-tile j; sn: receives the
-    // scores of sub-tile j+1; lp: lookups of sub-tile j-1; lc: receives the lookups of sub-tile j.
-    // On entry kf holds the K fragments of sub-tile j+1 and vf the V^T fragments of sub-tile j-1.
-    auto step = [&](auto masked_tag, int j, const int8_t *Knext, const int8_t *Vcur, const v16i &sc, v16i &sn,
-                    const uint32_t (&lp)[16], uint32_t (&lc)[16]) __attribute__((always_inline)) {
+    // scores of sub-tile j+1; lc / pfc: lookups and operands of sub-tile j; lp / pfp: of sub-tile j-1.
+    // A score looked up after MFMA slot s is packed HALF slots later, so only half a step's lookups
+    // are in flight and the packing never waits for what was just issued.  On entry kf holds the K
+    // fragments of sub-tile j+1 and vf the V^T fragments of sub-tile j-1.
+    auto step = [&](auto masked_tag, int j, const int8_t *Knext, const int8_t *Vcur, const v16i (&sc)[RB], v16i (&sn)[RB],
+                    const uint32_t (&lp)[NEL], uint32_t (&lc)[NEL], v4i (&pfp)[RB], v4i (&pfc)[RB]) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
 #pragma unroll
         for (int sl = 0; sl < NSLOT; ++sl) {
-            if (sl == 0) sn = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[0], qf[0], v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, 0, 0, 0);
-            else if (sl < KB) sn = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[sl], qf[sl], sn, 0, 0, 0);
-            else o[sl - KB] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[sl - KB], pf, o[sl - KB], 0, 0, 0);
+            if (sl < HALF) {
+                const int kb = sl / RB, rb = sl % RB;
+                if (kb == 0)
+                    sn[rb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[0], qf[rb][0], v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, 0, 0, 0);
+                else
+                    sn[rb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[kb], qf[rb][kb], sn[rb], 0, 0, 0);
+            } else {
+                const int cb = (sl - HALF) / RB, rb = (sl - HALF) % RB;
+                o[rb][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[cb], pfp[rb], o[rb][cb], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
+            if (sl < HALF) pack(masked_tag, j - 1, lp, (sl + HALF) * EPS, pfp);
+            else pack(masked_tag, j, lc, (sl - HALF) * EPS, pfc);
 #pragma unroll
-            for (int e = sl * EPS; e < (sl + 1) * EPS; ++e) {
+            for (int w = sl * EPS; w < (sl + 1) * EPS; ++w) {
+                const int rb = w / 16, e = w % 16;
                 // hidden keys may exceed the row max
-                const int c = MASKED ? min(max(sc[e], ri.bound), ri.mx) : max(sc[e], ri.bound);
-                lc[e] = pt[ri(c) * 32];
+                const int c = MASKED ? min(max(sc[rb][e], ri[rb].bound), ri[rb].mx) : max(sc[rb][e], ri[rb].bound);
+                lc[w] = pt[rb * 1024 + ri[rb](c) * 32];
             }
-            if (sl < KB) {
-#pragma unroll
-                for (int g = sl * GPS; g < (sl + 1) * GPS; ++g) pack(masked_tag, j - 1, lp, g);
-            }
-            if (sl == KB - 1) read_kf(Knext, kf); // the scores' MFMAs have all issued
+            if (sl == HALF - 1) read_kf(Knext, kf); // the scores' MFMAs have all issued
             if (sl == NSLOT - 1) read_vf(Vcur, vf);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // One iteration = tile T: its two sub-tiles' lookups, the scores of tile T+1's sub-tiles.
-    // PAR = T & 1 names the buffers statically: K(T+1) is in Ks[PAR^1], V(T) in Vs[PAR].
-    auto iteration = [&](auto masked_tag, auto par_tag, int T) __attribute__((always_inline)) {
-        constexpr int PAR = decltype(par_tag)::value;
-        int8_t *Kdma = PAR ? Ks1 : Ks0;             // K(T+2) replaces K(T), consumed an iteration ago
-        int8_t *Vdma = PAR ? Vs0 : Vs1;             // V(T+1) replaces V(T-1)
-        const int8_t *Krd = PAR ? Ks0 : Ks1;
-        const int8_t *Vrd = PAR ? Vs1 : Vs0;
-        if (T + 2 < ntiles) dma_k(T + 2, Kdma);
+    // One iteration = V tile T: the lookups of its NSUB sub-tiles, the scores of the NSUB sub-tiles
+    // two further on (K tile T+1).  With PAR = T & 1: K tile T+2 replaces K tile T (read an iteration
+    // ago) in Ks[PAR], V tile T+1 replaces V tile T-1 in Vs[PAR^1]; K tile T+1 is read from Ks[PAR^1]
+    // and V tile T from Vs[PAR].
+    auto iteration = [&](auto masked_tag, int T, int8_t *Kdma, int8_t *Vdma, const int8_t *Krd, const int8_t *Vrd)
+                         __attribute__((always_inline)) {
+        if (T + 2 <= ntiles) dma_k(T + 2, Kdma);
         if (T + 1 < ntiles) dma_v(T + 1, Vdma);
-        step(masked_tag, 2 * T, Krd, Vrd, sA, sB, lB, lA);
-        step(masked_tag, 2 * T + 1, Krd + SUB, Vrd + SUB, sB, sA, lA, lB);
+#pragma unroll 1
+        for (int u = 0; u < NSUB; u += 2) {
+            step(masked_tag, NSUB * T + u, Krd + u * SUB, Vrd + u * SUB, sA, sB, lB, lA, pfB, pfA);
+            step(masked_tag, NSUB * T + u + 1, Krd + (u + 1) * SUB, Vrd + (u + 1) * SUB, sB, sA, lA, lB, pfA, pfB);
+        }
         __syncthreads();
     };
 
-    // ---- prologue: scores of sub-tile 0, fragments of sub-tile 1; an empty "sub-tile -1"
-    read_kf(Ks0, kf);
-    sA = v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    // ---- prologue: scores of sub-tile 0, fragments of sub-tile 1 (the last two sub-tiles of K tile 0);
+    // an empty "sub-tile -1"
+    read_kf(Ks0 + KSHIFT * SUB, kf);
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) sA = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[kb], qf[kb], sA, 0, 0, 0);
+    for (int rb = 0; rb < RB; ++rb) {
+        sA[rb] = v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) sA[rb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[kb], qf[rb][kb], sA[rb], 0, 0, 0);
+    }
     __builtin_amdgcn_sched_barrier(0);
-    read_kf(Ks0 + SUB, kf);
+    read_kf(Ks0 + (KSHIFT + 1) * SUB, kf);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) lB[i] = 0; // operand bytes 0 = probability 128 - 128: adds nothing
+    for (int i = 0; i < NEL; ++i) lB[i] = 0; // operand bytes 0 = probability 128 - 128: adds nothing
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) vf[cb] = v4i{0, 0, 0, 0};
-    pf = v4i{0, 0, 0, 0};
-    __syncthreads(); // every wave has read K(0) before iteration 0 overwrites it with K(2)
-
-    // iterations whose two sub-tiles are fully visible to this wave need no masks (wave-uniform)
-    const int nfull_sub = CAUSAL ? min(L / 32, (qw0 + 1) / 32) : L / 32;
-    const int nhot = min(nfull_sub / 2, ntiles);
-    for (int T = 0; T < ntiles; T += 2) {
-        if (T < nhot) iteration(std::false_type{}, std::integral_constant<int, 0>{}, T);
-        else iteration(std::true_type{}, std::integral_constant<int, 0>{}, T);
-        if (T + 1 < ntiles) {
-            if (T + 1 < nhot) iteration(std::false_type{}, std::integral_constant<int, 1>{}, T + 1);
-            else iteration(std::true_type{}, std::integral_constant<int, 1>{}, T + 1);
-        }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        pfA[rb] = v4i{0, 0, 0, 0};
+        pfB[rb] = v4i{0, 0, 0, 0};
     }
-    // ---- drain: the last sub-tile's probabilities meet V (its lookups are in lB, its V^T in vf)
+    __syncthreads(); // every wave has read K tile 0 before iteration 0 overwrites it with K tile 2
+
+    // Iterations whose sub-tiles are all fully visible to this wave need no masks (wave-uniform
+    // count).  They run in pairs in a loop of their own, every buffer named statically (the compiler
+    // then knows which direct-to-LDS load a fragment read depends on) and no branch inside the body;
+    // the few remaining iterations take the masked code with the buffers chosen at run time.
+    const int nfull_sub = CAUSAL ? min(L / 32, (qw0 + 1) / 32) : L / 32;
+    const int nhot = min(nfull_sub / NSUB, ntiles);
+    int T = 0;
+    for (; T + 2 <= nhot; T += 2) {
+        iteration(std::false_type{}, T, Ks0, Vs1, Ks1, Vs0);
+        iteration(std::false_type{}, T + 1, Ks1, Vs0, Ks0, Vs1);
+    }
+#pragma unroll 1
+    for (; T < ntiles; ++T) {
+        const bool odd = T & 1;
+        iteration(std::true_type{}, T, odd ? Ks1 : Ks0, odd ? Vs0 : Vs1, odd ? Ks0 : Ks1, odd ? Vs1 : Vs0);
+    }
+    // ---- drain: the second half of the last sub-tile's lookups (in lB) is packed, then its
+    // probabilities meet V (V^T fragments in vf)
 #pragma unroll
-    for (int g = 0; g < 4; ++g) pack(std::true_type{}, 2 * ntiles - 1, lB, g);
+    for (int sl = 0; sl < HALF; ++sl) pack(std::true_type{}, NSUB * ntiles - 1, lB, (sl + HALF) * EPS, pfB);
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[cb], pf, o[cb], 0, 0, 0);
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) o[rb][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[cb], pfB[rb], o[rb][cb], 0, 0, 0);
 
     // ================================================================= epilogue (Sec. 3.2: requantization)
-    if (row >= L) return;
-    int8_t *Op = p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)row * p.os[2];
-    const int64_t half = 1ll << (hp.rq_shift - 1);
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
+    for (int rb = 0; rb < RB; ++rb) {
+        const int row = qw0 + 32 * rb + n;
+        if (row >= L) continue;
+        int8_t *Op = p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)row * p.os[2];
+        const int64_t half = 1ll << (hp.rq_shift - 1);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int ch0 = cb * 32 + 8 * g + 4 * h;
-            uint32_t packed = 0;
+        for (int cb = 0; cb < CB; ++cb) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int32_t acc = o[cb][4 * g + r] + 128 * colsum[ch0 + r];
-                if (p.dbg_acc) p.dbg_acc[((int64_t)bh * L + row) * D + ch0 + r] = acc;
-                int64_t v = ((int64_t)acc * hp.rq_mult + half) >> hp.rq_shift;
-                v = v > 127 ? 127 : (v < -127 ? -127 : v);
-                packed |= ((uint32_t)(int)v & 0xffu) << (8 * r);
+            for (int g = 0; g < 4; ++g) {
+                const int ch0 = cb * 32 + 8 * g + 4 * h;
+                uint32_t packed = 0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int32_t acc = o[rb][cb][4 * g + r] + 128 * colsum[ch0 + r];
+                    if (p.dbg_acc) p.dbg_acc[((int64_t)bh * L + row) * D + ch0 + r] = acc;
+                    int64_t v = ((int64_t)acc * hp.rq_mult + half) >> hp.rq_shift;
+                    v = v > 127 ? 127 : (v < -127 ? -127 : v);
+                    packed |= ((uint32_t)(int)v & 0xffu) << (8 * r);
+                }
+                *(uint32_t *)(Op + ch0) = packed;
             }
-            *(uint32_t *)(Op + ch0) = packed;
         }
     }
 }
 
-template <int D, bool CAUSAL>
+template <int D, int RB, bool CAUSAL>
 int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
 {
     const dim3 grid((unsigned)fwd_grid_size(p.B, p.Hq, p.Hkv, p.n_qtiles)), block(NT);
     if (idx_mode == IDX_MAD24)
-        hipLaunchKernelGGL((sweep_c_kernel<D, CAUSAL, IDX_MAD24>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_MAD24>), grid, block, 0, st, p);
     else if (idx_mode == IDX_MULHI24)
-        hipLaunchKernelGGL((sweep_c_kernel<D, CAUSAL, IDX_MULHI24>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_MULHI24>), grid, block, 0, st, p);
     else if (idx_mode == IDX_FP32)
-        hipLaunchKernelGGL((sweep_c_kernel<D, CAUSAL, IDX_FP32>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_FP32>), grid, block, 0, st, p);
     else
-        hipLaunchKernelGGL((sweep_c_kernel<D, CAUSAL, IDX_DIV>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_DIV>), grid, block, 0, st, p);
     return (int)hipGetLastError();
+}
+
+template <int RB>
+int launch_rb(const FwdParams &p, int d, int idx_mode, hipStream_t st)
+{
+    if (d == 64) return p.causal ? launch_mode<64, RB, true>(p, idx_mode, st) : launch_mode<64, RB, false>(p, idx_mode, st);
+    if (d == 128) return p.causal ? launch_mode<128, RB, true>(p, idx_mode, st) : launch_mode<128, RB, false>(p, idx_mode, st);
+    return (int)hipErrorInvalidValue;
 }
 
 } // namespace
 
-// p.n_qtiles must count tiles of 128 query rows; p.ws_row_max / ws_row_sum / ws_colsum filled.
-int launch_sweep_c(const FwdParams &p, int d, int idx_mode, void *stream)
+// rows_per_wave is 32 or 64; p.n_qtiles must count tiles of 4 * rows_per_wave query rows, and the
+// V chunk sums in p.ws_colsum must be over chunks of as many keys; p.ws_row_max / ws_row_sum filled.
+int launch_sweep_c(const FwdParams &p, int d, int idx_mode, int rows_per_wave, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    if (d == 64) return p.causal ? launch_mode<64, true>(p, idx_mode, st) : launch_mode<64, false>(p, idx_mode, st);
-    if (d == 128) return p.causal ? launch_mode<128, true>(p, idx_mode, st) : launch_mode<128, false>(p, idx_mode, st);
+    if (rows_per_wave == 32) return launch_rb<1>(p, d, idx_mode, st);
+    if (rows_per_wave == 64) return launch_rb<2>(p, d, idx_mode, st);
     return (int)hipErrorInvalidValue;
 }
 

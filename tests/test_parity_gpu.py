@@ -25,7 +25,7 @@ def torch_mod():
 # 5 / 6 = two launches (sweeps A+B at high occupancy, then sweep C with 64- / 32-key tiles);
 # 7 / 8 = two launches, the first with 64 query rows per wave and 32- / 64-key tiles; 9 = as 8
 # with sweep C stepping through 32-key halves of its 64-key tiles
-@pytest.fixture(scope="module", params=[0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10], ids=lambda v: f"variant{v}")
+@pytest.fixture(scope="module", params=[0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11], ids=lambda v: f"variant{v}")
 def ia(torch_mod, request):
     from paper_2511_21513_amd import binding
 

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libintattn.so")
-SOURCES = ["api.cpp", "fwd_kernel.hip", "fwd_pipe.hip", "sweep_c.hip", "quantonly_kernel.hip"]
+SOURCES = ["api.cpp", "fwd_kernel.hip", "sweep_ab.hip", "sweep_c.hip", "quantonly_kernel.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",

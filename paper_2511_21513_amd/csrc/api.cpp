@@ -261,7 +261,7 @@ int validate(intattn_ctx *ctx, const intattn_args *a)
         if (s[2] < a->d) return fail(ctx, INTATTN_ERR_INVALID_ARG, "the L stride must be at least d");
         if (s[2] > (1 << 24)) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "the L stride must not exceed 2^24 bytes");
     }
-    const int64_t rows_per_block = fwd_rows_per_block(ctx->variant);
+    const int64_t rows_per_block = fwd_rows_per_block(fwd_choose_variant(ctx->variant, a->B, a->Hq, a->L));
     const int64_t n_qtiles = (a->L + rows_per_block - 1) / rows_per_block;
     // the launch grid pads the (batch, KV head) groups to a multiple of the 8 XCDs
     const int64_t groups_padded = (((int64_t)a->B * a->Hkv + 7) / 8) * 8;
@@ -380,7 +380,8 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator)
     p.causal = a->causal;
     p.group = a->Hq / a->Hkv;
     p.top = (1 << ctx->lut_bits) - 1;
-    const int rows_per_block = comparator ? 128 : fwd_rows_per_block(ctx->variant);
+    const int variant = fwd_choose_variant(ctx->variant, a->B, a->Hq, a->L);
+    const int rows_per_block = comparator ? 128 : fwd_rows_per_block(variant);
     p.n_qtiles = (a->L + rows_per_block - 1) / rows_per_block;
     std::memcpy(p.lut, ctx->lut, 32);
     p.dbg_row_max = a->dbg_row_max; p.dbg_row_sum = a->dbg_row_sum; p.dbg_acc = a->dbg_acc;
@@ -416,7 +417,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator)
         p.svso_table = ctx->d_svso;
     }
 
-    if (!comparator && fwd_needs_workspace(ctx->variant)) {
+    if (!comparator) {
         const size_t rows = (size_t)a->B * a->Hq * a->L;
         const size_t cs = (size_t)a->B * a->Hkv * p.n_qtiles * a->d;
         rc = ensure_workspace(ctx, 2 * rows + cs);
@@ -427,7 +428,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator)
     }
 
     const int herr = comparator ? launch_quantonly(p, a->d, ctx->variant, stream)
-                                : launch_fwd(p, a->d, dv.idx_mode, ctx->variant, stream);
+                                : launch_fwd(p, a->d, dv.idx_mode, variant, stream);
     if (herr != 0) return hip_fail(ctx, (hipError_t)herr, comparator ? "launch(quant-only)" : "launch(intattn forward)");
     ctx->err.clear();
     return INTATTN_OK;
@@ -443,6 +444,7 @@ int intattn_create(intattn_ctx **out, const intattn_config *cfg)
     *out = nullptr;
     if (cfg->lut_bits < 1 || cfg->lut_bits > 5) return fail(nullptr, INTATTN_ERR_UNSUPPORTED, "lut_bits must be in 1..5");
     if (!(cfg->clip > 0.0) || !std::isfinite(cfg->clip)) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "clip must be finite and > 0");
+    if (!fwd_variant_known(cfg->variant)) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "unknown kernel variant");
     if (cfg->reserved != 0) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "reserved must be 0");
     if (cfg->device < -1) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "no such HIP device");
     if (cfg->device >= 0) {

@@ -45,12 +45,10 @@ constexpr int NT = WAVES * 64;
 // query row) -- without the output accumulators it needs half the registers, so twice as many
 // waves per SIMD hide the LDS and MFMA latencies of the two ALU-light sweeps; 2 = sweep C only,
 // reading that workspace.
-// KS is the number of 32-key sub-tiles sweep C computes per step (KT: the whole staged tile at
-// once; 1: one sub-tile at a time, which needs fewer registers and so admits a third wave per SIMD).
-template <int D, int RB, int KT, bool CAUSAL, int MODE, int PH, int KS>
-__global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (KS == 1 ? 3 : 2) : 1)) void fwd_kernel(const FwdParams p)
+template <int D, int RB, int KT, bool CAUSAL, int MODE, int PH>
+__global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (KT == 1 ? 3 : 2) : 1)) void fwd_kernel(const FwdParams p)
 {
-    static_assert(KS == KT || KS == 1, "sweep C steps over whole tiles or single sub-tiles");
+    constexpr int KS = KT; // sub-tiles sweep C computes per step: the whole staged tile
     constexpr int KB = D / 32;       // 32-wide blocks of the head dimension
     constexpr int CB = D / 32;       // 32-wide blocks of output channels
     constexpr int BK = 32 * KT;      // keys per tile
@@ -519,64 +517,67 @@ int launch_colsum(const FwdParams &p, int d, int chunk, hipStream_t st)
     return (int)hipGetLastError();
 }
 
-template <int D, int RB, int KT, bool CAUSAL, int PH, int KS>
+template <int D, int RB, int KT, bool CAUSAL, int PH>
 int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
 {
     const dim3 grid((unsigned)fwd_grid_size(p.B, p.Hq, p.Hkv, p.n_qtiles)), block(NT);
     if (idx_mode == IDX_MAD24)
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24, PH, KS>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24, PH>), grid, block, 0, st, p);
     else if (idx_mode == IDX_MULHI24)
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MULHI24, PH, KS>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MULHI24, PH>), grid, block, 0, st, p);
     else if (idx_mode == IDX_FP32)
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP32, PH, KS>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP32, PH>), grid, block, 0, st, p);
     else
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_DIV, PH, KS>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_DIV, PH>), grid, block, 0, st, p);
     return (int)hipGetLastError();
 }
 
-template <int RB, int KT, int PH, int KS = KT>
+template <int RB, int KT, int PH>
 int launch_shape(const FwdParams &p, int d, int idx_mode, hipStream_t st)
 {
     if (d == 64)
-        return p.causal ? launch_mode<64, RB, KT, true, PH, KS>(p, idx_mode, st) : launch_mode<64, RB, KT, false, PH, KS>(p, idx_mode, st);
+        return p.causal ? launch_mode<64, RB, KT, true, PH>(p, idx_mode, st) : launch_mode<64, RB, KT, false, PH>(p, idx_mode, st);
     if (d == 128)
-        return p.causal ? launch_mode<128, RB, KT, true, PH, KS>(p, idx_mode, st) : launch_mode<128, RB, KT, false, PH, KS>(p, idx_mode, st);
+        return p.causal ? launch_mode<128, RB, KT, true, PH>(p, idx_mode, st) : launch_mode<128, RB, KT, false, PH>(p, idx_mode, st);
     return (int)hipErrorInvalidValue;
 }
 
 } // namespace
 
-// variant 0/1: 32 query rows per wave (128 per workgroup); variant 2: 64 per wave (256).
-int fwd_rows_per_block(int variant) { return (variant == 2 || variant == 11) ? 256 : 128; }
-bool fwd_needs_workspace(int variant) { return variant != 4; }
+// Kernel variants (0 = automatic choice; the others are tuning knobs, all bit-identical):
+//   1  one launch, 32 query rows per wave, 64-key tiles     2  one launch, 64 rows per wave
+//   3  one launch, 32 rows per wave, 32-key tiles
+//   4  two launches: sweeps A+B (64 rows per wave), then sweep C (32 rows per wave), phase-ordered kernels
+//   5  as 4 with the software-pipelined sweep C kernel      6  as 5 with 64 rows per wave in sweep C
+//   7  software-pipelined sweeps A+B (64 rows per wave) and sweep C     8  as 7 with 32 rows per wave in A+B
+// Automatic choice: enough workgroups to amortise three launches -> variant 5; small problems
+// take the single launch.
+int fwd_choose_variant(int variant, int B, int Hq, int L)
+{
+    if (variant != 0) return variant;
+    const int64_t workgroups = (int64_t)B * Hq * ((L + 127) / 128);
+    return workgroups >= 1024 ? 5 : 1;
+}
+bool fwd_variant_known(int variant) { return variant >= 0 && variant <= 8; }
+int fwd_rows_per_block(int variant) { return (variant == 2 || variant == 6) ? 256 : 128; }
 
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    if (variant == 4) return launch_fwd_pipe(p, d, idx_mode, stream);
     // all launches go to the same stream: V chunk sums first, then the sweeps
     int e = launch_colsum(p, d, fwd_rows_per_block(variant), st);
     if (e != 0) return e;
     if (variant == 2) return launch_shape<2, 2, 0>(p, d, idx_mode, st);
     if (variant == 3) return launch_shape<1, 1, 0>(p, d, idx_mode, st);
-    if (variant == 10 || variant == 11) {
-        // sweeps A+B with 64 query rows per wave, then the software-pipelined sweep C with 32 / 64
+    if (variant >= 4 && variant <= 8) {
+        // sweeps A+B leave row max and row sum in the workspace for sweep C
         FwdParams pab = p;
-        pab.n_qtiles = (p.L + 255) / 256;
-        e = launch_shape<2, 2, 1>(pab, d, idx_mode, st);
+        if (variant != 8) pab.n_qtiles = (p.L + 255) / 256; // 64 query rows per wave in the first launch
+        e = variant <= 6 ? launch_shape<2, 2, 1>(pab, d, idx_mode, st)
+                         : launch_sweep_ab(pab, d, idx_mode, variant == 7 ? 64 : 32, stream);
         if (e != 0) return e;
-        return launch_sweep_c(p, d, idx_mode, variant == 10 ? 32 : 64, stream);
-    }
-    if (variant >= 5 && variant <= 9) {
-        // sweeps A+B at high occupancy, then sweep C
-        FwdParams pab = p;
-        if (variant >= 7) pab.n_qtiles = (p.L + 255) / 256; // 64 query rows per wave in the first launch
-        e = variant == 7 ? launch_shape<2, 1, 1>(pab, d, idx_mode, st)
-          : variant >= 8 ? launch_shape<2, 2, 1>(pab, d, idx_mode, st)
-                         : launch_shape<1, 2, 1>(pab, d, idx_mode, st);
-        if (e != 0) return e;
-        if (variant == 9) return launch_shape<1, 2, 2, 1>(p, d, idx_mode, st);
-        return variant == 6 ? launch_shape<1, 1, 2>(p, d, idx_mode, st) : launch_shape<1, 2, 2>(p, d, idx_mode, st);
+        if (variant == 4) return launch_shape<1, 2, 2>(p, d, idx_mode, st);
+        return launch_sweep_c(p, d, idx_mode, variant == 6 ? 64 : 32, stream);
     }
     return launch_shape<1, 2, 0>(p, d, idx_mode, st);
 }

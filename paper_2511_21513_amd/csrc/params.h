@@ -49,10 +49,11 @@ struct FwdParams {
 
 // Launchers implemented in the .hip files.  Return a hipError_t cast to int.
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *stream);
-int launch_fwd_pipe(const FwdParams &p, int d, int idx_mode, void *stream);
+int launch_sweep_ab(const FwdParams &p, int d, int idx_mode, int rows_per_wave, void *stream);
 int launch_sweep_c(const FwdParams &p, int d, int idx_mode, int rows_per_wave, void *stream);
+int fwd_choose_variant(int variant, int B, int Hq, int L); // resolves 0 (automatic) to a concrete variant
 int fwd_rows_per_block(int variant);
-bool fwd_needs_workspace(int variant);
+bool fwd_variant_known(int variant);
 int launch_quantonly(const FwdParams &p, int d, int variant, void *stream);
 
 } // namespace intattn

@@ -45,7 +45,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
 {
     constexpr int KB = D / 32;       // 32-wide blocks of the head dimension
     constexpr int CB = D / 32;       // 32-wide blocks of output channels
-    constexpr int NSUB = RB == 1 ? 2 : 4; // sub-tiles (pipeline steps) per tile; LDS for two workgroups per CU when RB = 1
+    constexpr int NSUB = 4;          // sub-tiles (pipeline steps) per tile: long enough to cover the latency of the loads
     constexpr int KSHIFT = NSUB - 2; // K tiles start this many sub-tiles before V tiles (see above)
     constexpr int BK = 32 * NSUB;    // keys per tile
     constexpr int BQ = WAVES * RB * 32;
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     __shared__ __attribute__((aligned(1024))) int8_t Ks1[TILE];
     __shared__ __attribute__((aligned(1024))) int8_t Vs0[TILE];
     __shared__ __attribute__((aligned(1024))) int8_t Vs1[TILE];
-    __shared__ uint32_t PT[WAVES][RB][32 * 32]; // [idx][row] per wave and row block
+    __shared__ uint16_t PT[WAVES][RB][32 * 32]; // [idx][row] per wave and row block (16-bit entries: half the LDS, few bank conflicts)
     __shared__ uint32_t lut_lds[8];
     __shared__ int32_t colsum[D];
 
@@ -174,17 +174,17 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
         const uint8_t *lut_b = (const uint8_t *)lut_lds;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-            uint32_t *ptw = PT[wave][rb];
+            uint16_t *ptw = PT[wave][rb];
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 const int kidx = 16 * h + j;
                 const uint32_t e = lut_b[kidx];
                 const uint32_t pr = (510u * e + sum[rb]) / (2u * sum[rb]);
-                ptw[kidx * 32 + n] = (pr ^ 0x80u) & 0xffu;
+                ptw[kidx * 32 + n] = (uint16_t)((pr ^ 0x80u) & 0xffu);
             }
         }
     }
-    const uint32_t *pt = PT[wave][0] + n; // row block rb: + 1024 rb
+    const uint16_t *pt = PT[wave][0] + n; // row block rb: + 1024 rb
 
     // ---- LDS read addresses (lane constants; the sub-tile is added per pair of steps)
     int kf_off[KB], vf_off[CB];

@@ -94,6 +94,15 @@ INTATTN_API int intattn_create(intattn_ctx **out, const intattn_config *cfg);
  * the default stream) and returns without waiting for it. */
 INTATTN_API int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
 
+/* The same forward cut at the point where the row maxima and row sums of IndexSoftmax
+ * (Sec. 3.1-3.2) are complete, for timing its kernels separately.  stage 0: everything, as
+ * intattn_forward.  stage 1: V column sums and sweeps A+B only (row max, row sum of E_hat go to
+ * the context's workspace; args->out is not written).  stage 2: sweep C only (P_hat, P_hat.V_hat,
+ * requantization), reading what the last stage-1 call on this context left: it must have had the
+ * same arguments, and nothing else may run on the context in between.  Returns
+ * INTATTN_ERR_UNSUPPORTED when the kernel variant in use for this problem is a single launch. */
+INTATTN_API int intattn_forward_stage(intattn_ctx *ctx, const intattn_args *args, void *hip_stream, int32_t stage);
+
 /* In-run comparator: the conventional INT8 pipeline the paper calls "Quant-Only"
  * (Sec. 2.2): INT8 Q.K^T, dequantize to fp32 with alpha, fp32 softmax, requantize P to
  * signed INT8 (x127), INT8 P.V, requantize the output with the same s_O.  Same arguments

@@ -20,6 +20,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = 0, -1, -2, -3, -4
 SYMBOLS = (
     "intattn_create",
     "intattn_forward",
+    "intattn_forward_stage",
     "intattn_forward_quantonly",
     "intattn_derive_params",
     "intattn_derive_index_map",
@@ -77,6 +78,8 @@ def load() -> ctypes.CDLL:
         lib.intattn_create.restype = i32
         lib.intattn_forward.argtypes = [vp, ctypes.POINTER(Args), vp]
         lib.intattn_forward.restype = i32
+        lib.intattn_forward_stage.argtypes = [vp, ctypes.POINTER(Args), vp, i32]
+        lib.intattn_forward_stage.restype = i32
         lib.intattn_forward_quantonly.argtypes = [vp, ctypes.POINTER(Args), vp]
         lib.intattn_forward_quantonly.restype = i32
         lib.intattn_derive_params.argtypes = [
@@ -190,6 +193,12 @@ class IntAttn:
     def forward_args(self, args: Args, stream: int = 0, quantonly: bool = False):
         fn = self._lib.intattn_forward_quantonly if quantonly else self._lib.intattn_forward
         rc = fn(self._ctx, ctypes.byref(args), ctypes.c_void_p(stream))
+        if rc != OK:
+            raise IntAttnError(rc, self.last_error())
+
+    def forward_stage(self, args: Args, stage: int, stream: int = 0):
+        """intattn_forward_stage: 0 = everything, 1 = column sums and sweeps A+B, 2 = sweep C."""
+        rc = self._lib.intattn_forward_stage(self._ctx, ctypes.byref(args), ctypes.c_void_p(stream), stage)
         if rc != OK:
             raise IntAttnError(rc, self.last_error())
 

@@ -357,7 +357,7 @@ int ensure_workspace(intattn_ctx *ctx, size_t n_int32)
     return INTATTN_OK;
 }
 
-int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator)
+int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, int stage = 0)
 {
     int rc = validate(ctx, a);
     if (rc) return rc;
@@ -428,7 +428,9 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator)
     }
 
     const int herr = comparator ? launch_quantonly(p, a->d, ctx->variant, stream)
-                                : launch_fwd(p, a->d, dv.idx_mode, variant, stream);
+                                : launch_fwd(p, a->d, dv.idx_mode, variant, stage, stream);
+    if (herr == (int)hipErrorNotSupported)
+        return fail(ctx, INTATTN_ERR_UNSUPPORTED, "the kernel variant in use for this problem is a single launch: no stages");
     if (herr != 0) return hip_fail(ctx, (hipError_t)herr, comparator ? "launch(quant-only)" : "launch(intattn forward)");
     ctx->err.clear();
     return INTATTN_OK;
@@ -471,6 +473,12 @@ int intattn_create(intattn_ctx **out, const intattn_config *cfg)
 int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void *hip_stream)
 {
     return run(ctx, args, hip_stream, false);
+}
+
+int intattn_forward_stage(intattn_ctx *ctx, const intattn_args *args, void *hip_stream, int32_t stage)
+{
+    if (stage < 0 || stage > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "stage must be 0, 1 or 2");
+    return run(ctx, args, hip_stream, false, stage);
 }
 
 int intattn_forward_quantonly(intattn_ctx *ctx, const intattn_args *args, void *hip_stream)

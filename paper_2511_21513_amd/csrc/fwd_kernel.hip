@@ -561,21 +561,26 @@ int fwd_choose_variant(int variant, int B, int Hq, int L)
 bool fwd_variant_known(int variant) { return variant >= 0 && variant <= 8; }
 int fwd_rows_per_block(int variant) { return (variant == 2 || variant == 6) ? 256 : 128; }
 
-int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *stream)
+int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
+    const bool two_launches = variant >= 4 && variant <= 8;
+    if (stage != 0 && !two_launches) return (int)hipErrorNotSupported;
     // all launches go to the same stream: V chunk sums first, then the sweeps
-    int e = launch_colsum(p, d, fwd_rows_per_block(variant), st);
+    int e = 0;
+    if (stage != 2) e = launch_colsum(p, d, fwd_rows_per_block(variant), st);
     if (e != 0) return e;
     if (variant == 2) return launch_shape<2, 2, 0>(p, d, idx_mode, st);
     if (variant == 3) return launch_shape<1, 1, 0>(p, d, idx_mode, st);
-    if (variant >= 4 && variant <= 8) {
+    if (two_launches) {
         // sweeps A+B leave row max and row sum in the workspace for sweep C
-        FwdParams pab = p;
-        if (variant != 8) pab.n_qtiles = (p.L + 255) / 256; // 64 query rows per wave in the first launch
-        e = variant <= 6 ? launch_shape<2, 2, 1>(pab, d, idx_mode, st)
-                         : launch_sweep_ab(pab, d, idx_mode, variant == 7 ? 64 : 32, stream);
-        if (e != 0) return e;
+        if (stage != 2) {
+            FwdParams pab = p;
+            if (variant != 8) pab.n_qtiles = (p.L + 255) / 256; // 64 query rows per wave in the first launch
+            e = variant <= 6 ? launch_shape<2, 2, 1>(pab, d, idx_mode, st)
+                             : launch_sweep_ab(pab, d, idx_mode, variant == 7 ? 64 : 32, stream);
+            if (e != 0 || stage == 1) return e;
+        }
         if (variant == 4) return launch_shape<1, 2, 2>(p, d, idx_mode, st);
         return launch_sweep_c(p, d, idx_mode, variant == 6 ? 64 : 32, stream);
     }

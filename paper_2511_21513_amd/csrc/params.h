@@ -48,7 +48,8 @@ struct FwdParams {
 };
 
 // Launchers implemented in the .hip files.  Return a hipError_t cast to int.
-int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, void *stream);
+// stage 0: everything; 1: V column sums + sweeps A+B; 2: sweep C (two-launch variants only; else hipErrorNotSupported)
+int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, void *stream);
 int launch_sweep_ab(const FwdParams &p, int d, int idx_mode, int rows_per_wave, void *stream);
 int launch_sweep_c(const FwdParams &p, int d, int idx_mode, int rows_per_wave, void *stream);
 int fwd_choose_variant(int variant, int B, int Hq, int L); // resolves 0 (automatic) to a concrete variant

@@ -229,3 +229,31 @@ def test_quantonly_comparator_close_to_fp64(torch_mod, ia, shape):
     err = np.abs(got.cpu().numpy().astype(np.float64) - np.clip(ref, -127, 127))
     assert err.mean() < 1.0, err.mean()
     assert err.max() <= 6.0, err.max()
+
+
+def test_stages_compose_to_the_forward(torch_mod, oracle):
+    """Stage 1 (column sums, sweeps A+B) followed by stage 2 (sweep C) gives the bytes of the
+    one-call forward; a single-launch variant refuses to be cut."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    dev = torch.device("cuda:0")
+    p = inputs.random_problem(21, 2, 4, 2, 300, 128, True)
+    q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
+    want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, None, causal=True)["out"]
+    for variant in (4, 5, 7):
+        ia = binding.IntAttn(device=0, variant=variant)
+        out = torch.zeros_like(q)
+        args, keep = ia.make_args(q, k, v, out, p.s_q, p.s_k, p.s_v, None, causal=True, per_head=False)
+        ia.forward_stage(args, 1)
+        torch.cuda.synchronize()
+        assert not out.any(), "stage 1 must not write the output"
+        ia.forward_stage(args, 2)
+        torch.cuda.synchronize()
+        assert int((out.cpu().numpy() != want).sum()) == 0
+        ia.close()
+    ia = binding.IntAttn(device=0, variant=1)
+    args, keep = ia.make_args(q, k, v, torch.zeros_like(q), p.s_q, p.s_k, p.s_v, None, causal=True, per_head=False)
+    with pytest.raises(binding.IntAttnError):
+        ia.forward_stage(args, 2)
+    ia.close()

@@ -186,7 +186,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     }
     const uint16_t *pt = PT[wave][0] + n; // row block rb: + 1024 rb
 
-    // ---- LDS read addresses (lane constants; the sub-tile is added per pair of steps)
+    // ---- LDS read addresses (lane constants; sub-tile and buffer go into immediate offsets)
     int kf_off[KB], vf_off[CB];
     {
         const int sw = swz_k<D>(n); // equal for keys n and n + 32
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
                          __attribute__((always_inline)) {
         if (T + 2 <= ntiles) dma_k(T + 2, Kdma);
         if (T + 1 < ntiles) dma_v(T + 1, Vdma);
-#pragma unroll 1
+#pragma unroll
         for (int u = 0; u < NSUB; u += 2) {
             step(masked_tag, NSUB * T + u, Krd + u * SUB, Vrd + u * SUB, sA, sB, lB, lA, pfB, pfA);
             step(masked_tag, NSUB * T + u + 1, Krd + (u + 1) * SUB, Vrd + (u + 1) * SUB, sB, sA, lA, lB, pfA, pfB);

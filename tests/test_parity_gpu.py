@@ -187,6 +187,15 @@ def test_config5_batched_prefill_4k_sampled(torch_mod, ia, oracle):
     check_sampled(torch_mod, ia, oracle, p, s_o, heads, 16, 6)
 
 
+def test_long_ragged_sequence_sampled(torch_mod, ia, oracle):
+    """L far beyond the benchmark sizes and not a multiple of any tile (70001 = 546 * 128 + 113):
+    hundreds of key tiles per row, row sums beyond 2^16, a ragged last tile in every sweep."""
+    p = inputs.random_problem(31, 1, 2, 1, 70001, 64, True, spread=1.2)
+    check_sampled(torch_mod, ia, oracle, p, None, [(0, 0), (0, 1)], 12, 7)
+    p = inputs.random_problem(32, 1, 1, 1, 33333, 128, False, spread=1.0)
+    check_sampled(torch_mod, ia, oracle, p, inputs.calibrated_out_scale(p, sample_rows=8), [(0, 0)], 12, 8)
+
+
 def fp64_reference_out(p, s_o):
     """fp64 softmax attention of the dequantized inputs, in units of s_O (not rounded)."""
     g = p.Hq // p.Hkv

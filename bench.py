@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel (sweep C) measured with rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE, each scaled by the same counter's reading for a plain 1 GiB device copy
 # (profiles/sweep_c_kernel_c4_gqa_prefill_8k.md).  Only workloads that were profiled have an entry.
-MEASURED_HBM_TRAFFIC_BYTES = {"c4_gqa_prefill_8k": 54.55e6 + 33.55e6}
+MEASURED_HBM_TRAFFIC_BYTES = {"c4_gqa_prefill_8k": 54.85e6 + 33.55e6}
 
 ALIASES = {"c1": "c1_single_head", "c2": "c2_vit_b16", "c3": "c3_llm_prefill_2k",
            "c4": "c4_gqa_prefill_8k", "c5": "c5_batched_prefill_4k"}

@@ -74,7 +74,7 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device copy of this many MiB three times "
                          "(the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--cpu-heads", type=int, default=8)
+    ap.add_argument("--cpu-heads", type=int, default=32)
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (heads are independent; nothing is sharded "

@@ -91,7 +91,11 @@ typedef struct {
 INTATTN_API int intattn_create(intattn_ctx **out, const intattn_config *cfg);
 
 /* Enqueues the fused IntAttention forward (Sec. 3) on hip_stream (a hipStream_t; NULL is
- * the default stream) and returns without waiting for it. */
+ * the default stream) and returns without waiting for it.  The context owns a device workspace
+ * (8 bytes per query row plus d int32 per 128 keys and KV head) that the first call allocates and
+ * a later, larger call re-allocates (hipMalloc / hipFree: not for use under graph capture); the
+ * kernels of a call pass intermediate results through it, so calls on ONE context must not
+ * overlap in time (same stream, or ordered by the caller); use one context per concurrent stream. */
 INTATTN_API int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
 
 /* The same forward cut at the point where the row maxima and row sums of IndexSoftmax

@@ -7,9 +7,9 @@
 // is swept three times, recomputing the INT8 score tile each time instead of ever storing
 // the L x L matrix:
 //   sweep A: S^T = K.Q^T (MFMA)            -> running row max
-//   sweep B: S^T - max (the MFMA accumulator starts at -max) -> clip, index, LUT_hat -> row sum;
-//            then the 2^b distinct probabilities of the row, P_hat = round(255 E/S), go to a
-//            per-row table in LDS
+//   sweep B: S^T again -> clip, index (the row max is folded into per-row constants), LUT_hat ->
+//            row sum; then the 2^b distinct probabilities of the row, P_hat = round(255 E/S), go
+//            to a per-row table in LDS
 //   sweep C: S^T again -> index -> per-row table -> 16 probability bytes per lane, which
 //            are exactly one MFMA B operand of O^T += V^T.P^T; then requantize and store.
 // Scores are produced transposed (keys x queries) so that each lane owns one query row:
@@ -18,13 +18,19 @@
 // The int8 MFMA is signed x signed while P_hat is unsigned (0..255).  The kernel feeds
 // P_hat - 128 and adds 128 * (column sums of the V rows of every processed tile) at the end;
 // hidden keys inside a processed tile carry P_hat = 0, i.e. the byte -128, so the correction
-// is the plain column sum, which one extra MFMA per 32 keys against an all-ones operand
-// produces (in sweep B, which has matrix-core slack).  All intermediate magnitudes stay below 2^31 for L < 131072.
+// is the plain column sum.  colsum_kernel (below) leaves the sums of V over each chunk of as
+// many keys as a workgroup has query rows; sweep C adds up the chunks it covers.  All
+// intermediate magnitudes stay below 2^31 for L < 131072.
 //
 // LDS tiles are row-major [key][d] with the 16-byte chunks of each row XOR-swizzled so that
 // both access patterns are bank-conflict free: K fragments are read with 128-bit loads
 // (one key row per lane), V^T fragments with the transposing 64-bit load (eight key rows per
-// 16 lanes).
+// 16 lanes).  The tiles are filled by buffer loads that write LDS directly.
+//
+// Within a tile the work is ordered in phases (all fragment reads, all MFMAs, all index
+// arithmetic with every table lookup in flight, then the consumers).  This is the kernel for
+// small problems (all three sweeps in one launch) and for sweeps A+B of large ones; sweep C of
+// large problems has a software-pipelined kernel of its own.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -41,10 +47,10 @@ constexpr int WAVES = 4;
 constexpr int NT = WAVES * 64;
 
 // PH selects which part of the path this instantiation runs: 0 = all three sweeps in one launch;
-// 1 = sweeps A and B only (row max, row sum and V column sums go to a small workspace: 8 bytes per
-// query row) -- without the output accumulators it needs half the registers, so twice as many
-// waves per SIMD hide the LDS and MFMA latencies of the two ALU-light sweeps; 2 = sweep C only,
-// reading that workspace.
+// 1 = sweeps A and B only (row max and row sum go to a small workspace: 8 bytes per query row) --
+// without the output accumulators it needs far fewer registers, so a wave can own 64 query rows
+// (every K fragment read feeds two MFMAs) at three waves per SIMD; 2 = sweep C only, reading that
+// workspace.
 template <int D, int RB, int KT, bool CAUSAL, int MODE, int PH>
 __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (KT == 1 ? 3 : 2) : 1)) void fwd_kernel(const FwdParams p)
 {

@@ -10,6 +10,7 @@ from .oracle import (  # noqa: F401
     index_map,
     lut,
     prob,
+    quantize,
     requant_params,
     rows,
 )

@@ -15,10 +15,15 @@
  *
  * Readings taken where the paper is silent (each is also what the HIP path
  * implements, and each is listed in the design notes):
- *   - "round" (the floor-ceil bracket of Eq. quant, Eq. clipping_thr, the index
- *     map, Eq. lut16, Eq. uint8-prob) is round-half-up.  For the index map and
+ *   - "round" (the floor-ceil bracket of Eq. clipping_thr, the index map,
+ *     Eq. lut16, Eq. uint8-prob) is round-half-up.  For the index map and
  *     Eq. uint8-prob it is evaluated in exact integer arithmetic:
  *     round(x/y) = floor((2x + y) / (2y)) for y > 0.
+ *   - Eq. quant (the dynamic quantizer in front of the path) works on fp32
+ *     values: the scale is one fp32 division, every element one fp32 division
+ *     rounded to the nearest integer with ties to even (the default IEEE
+ *     rounding of rintf); max|X| is floored at 1e-12 so that an all-zero group
+ *     has a scale.
  *   - causal masking: key j is visible to query i iff j <= i; hidden keys take
  *     no part in rowMax or rowSum and get P = 0.
  *   - grouped-query attention: query head h reads KV head h / (Hq/Hkv).
@@ -305,4 +310,46 @@ int intattn_oracle_rows(int B, int Hq, int Hkv, int L, int d, int causal, const 
     }
     free(hc.a); free(hc.e); free(hc.p);
     return rc;
+}
+
+/* ------------------------------------------------------------------ dynamic quantizer (Sec. 2.1) */
+
+/* Eq. quant: s_X = max|X| / 127, quant(X) = clamp(round(X / s_X), -127, 127), symmetric, zero
+ * point 0.  x is [B, H, L, d] contiguous fp32 (fp16 / bf16 inputs are widened exactly by the
+ * caller).  per_head = 0: one scale for the tensor (the paper's per-tensor form); 1: one scale
+ * per head index (axis 1) shared over the batch (Sec. 3.3 with one group per head).
+ * scales receives 1 or H values.  Inputs must be finite. */
+int intattn_oracle_quantize(int B, int H, int L, int d, const float *x, int per_head, int8_t *xq,
+                            float *scales)
+{
+    if (B < 1 || H < 1 || L < 1 || d < 1 || !x || !xq || !scales) return ORACLE_BAD_ARG;
+    const int groups = per_head ? H : 1;
+    const int64_t head_elems = (int64_t)L * d;
+    for (int g = 0; g < groups; ++g) {
+        float amax = 0.0f;
+        for (int b = 0; b < B; ++b)
+            for (int h = 0; h < H; ++h) {
+                if (per_head && h != g) continue;
+                const float *xs = x + ((int64_t)b * H + h) * head_elems;
+                for (int64_t i = 0; i < head_elems; ++i) {
+                    const float a = fabsf(xs[i]);
+                    if (a > amax) amax = a;
+                }
+            }
+        if (amax < 1e-12f) amax = 1e-12f;
+        scales[g] = amax / 127.0f; /* one fp32 division */
+    }
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h) {
+            const float s = scales[per_head ? h : 0];
+            const float *xs = x + ((int64_t)b * H + h) * head_elems;
+            int8_t *qs = xq + ((int64_t)b * H + h) * head_elems;
+            for (int64_t i = 0; i < head_elems; ++i) {
+                float r = rintf(xs[i] / s); /* fp32 division, nearest integer, ties to even */
+                if (r > 127.0f) r = 127.0f;
+                if (r < -127.0f) r = -127.0f;
+                qs[i] = (int8_t)r;
+            }
+        }
+    return ORACLE_OK;
 }

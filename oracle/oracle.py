@@ -54,6 +54,8 @@ def _load():
                 [i32] * 6 + [vp] * 3 + [i32] + [vp] * 4 + [i32, dbl] + [i32] * 3 + [vp] * 5
             )
             lib.intattn_oracle_rows.restype = i32
+            lib.intattn_oracle_quantize.argtypes = [i32] * 4 + [vp, i32, vp, vp]
+            lib.intattn_oracle_quantize.restype = i32
             _lib = lib
     return _lib
 
@@ -173,3 +175,18 @@ def rows(q, k, v, s_q, s_k, s_v, s_o=None, *, b, hq, rows, causal=False, per_hea
     if rc:
         raise ValueError(f"intattn_oracle_rows rc={rc}")
     return res
+
+
+def quantize(x, per_head: bool = False):
+    """Eq. quant on a [B, H, L, d] tensor (fp32, or fp16 widened exactly): returns (int8 tensor,
+    fp32 scales of shape [1] or [H])."""
+    x = np.ascontiguousarray(np.asarray(x).astype(np.float32))
+    if x.ndim != 4:
+        raise ValueError("expected a [B, H, L, d] tensor")
+    B, H, L, d = x.shape
+    xq = np.empty(x.shape, dtype=np.int8)
+    scales = np.empty(H if per_head else 1, dtype=np.float32)
+    rc = _load().intattn_oracle_quantize(B, H, L, d, _ptr(x), int(per_head), _ptr(xq), _ptr(scales))
+    if rc != 0:
+        raise ValueError(f"intattn_oracle_quantize failed with {rc}")
+    return xq, scales

@@ -386,3 +386,89 @@ def test_output_saturates_symmetrically(oracle):
     v[..., ::2], v[..., 1::2] = -127, 127
     r = oracle.forward(q, k, v, [0.1], [0.1], [0.1], [0.01])["out"]
     assert (r[..., ::2] == -127).all() and (r[..., 1::2] == 127).all()
+
+
+# ------------------------------------------------------------------ dynamic quantizer (Sec. 2.1, Eq. quant)
+
+def test_quantizer_grid_points_come_back_exactly(oracle):
+    """A tensor whose values are integers k in [-127, 127] times a power of two has
+    s = 2^e exactly (max|x| = 127 * 2^e) and must quantize to exactly those integers."""
+    rng = np.random.default_rng(50)
+    k = rng.integers(-127, 128, size=(2, 3, 17, 8)).astype(np.int32)
+    k[0, 0, 0, 0] = 127
+    for e in (-9, 0, 5):
+        x = (k.astype(np.float32) * np.float32(2.0 ** e))
+        xq, s = oracle.quantize(x)
+        assert s.shape == (1,) and s[0] == np.float32(2.0 ** e)
+        np.testing.assert_array_equal(xq.astype(np.int32), k)
+
+
+def test_quantizer_scale_is_one_fp32_division_and_max_maps_to_127(oracle):
+    rng = np.random.default_rng(51)
+    x = rng.standard_normal((1, 4, 33, 16)).astype(np.float32) * np.float32(3.7)
+    xq, s = oracle.quantize(x)
+    amax = np.abs(x).max()
+    assert s[0] == np.float32(amax) / np.float32(127.0)
+    i = np.unravel_index(np.abs(x).argmax(), x.shape)
+    assert abs(int(xq[i])) == 127 and np.sign(xq[i]) == np.sign(x[i])
+    assert xq.min() >= -127  # symmetric range: -128 is never produced
+    # reconstruction error at most half a step (plus the rounding of the fp32 quotient)
+    err = np.abs(xq.astype(np.float64) * float(s[0]) - x.astype(np.float64))
+    assert err.max() <= 0.5 * float(s[0]) * (1 + 1e-6)
+
+
+def test_quantizer_ties_go_to_even(oracle):
+    """With max|x| = 127 the scale is exactly 1, so x/s = x: halves are exact ties."""
+    x = np.zeros((1, 1, 1, 8), dtype=np.float32)
+    x[0, 0, 0] = [127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5]
+    xq, s = oracle.quantize(x)
+    assert s[0] == np.float32(1.0)
+    np.testing.assert_array_equal(xq[0, 0, 0], [127, 0, 2, 2, 0, -2, -2, 126])
+
+
+def test_quantizer_exact_rational_restatement(oracle):
+    """Element by element with exact rationals: the fp32 quotient x/s is the fp32 value nearest
+    to the rational x/s (checked through fp64, which holds the quotient of two fp32 values to
+    well below half an fp32 ulp except at exact fp32 ties, which the fp64 quotient reproduces),
+    then nearest integer, ties to even."""
+    rng = np.random.default_rng(52)
+    x = (rng.standard_t(4, size=(1, 2, 9, 8)) * 0.3).astype(np.float32)
+    xq, s = oracle.quantize(x, per_head=True)
+    for h in range(2):
+        sh = np.float32(np.abs(x[:, h]).max()) / np.float32(127.0)
+        assert s[h] == sh
+        for xv, qv in zip(x[0, h].ravel(), xq[0, h].ravel()):
+            y = np.float32(np.float64(xv) / np.float64(sh))  # correctly rounded fp32 quotient
+            fr = Fraction(float(y))
+            fl = fr.numerator // fr.denominator
+            rem = fr - fl
+            want = fl + (1 if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1) else 0)
+            assert int(qv) == max(-127, min(127, want))
+
+
+def test_quantizer_zero_tensor_and_per_head_groups(oracle):
+    z, s = oracle.quantize(np.zeros((1, 2, 3, 8), dtype=np.float32), per_head=True)
+    assert not z.any() and (s == np.float32(1e-12) / np.float32(127.0)).all()
+    rng = np.random.default_rng(53)
+    x = rng.standard_normal((3, 4, 11, 8)).astype(np.float32)
+    x[:, 2] *= 50.0  # one loud head must not change the others' scales
+    xq, s = oracle.quantize(x, per_head=True)
+    for h in range(4):
+        one, s1 = oracle.quantize(np.ascontiguousarray(x[:, h:h + 1]))
+        assert s1[0] == s[h]
+        np.testing.assert_array_equal(one[:, 0], xq[:, h])
+    # per tensor: the loud head sets the only scale
+    _, st = oracle.quantize(x)
+    assert st[0] == s[2] == s.max()
+
+
+def test_quantizer_reproduces_the_input_recipe(oracle):
+    """The seeded workload generator quantizes with numpy (max, divide, rint, clip): the oracle's
+    C loop must give the same bytes and scales on its fp32 draws."""
+    rng = np.random.default_rng(54)
+    x = rng.standard_normal((2, 3, 40, 16), dtype=np.float32)
+    for per_head in (False, True):
+        a, sa = oracle.quantize(x, per_head)
+        b, sb = inputs.quantize(x, per_head)
+        np.testing.assert_array_equal(a, b)
+        np.testing.assert_array_equal(sa, sb)

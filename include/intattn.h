@@ -114,6 +114,28 @@ INTATTN_API int intattn_forward_stage(intattn_ctx *ctx, const intattn_args *args
  * attention.  dbg_* taps are ignored. */
 INTATTN_API int intattn_forward_quantonly(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
 
+/* Arguments of intattn_quantize.  src and dst are DEVICE pointers to [B, H, L, d] tensors with byte
+ * strides for B, H, L (d contiguous, d a multiple of 8; src and its strides multiples of 16
+ * bytes, dst and its strides multiples of 8); scales is a DEVICE array of 1 (scale_mode 0) or H (scale_mode 1) floats that receives
+ * the scales.  The caller owns all three. */
+typedef struct intattn_quant_args {
+    int32_t B, H, L, d;
+    int32_t dtype;       /* element type of src: 0 = fp32, 1 = fp16, 2 = bf16 */
+    int32_t scale_mode;  /* 0 = one scale for the tensor, 1 = one per head index (shared over the batch) */
+    const void *src;
+    int8_t *dst;
+    int64_t src_stride[3];
+    int64_t dst_stride[3];
+    float *scales;
+} intattn_quant_args;
+
+/* Dynamic symmetric INT8 quantization of one of Q, K, V (Sec. 2.1, Eq. quant): s = max|X| / 127
+ * over the tensor (or over each head index), X_hat = clamp(round(X / s), -127, 127), computed in
+ * fp32 (one IEEE division per element, ties to even; max|X| is floored at 1e-12).  Enqueued on
+ * hip_stream; the scales stay in device memory.  Inputs must be finite.  Uses a small scratch
+ * buffer of the context (allocated by the first call, B * H <= 65535). */
+INTATTN_API int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *args, void *hip_stream);
+
 /* Host-only parameter derivation, exposed for tests: c_int of Eq. clipping_thr for
  * (s_q, s_k, d), and the output multiplier/shift for (s_v, s_o).  Any output pointer may be
  * NULL.  Returns INTATTN_ERR_INVALID_ARG for non-positive scales or an unrepresentable ratio. */

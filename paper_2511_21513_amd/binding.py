@@ -22,6 +22,7 @@ SYMBOLS = (
     "intattn_forward",
     "intattn_forward_stage",
     "intattn_forward_quantonly",
+    "intattn_quantize",
     "intattn_derive_params",
     "intattn_derive_index_map",
     "intattn_get_lut",
@@ -60,6 +61,16 @@ class Args(ctypes.Structure):
     ]
 
 
+class QuantArgs(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("dtype", ctypes.c_int32), ("scale_mode", ctypes.c_int32),
+        ("src", ctypes.c_void_p), ("dst", ctypes.c_void_p),
+        ("src_stride", ctypes.c_int64 * 3), ("dst_stride", ctypes.c_int64 * 3),
+        ("scales", ctypes.c_void_p),
+    ]
+
+
 _lib = None
 
 
@@ -80,6 +91,8 @@ def load() -> ctypes.CDLL:
         lib.intattn_forward.restype = i32
         lib.intattn_forward_stage.argtypes = [vp, ctypes.POINTER(Args), vp, i32]
         lib.intattn_forward_stage.restype = i32
+        lib.intattn_quantize.argtypes = [vp, ctypes.POINTER(QuantArgs), vp]
+        lib.intattn_quantize.restype = i32
         lib.intattn_forward_quantonly.argtypes = [vp, ctypes.POINTER(Args), vp]
         lib.intattn_forward_quantonly.restype = i32
         lib.intattn_derive_params.argtypes = [
@@ -195,6 +208,34 @@ class IntAttn:
         rc = fn(self._ctx, ctypes.byref(args), ctypes.c_void_p(stream))
         if rc != OK:
             raise IntAttnError(rc, self.last_error())
+
+    def quantize(self, x, per_head: bool = False, out=None, scales=None, stream=None):
+        """intattn_quantize on a [B, H, L, d] device tensor (torch float32 / float16 / bfloat16,
+        last dimension contiguous): returns (int8 tensor, float32 device tensor of 1 or H scales).
+        Argument marshalling only."""
+        import torch
+
+        dtypes = {torch.float32: 0, torch.float16: 1, torch.bfloat16: 2}
+        if x.dim() != 4 or x.dtype not in dtypes or x.stride(3) != 1:
+            raise ValueError("expected a [B, H, L, d] float32/float16/bfloat16 tensor with contiguous last dimension")
+        B, H, L, d = x.shape
+        if out is None:
+            out = torch.empty((B, H, L, d), dtype=torch.int8, device=x.device)
+        if scales is None:
+            scales = torch.empty(H if per_head else 1, dtype=torch.float32, device=x.device)
+        a = QuantArgs()
+        a.B, a.H, a.L, a.d = B, H, L, d
+        a.dtype, a.scale_mode = dtypes[x.dtype], int(per_head)
+        a.src, a.dst, a.scales = x.data_ptr(), out.data_ptr(), scales.data_ptr()
+        es = x.element_size()
+        for i in range(3):
+            a.src_stride[i] = x.stride(i) * es
+            a.dst_stride[i] = out.stride(i)
+        st = torch.cuda.current_stream(x.device).cuda_stream if stream is None else stream
+        rc = self._lib.intattn_quantize(self._ctx, ctypes.byref(a), ctypes.c_void_p(st))
+        if rc != OK:
+            raise IntAttnError(rc, self.last_error())
+        return out, scales
 
     def forward_stage(self, args: Args, stage: int, stream: int = 0):
         """intattn_forward_stage: 0 = everything, 1 = column sums and sweeps A+B, 2 = sweep C."""

@@ -29,6 +29,8 @@ struct intattn_ctx {
     // kernel workspace (row max and row sum between the two launches, V chunk sums), grown on demand
     int32_t *d_ws = nullptr;
     size_t ws_cap = 0; // in int32 elements
+    uint32_t *d_amax = nullptr; // scratch of the quantizer: max|X| bits per group
+    int amax_cap = 0;
     std::vector<HeadParams> hp_host;  // what d_hp currently holds
     std::vector<float> alpha_host, svso_host;
     std::string err;
@@ -481,6 +483,51 @@ int intattn_forward_stage(intattn_ctx *ctx, const intattn_args *args, void *hip_
     return run(ctx, args, hip_stream, false, stage);
 }
 
+int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *a, void *hip_stream)
+{
+    if (!ctx) return INTATTN_ERR_INVALID_ARG;
+    if (!a) return fail(ctx, INTATTN_ERR_INVALID_ARG, "args is NULL");
+    if (ctx->device < 0) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "host-only context: no device to run on");
+    if (a->B < 1 || a->H < 1 || a->L < 1 || a->d < 8) return fail(ctx, INTATTN_ERR_INVALID_ARG, "B, H, L must be >= 1 and d >= 8");
+    if (a->d % 8 != 0) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "d must be a multiple of 8");
+    if ((int64_t)a->B * a->H > 65535) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "B * H must not exceed 65535");
+    if (a->dtype < 0 || a->dtype > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "dtype must be 0 (fp32), 1 (fp16) or 2 (bf16)");
+    if (a->scale_mode != 0 && a->scale_mode != 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode must be 0 or 1");
+    if (!a->src || !a->dst || !a->scales) return fail(ctx, INTATTN_ERR_INVALID_ARG, "src, dst, scales must be non-NULL");
+    if ((const void *)a->dst == a->src) return fail(ctx, INTATTN_ERR_INVALID_ARG, "dst must not alias src");
+    if ((((uintptr_t)a->src) & 15u) || (((uintptr_t)a->dst) & 7u))
+        return fail(ctx, INTATTN_ERR_INVALID_ARG, "src must be 16-byte aligned and dst 8-byte aligned");
+    const int64_t es = a->dtype == 0 ? 4 : 2;
+    for (int i = 0; i < 3; ++i) {
+        if (a->src_stride[i] < 0 || a->dst_stride[i] < 0 || (a->src_stride[i] & 15) != 0 || (a->dst_stride[i] & 7) != 0)
+            return fail(ctx, INTATTN_ERR_INVALID_ARG, "src strides must be non-negative multiples of 16, dst strides of 8");
+    }
+    if (a->src_stride[2] < es * a->d || a->dst_stride[2] < a->d)
+        return fail(ctx, INTATTN_ERR_INVALID_ARG, "the L strides must cover a row of d elements");
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return hip_fail(ctx, guard.status, "hipSetDevice");
+    const int groups = a->scale_mode ? a->H : 1;
+    if (groups > ctx->amax_cap) {
+        uint32_t *m = nullptr;
+        const hipError_t e = hipMalloc((void **)&m, sizeof(uint32_t) * (size_t)groups);
+        if (e != hipSuccess) return fail(ctx, INTATTN_ERR_NOMEM, std::string("hipMalloc of the quantizer scratch: ") + hipGetErrorString(e));
+        if (ctx->d_amax) (void)hipFree(ctx->d_amax);
+        ctx->d_amax = m;
+        ctx->amax_cap = groups;
+    }
+    QuantParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.src = a->src; p.dst = a->dst;
+    for (int i = 0; i < 3; ++i) { p.ss[i] = a->src_stride[i]; p.ds[i] = a->dst_stride[i]; }
+    p.B = a->B; p.H = a->H; p.L = a->L; p.d = a->d;
+    p.dtype = a->dtype; p.per_head = a->scale_mode;
+    p.scales = a->scales; p.amax_bits = ctx->d_amax;
+    const int herr = launch_quantize(p, hip_stream);
+    if (herr != 0) return hip_fail(ctx, (hipError_t)herr, "launch(quantize)");
+    ctx->err.clear();
+    return INTATTN_OK;
+}
+
 int intattn_forward_quantonly(intattn_ctx *ctx, const intattn_args *args, void *hip_stream)
 {
     return run(ctx, args, hip_stream, true);
@@ -545,6 +592,7 @@ void intattn_destroy(intattn_ctx *ctx)
         if (ctx->d_alpha) (void)hipFree(ctx->d_alpha);
         if (ctx->d_svso) (void)hipFree(ctx->d_svso);
         if (ctx->d_ws) (void)hipFree(ctx->d_ws);
+        if (ctx->d_amax) (void)hipFree(ctx->d_amax);
     }
     delete ctx;
 }

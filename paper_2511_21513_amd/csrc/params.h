@@ -47,6 +47,18 @@ struct FwdParams {
     const float *svso_table;    // device [Hq]
 };
 
+// Arguments of the dynamic quantizer (Sec. 2.1, Eq. quant).
+struct QuantParams {
+    const void *src;       // [B, H, L, d], d contiguous
+    int8_t *dst;
+    int64_t ss[3], ds[3];  // byte strides of B, H, L
+    int32_t B, H, L, d;
+    int32_t dtype;         // 0 fp32, 1 fp16, 2 bf16
+    int32_t per_head;      // 0: one scale; 1: one per head index
+    float *scales;         // device, 1 or H values (out)
+    uint32_t *amax_bits;   // device scratch, 1 or H values
+};
+
 // Launchers implemented in the .hip files.  Return a hipError_t cast to int.
 // stage 0: everything; 1: V column sums + sweeps A+B; 2: sweep C (two-launch variants only; else hipErrorNotSupported)
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, void *stream);
@@ -55,6 +67,7 @@ int launch_sweep_c(const FwdParams &p, int d, int idx_mode, int rows_per_wave, v
 int fwd_choose_variant(int variant, int B, int Hq, int L); // resolves 0 (automatic) to a concrete variant
 int fwd_rows_per_block(int variant);
 bool fwd_variant_known(int variant);
+int launch_quantize(const QuantParams &p, void *stream);
 int launch_quantonly(const FwdParams &p, int d, int variant, void *stream);
 
 } // namespace intattn

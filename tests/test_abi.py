@@ -44,11 +44,14 @@ def test_struct_layout_matches_header(lib):
     ctypes mirrors."""
     fields_cfg = [f[0] for f in binding.Config._fields_]
     fields_arg = [f[0] for f in binding.Args._fields_]
+    fields_qnt = [f[0] for f in binding.QuantArgs._fields_]
     src = ['#include <stdio.h>', '#include <stddef.h>', f'#include "{HEADER}"', "int main(void){"]
     src.append('printf("%zu\\n", sizeof(intattn_config));')
     src += [f'printf("%zu\\n", offsetof(intattn_config, {f}));' for f in fields_cfg]
     src.append('printf("%zu\\n", sizeof(intattn_args));')
     src += [f'printf("%zu\\n", offsetof(intattn_args, {f}));' for f in fields_arg]
+    src.append('printf("%zu\\n", sizeof(intattn_quant_args));')
+    src += [f'printf("%zu\\n", offsetof(intattn_quant_args, {f}));' for f in fields_qnt]
     src.append("return 0;}")
     with tempfile.TemporaryDirectory() as td:
         c = os.path.join(td, "probe.c")
@@ -58,6 +61,7 @@ def test_struct_layout_matches_header(lib):
         vals = [int(x) for x in subprocess.run([exe], check=True, capture_output=True, text=True).stdout.split()]
     want = [ctypes.sizeof(binding.Config)] + [getattr(binding.Config, f).offset for f in fields_cfg]
     want += [ctypes.sizeof(binding.Args)] + [getattr(binding.Args, f).offset for f in fields_arg]
+    want += [ctypes.sizeof(binding.QuantArgs)] + [getattr(binding.QuantArgs, f).offset for f in fields_qnt]
     assert vals == want
 
 
@@ -181,3 +185,17 @@ def test_forward_rejects_bad_arguments_without_a_gpu(host_ctx, lib):
     zero = np.asarray([0.0], dtype=np.float32)
     # scale checks come after the host-only rejection on this context, so only the struct checks are reachable here
     assert call(mk(scale_q=zero.ctypes.data)) == binding.ERR_INVALID_ARG
+
+
+def test_quantize_rejects_bad_arguments_without_a_gpu(host_ctx, lib):
+    a = binding.QuantArgs()
+    a.B, a.H, a.L, a.d, a.dtype, a.scale_mode = 1, 2, 16, 64, 1, 0
+    a.src, a.dst, a.scales = 0x1000, 0x2000, 0x3000
+    for i, st in enumerate((2 * 16 * 128, 16 * 128, 128)):
+        a.src_stride[i] = st
+        a.dst_stride[i] = st // 2
+    ctx = host_ctx._ctx
+    # a host-only context has no device to run on; everything else is refused before that matters
+    assert lib.intattn_quantize(ctx, None, None) == binding.ERR_INVALID_ARG
+    assert lib.intattn_quantize(ctx, ctypes.byref(a), None) == binding.ERR_UNSUPPORTED
+    assert lib.intattn_quantize(None, ctypes.byref(a), None) == binding.ERR_INVALID_ARG

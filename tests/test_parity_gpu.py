@@ -266,3 +266,86 @@ def test_stages_compose_to_the_forward(torch_mod, oracle):
     with pytest.raises(binding.IntAttnError):
         ia.forward_stage(args, 2)
     ia.close()
+
+
+QUANT_CASES = [
+    # B, H, L, d, dtype, per_head
+    (1, 1, 1, 8, "float32", False),
+    (2, 3, 37, 64, "float16", False),
+    (2, 3, 37, 64, "bfloat16", True),
+    (1, 5, 1000, 128, "float32", True),
+    (3, 2, 513, 72, "float16", True),
+    (1, 8, 4096, 128, "bfloat16", False),
+]
+
+
+@pytest.mark.parametrize("case", QUANT_CASES, ids=lambda c: "B{}H{}L{}d{}{}ph{}".format(*c[:5], int(c[5])))
+def test_quantizer_bit_exact(torch_mod, oracle, case):
+    """The on-GPU dynamic quantizer (Sec. 2.1, Eq. quant) against the oracle: INT8 bytes and fp32
+    scales must be identical (fp16 / bf16 inputs are widened exactly on both sides)."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    B, H, L, d, dtype, per_head = case
+    print(f"case {case}", flush=True)
+    rng = np.random.default_rng(B * 1000 + L)
+    x = (rng.standard_t(4, size=(B, H, L, d)) * rng.uniform(0.05, 20.0, size=(1, H, 1, 1))).astype(np.float32)
+    xt = torch.from_numpy(x).to("cuda:0").to(getattr(torch, dtype))
+    ia = binding.IntAttn(device=0)
+    xq, s = ia.quantize(xt, per_head)
+    torch.cuda.synchronize()
+    want_q, want_s = oracle.quantize(xt.float().cpu().numpy(), per_head)
+    np.testing.assert_array_equal(s.cpu().numpy(), want_s)
+    assert int((xq.cpu().numpy() != want_q).sum()) == 0
+    ia.close()
+
+
+def test_quantizer_edge_cases(torch_mod, oracle):
+    """All-zero tensor (floored scale), exact ties (scale exactly 1), a strided [B, L, H, d] view
+    in and out, and the same context reused with more groups."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    ia = binding.IntAttn(device=0)
+    z = torch.zeros((1, 2, 5, 16), device="cuda:0", dtype=torch.float16)
+    zq, zs = ia.quantize(z, per_head=True)
+    want_q, want_s = oracle.quantize(z.float().cpu().numpy(), True)
+    np.testing.assert_array_equal(zs.cpu().numpy(), want_s)
+    assert not zq.any()
+    t = torch.zeros((1, 1, 1, 8), device="cuda:0")
+    t[0, 0, 0] = torch.tensor([127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5])
+    tq, ts = ia.quantize(t)
+    assert ts.item() == 1.0 and tq[0, 0, 0].tolist() == [127, 0, 2, 2, 0, -2, -2, 126]
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((2, 150, 6, 64)).astype(np.float32)  # [B, L, H, d] in memory
+    xv = torch.from_numpy(x).to("cuda:0").permute(0, 2, 1, 3)
+    out = torch.empty((2, 150, 6, 64), dtype=torch.int8, device="cuda:0").permute(0, 2, 1, 3)
+    xq, s = ia.quantize(xv, per_head=True, out=out)
+    torch.cuda.synchronize()
+    want_q, want_s = oracle.quantize(np.ascontiguousarray(x.transpose(0, 2, 1, 3)), True)
+    np.testing.assert_array_equal(s.cpu().numpy(), want_s)
+    assert int((xq.cpu().numpy() != want_q).sum()) == 0
+    ia.close()
+
+
+def test_quantizer_feeds_the_forward(torch_mod, oracle):
+    """fp16 Q, K, V -> on-GPU quantizer -> forward: the same bytes as the oracle quantizer
+    followed by the oracle forward."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    rng = np.random.default_rng(78)
+    B, Hq, Hkv, L, d = 1, 4, 2, 300, 64
+    qf = torch.from_numpy(rng.standard_normal((B, Hq, L, d)).astype(np.float32)).to("cuda:0").half()
+    kf = torch.from_numpy(rng.standard_normal((B, Hkv, L, d)).astype(np.float32)).to("cuda:0").half()
+    vf = torch.from_numpy(rng.standard_normal((B, Hkv, L, d)).astype(np.float32)).to("cuda:0").half()
+    ia = binding.IntAttn(device=0)
+    (q, sq), (k, sk), (v, sv) = (ia.quantize(t) for t in (qf, kf, vf))
+    out = ia.forward(q, k, v, sq.cpu().numpy(), sk.cpu().numpy(), sv.cpu().numpy(), causal=True)
+    torch.cuda.synchronize()
+    oq, osq = oracle.quantize(qf.float().cpu().numpy())
+    ok, osk = oracle.quantize(kf.float().cpu().numpy())
+    ov, osv = oracle.quantize(vf.float().cpu().numpy())
+    want = oracle.forward(oq, ok, ov, osq, osk, osv, None, causal=True)["out"]
+    assert int((out.cpu().numpy() != want).sum()) == 0
+    ia.close()

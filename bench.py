@@ -62,6 +62,60 @@ def cpu_baseline(p, budget_heads):
             "seconds": dt}
 
 
+def quantizer_bench(a, name, dev):
+    """One step = Eq. quant on fp16 Q, K and V of the workload's shape (three calls, per-tensor
+    scales).  Two passes over the input are inherent (the scale needs the global max first), so
+    the algorithmic bytes per element are 2 reads of 2 bytes and 1 write of 1 byte."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2511_21513_amd import binding, inputs
+
+    B, Hq, Hkv, L, d = inputs.CONFIGS[name][:5]
+    g = torch.Generator(device=dev).manual_seed(0)
+    xs = [torch.randn((B, h, L, d), device=dev, generator=g, dtype=torch.float32).half() for h in (Hq, Hkv, Hkv)]
+    ia = binding.IntAttn(device=0)
+    outs = [torch.empty(x.shape, dtype=torch.int8, device=dev) for x in xs]
+    scs = [torch.empty(1, dtype=torch.float32, device=dev) for _ in xs]
+    stream = torch.cuda.current_stream(dev).cuda_stream
+
+    def step():
+        for x, o, s in zip(xs, outs, scs):
+            ia.quantize(x, False, out=o, scales=s, stream=stream)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(a.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / a.steps
+    n = sum(x.numel() for x in xs)
+    alg_bytes = n * (2 * 2 + 1)
+    gbps = alg_bytes / (ms * 1e-3) / 1e9
+    # parity of the timed outputs on the smallest tensor, and the oracle's own rate beside it
+    t0 = time.perf_counter()
+    want_q, want_s = oracle.quantize(xs[1].float().cpu().numpy())
+    cpu_s = time.perf_counter() - t0
+    mism = int((outs[1].cpu().numpy() != want_q).sum()) + int(scs[1].cpu().numpy()[0] != want_s[0])
+    res = {"metric": "dynamic INT8 quantizer (Eq. quant), algorithmic GB/s", "value": gbps, "unit": "GB/s", "n_gpus": 1,
+           "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": name + " (fp16 Q, K, V -> INT8, per-tensor scales)", "elements": n},
+           "parity_mismatches": mism,
+           "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBS,
+                        "traffic": None, "kernel": "absmax_kernel + quantize_kernel",
+                        "algorithmic_bytes_per_step": alg_bytes},
+           "cpu_baseline": {"value": xs[1].numel() * 5 / cpu_s / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                            "sample": f"the K tensor ({xs[1].numel()} elements), {cpu_s:.2f} s"}}
+    ia.close()
+    print(json.dumps(res))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -75,6 +129,9 @@ def main():
                     help="instead of the benchmark, run a plain device copy of this many MiB three times "
                          "(the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-heads", type=int, default=32)
+    ap.add_argument("--quantizer", action="store_true",
+                    help="instead of the attention benchmark, time the dynamic quantizer in front of it: "
+                         "fp16 Q, K, V of the workload's shape to INT8 with per-tensor scales (HBM-bound)")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (heads are independent; nothing is sharded "
@@ -97,9 +154,11 @@ def main():
     from paper_2511_21513_amd import binding, inputs
 
     name = ALIASES.get(a.workload, a.workload)
-    p = inputs.make_problem(name)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if a.quantizer:
+        return quantizer_bench(a, name, dev)
+    p = inputs.make_problem(name)
     ia = binding.IntAttn(device=0, variant=a.variant)
     q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
     out = torch.empty_like(q)

@@ -29,8 +29,8 @@ struct intattn_ctx {
     // kernel workspace (row max and row sum between the two launches, V chunk sums), grown on demand
     int32_t *d_ws = nullptr;
     size_t ws_cap = 0; // in int32 elements
-    uint32_t *d_amax = nullptr; // scratch of the quantizer: max|X| bits per group
-    int amax_cap = 0;
+    float *d_amax = nullptr; // scratch of the quantizer: partial max|X| per workgroup of its first pass
+    int64_t amax_cap = 0;
     std::vector<HeadParams> hp_host;  // what d_hp currently holds
     std::vector<float> alpha_host, svso_host;
     std::string err;
@@ -491,6 +491,7 @@ int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *a, void *hip_st
     if (a->B < 1 || a->H < 1 || a->L < 1 || a->d < 8) return fail(ctx, INTATTN_ERR_INVALID_ARG, "B, H, L must be >= 1 and d >= 8");
     if (a->d % 8 != 0) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "d must be a multiple of 8");
     if ((int64_t)a->B * a->H > 65535) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "B * H must not exceed 65535");
+    if ((int64_t)a->L * (a->d / 8) > 2147483647LL) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "L * d / 8 must fit 31 bits");
     if (a->dtype < 0 || a->dtype > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "dtype must be 0 (fp32), 1 (fp16) or 2 (bf16)");
     if (a->scale_mode != 0 && a->scale_mode != 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode must be 0 or 1");
     if (!a->src || !a->dst || !a->scales) return fail(ctx, INTATTN_ERR_INVALID_ARG, "src, dst, scales must be non-NULL");
@@ -506,10 +507,11 @@ int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *a, void *hip_st
         return fail(ctx, INTATTN_ERR_INVALID_ARG, "the L strides must cover a row of d elements");
     DeviceGuard guard(ctx->device);
     if (guard.status != hipSuccess) return hip_fail(ctx, guard.status, "hipSetDevice");
-    const int groups = a->scale_mode ? a->H : 1;
+    const int n_partial = quantize_partials_per_slice(a->B, a->H, a->L, a->d);
+    const int64_t groups = (int64_t)a->B * a->H * n_partial;
     if (groups > ctx->amax_cap) {
-        uint32_t *m = nullptr;
-        const hipError_t e = hipMalloc((void **)&m, sizeof(uint32_t) * (size_t)groups);
+        float *m = nullptr;
+        const hipError_t e = hipMalloc((void **)&m, sizeof(float) * (size_t)groups);
         if (e != hipSuccess) return fail(ctx, INTATTN_ERR_NOMEM, std::string("hipMalloc of the quantizer scratch: ") + hipGetErrorString(e));
         if (ctx->d_amax) (void)hipFree(ctx->d_amax);
         ctx->d_amax = m;
@@ -521,7 +523,7 @@ int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *a, void *hip_st
     for (int i = 0; i < 3; ++i) { p.ss[i] = a->src_stride[i]; p.ds[i] = a->dst_stride[i]; }
     p.B = a->B; p.H = a->H; p.L = a->L; p.d = a->d;
     p.dtype = a->dtype; p.per_head = a->scale_mode;
-    p.scales = a->scales; p.amax_bits = ctx->d_amax;
+    p.scales = a->scales; p.partial = ctx->d_amax; p.n_partial = n_partial;
     const int herr = launch_quantize(p, hip_stream);
     if (herr != 0) return hip_fail(ctx, (hipError_t)herr, "launch(quantize)");
     ctx->err.clear();

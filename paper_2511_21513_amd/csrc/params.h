@@ -56,7 +56,8 @@ struct QuantParams {
     int32_t dtype;         // 0 fp32, 1 fp16, 2 bf16
     int32_t per_head;      // 0: one scale; 1: one per head index
     float *scales;         // device, 1 or H values (out)
-    uint32_t *amax_bits;   // device scratch, 1 or H values
+    float *partial;        // device scratch: max|X| of every workgroup of the first pass, [B * H][n_partial]
+    int32_t n_partial;
 };
 
 // Launchers implemented in the .hip files.  Return a hipError_t cast to int.
@@ -67,6 +68,7 @@ int launch_sweep_c(const FwdParams &p, int d, int idx_mode, int rows_per_wave, v
 int fwd_choose_variant(int variant, int B, int Hq, int L); // resolves 0 (automatic) to a concrete variant
 int fwd_rows_per_block(int variant);
 bool fwd_variant_known(int variant);
+int quantize_partials_per_slice(int B, int H, int L, int d);
 int launch_quantize(const QuantParams &p, void *stream);
 int launch_quantonly(const FwdParams &p, int d, int variant, void *stream);
 

@@ -1,10 +1,11 @@
 // Dynamic symmetric INT8 quantizer in front of the attention path (Sec. 2.1, Eq. quant) for gfx950:
 //   s_X = max|X| / 127 per tensor (or per head index, Sec. 3.3),  X_hat = clamp(round(X / s_X), -127, 127).
 // fp32, fp16 or bf16 in, INT8 and the fp32 scales (device memory) out.  Two passes over the input,
-// both bound by HBM: (1) max|X| per group, one 16-byte load per lane and step, reduced per wave
-// and per workgroup, one atomic max per workgroup (the bits of a non-negative float order like
-// an unsigned integer); (2) one IEEE fp32 division per element, nearest integer with ties to even
-// (v_rndne_f32), eight INT8 results per 8-byte store.
+// both bound by HBM: (1) max|X| of each workgroup's part of a (b, h) slice, 16-byte loads, reduced
+// per wave and per workgroup and stored (no atomics: two thousand updates of one word cost more
+// than reading the tensor); (2) every workgroup reduces the partial maxima of its group, then one
+// IEEE fp32 division per element, nearest integer with ties to even (v_rndne_f32), eight INT8
+// results per 8-byte store.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -41,6 +42,21 @@ __device__ __forceinline__ void load8(const uint8_t *p, float (&x)[8])
     }
 }
 
+// Byte offsets of item `it` (eight elements) inside a (b, h) slice.  Rows that follow each other
+// without gaps need no division; the host checked that the item count fits 31 bits.
+template <int ES>
+__device__ __forceinline__ void item_offsets(const QuantParams &p, uint32_t it, uint32_t ipr, int64_t &so, int64_t &dofs)
+{
+    if (p.ss[2] == (int64_t)p.d * ES && p.ds[2] == (int64_t)p.d) { // wave-uniform
+        so = (int64_t)it * 8 * ES;
+        dofs = (int64_t)it * 8;
+    } else {
+        const uint32_t row = it / ipr, c = it - row * ipr;
+        so = (int64_t)row * p.ss[2] + (int64_t)c * 8 * ES;
+        dofs = (int64_t)row * p.ds[2] + (int64_t)c * 8;
+    }
+}
+
 // blockIdx.y = b * H + h; blockIdx.x walks the (L * d / 8) items of that slice.
 template <int DTYPE>
 __global__ __launch_bounds__(QNT) void absmax_kernel(const QuantParams p)
@@ -52,17 +68,24 @@ __global__ __launch_bounds__(QNT) void absmax_kernel(const QuantParams p)
     const int ipr = p.d / 8; // items per row
     const int64_t items = (int64_t)p.L * ipr;
     float m = 0.0f;
+    // grid-stride walk, QITEMS loads in flight per thread
+    for (int64_t base = (int64_t)blockIdx.x * QNT + threadIdx.x; base < items; base += (int64_t)gridDim.x * QNT * QITEMS) {
+        float x[QITEMS][8];
 #pragma unroll
-    for (int j = 0; j < QITEMS; ++j) {
-        const int64_t it = ((int64_t)blockIdx.x * QITEMS + j) * QNT + threadIdx.x;
-        if (it < items) {
-            const int64_t row = it / ipr;
-            const int c = (int)(it % ipr);
-            float x[8];
-            load8<DTYPE>(src + row * p.ss[2] + (int64_t)c * 8 * ES, x);
+        for (int j = 0; j < QITEMS; ++j) {
+            const int64_t it = base + (int64_t)j * gridDim.x * QNT;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf(x[i]));
+            for (int i = 0; i < 8; ++i) x[j][i] = 0.0f;
+            if (it < items) {
+                int64_t so, dofs;
+                item_offsets<ES>(p, (uint32_t)it, (uint32_t)ipr, so, dofs);
+                load8<DTYPE>(src + so, x[j]);
+            }
         }
+#pragma unroll
+        for (int j = 0; j < QITEMS; ++j)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf(x[j][i]));
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
@@ -71,7 +94,7 @@ __global__ __launch_bounds__(QNT) void absmax_kernel(const QuantParams p)
     if (threadIdx.x == 0) {
 #pragma unroll
         for (int w = 1; w < QNT / 64; ++w) m = fmaxf(m, wmax[w]);
-        atomicMax(p.amax_bits + (p.per_head ? h : 0), __float_as_uint(m));
+        p.partial[(int64_t)bh * gridDim.x + blockIdx.x] = m;
     }
 }
 
@@ -81,7 +104,22 @@ __global__ __launch_bounds__(QNT) void quantize_kernel(const QuantParams p)
     constexpr int ES = DTYPE == 0 ? 4 : 2;
     const int bh = blockIdx.y, b = bh / p.H, h = bh % p.H;
     const int g = p.per_head ? h : 0;
-    const float amax = fmaxf(__uint_as_float(p.amax_bits[g]), 1e-12f);
+    // max|X| of the group from the partial maxima: slices (b', h') with h' = h, or all slices
+    __shared__ float wmax[QNT / 64];
+    float m = 0.0f;
+    if (p.per_head) {
+        for (int i = threadIdx.x; i < p.B * p.n_partial; i += QNT)
+            m = fmaxf(m, p.partial[((int64_t)(i / p.n_partial) * p.H + h) * p.n_partial + i % p.n_partial]);
+    } else {
+        for (int i = threadIdx.x; i < p.B * p.H * p.n_partial; i += QNT) m = fmaxf(m, p.partial[i]);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < QNT / 64; ++w) m = fmaxf(m, wmax[w]);
+    const float amax = fmaxf(m, 1e-12f);
     const float s = amax / 127.0f; // one IEEE fp32 division
     if (blockIdx.x == 0 && threadIdx.x == 0 && b == 0 && (p.per_head || h == 0)) p.scales[g] = s;
     const uint8_t *src = (const uint8_t *)p.src + (int64_t)b * p.ss[0] + (int64_t)h * p.ss[1];
@@ -92,10 +130,10 @@ __global__ __launch_bounds__(QNT) void quantize_kernel(const QuantParams p)
     for (int j = 0; j < QITEMS; ++j) {
         const int64_t it = ((int64_t)blockIdx.x * QITEMS + j) * QNT + threadIdx.x;
         if (it < items) {
-            const int64_t row = it / ipr;
-            const int c = (int)(it % ipr);
+            int64_t so, dofs;
+            item_offsets<ES>(p, (uint32_t)it, (uint32_t)ipr, so, dofs);
             float x[8];
-            load8<DTYPE>(src + row * p.ss[2] + (int64_t)c * 8 * ES, x);
+            load8<DTYPE>(src + so, x);
             uint32_t w[2] = {0u, 0u};
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -103,15 +141,9 @@ __global__ __launch_bounds__(QNT) void quantize_kernel(const QuantParams p)
                 r = fminf(fmaxf(r, -127.0f), 127.0f);
                 w[i / 4] |= ((uint32_t)(int)r & 0xffu) << (8 * (i % 4));
             }
-            *(uint2 *)(dst + row * p.ds[2] + (int64_t)c * 8) = make_uint2(w[0], w[1]);
+            *(uint2 *)(dst + dofs) = make_uint2(w[0], w[1]);
         }
     }
-}
-
-__global__ void zero_amax_kernel(uint32_t *a, int n)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) a[i] = 0u;
 }
 
 template <int DTYPE>
@@ -119,19 +151,27 @@ int launch_dtype(const QuantParams &p, hipStream_t st)
 {
     const int64_t items = (int64_t)p.L * (p.d / 8);
     const dim3 grid((unsigned)((items + QNT * QITEMS - 1) / (QNT * QITEMS)), (unsigned)(p.B * p.H)), block(QNT);
-    hipLaunchKernelGGL(absmax_kernel<DTYPE>, grid, block, 0, st, p);
+    const dim3 rgrid((unsigned)p.n_partial, grid.y); // the reduction pass: each workgroup walks its part of a slice
+    hipLaunchKernelGGL(absmax_kernel<DTYPE>, rgrid, block, 0, st, p);
     hipLaunchKernelGGL(quantize_kernel<DTYPE>, grid, block, 0, st, p);
     return (int)hipGetLastError();
 }
 
 } // namespace
 
+// Partial maxima per (b, h) slice: about 2048 workgroups in all, never more than the slice has
+// work for.
+int quantize_partials_per_slice(int B, int H, int L, int d)
+{
+    const int64_t items = (int64_t)L * (d / 8);
+    const int64_t blocks = (items + QNT * QITEMS - 1) / (QNT * QITEMS);
+    const int64_t want = (2048 + (int64_t)B * H - 1) / ((int64_t)B * H);
+    return (int)(blocks < want ? blocks : want);
+}
+
 int launch_quantize(const QuantParams &p, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const int groups = p.per_head ? p.H : 1;
-    // cleared by a kernel, not a memset node, so that the call can be captured into a graph
-    hipLaunchKernelGGL(zero_amax_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, p.amax_bits, groups);
     if (p.dtype == 0) return launch_dtype<0>(p, st);
     if (p.dtype == 1) return launch_dtype<1>(p, st);
     if (p.dtype == 2) return launch_dtype<2>(p, st);

@@ -145,8 +145,9 @@ INTATTN_API int intattn_derive_params(const intattn_ctx *ctx, float s_q, float s
 /* Host-only, exposed for tests: how the kernels evaluate the index map of Sec. 3.1,
  * idx = round(x * (2^b - 1) / c_int) for x in [0, c_int], without dividing.  On entry *mode
  * names the scheme asked for; on return it is that scheme, or 0 if no constants exist for it
- * (the kernels then divide).  Both schemes are proven equal to the exact quotient on the
- * whole range before they are returned.
+ * (the kernels then use scheme 0, which exists for every c_int).  Every scheme is checked
+ * against the exact quotient at both sides of every index step before it is returned.
+ *   mode 0: idx = trunc(fma(x, r, 0.5)) in IEEE fp64, *mul / *add = low / high word of the bits of r
  *   mode 1: idx = (x * mul + add) >> shift                 (32-bit sum, 24-bit factors)
  *   mode 2: idx = (((x << shift) + add) * mul) >> 32       (48-bit product of 24-bit factors)
  *   mode 3: idx = trunc(fma(x, r, 0.5)) in IEEE fp32, *mul = the bits of r; add = shift = 0 */

@@ -228,6 +228,27 @@ bool find_fp32(uint32_t c_int, uint32_t top, HeadParams *hp)
     return false;
 }
 
+// The fp64 scheme: r = the double after fl(top / c_int); idx = trunc(fma(x, r, 0.5)) in IEEE double.
+// Exact for every c_int <= 2^30 and x <= c_int without a search: r exceeds top/c_int by less than
+// two units in the last place, so y = x*r + 0.5 exceeds v = x*top/c_int + 0.5 by less than 2^-43
+// before and 2^-42 after the rounding of the fma, which is monotone: an integer v = k (a tie of the
+// rounding to nearest index) stays >= k, and any other v lies at least 1/(2 c_int) >= 2^-31 below
+// the next integer.  The check points are evaluated all the same.
+// Stored for the kernel as the bits of -r: low word in idx_mul, high word in idx_add.
+bool find_fp64(uint32_t c_int, uint32_t top, HeadParams *hp)
+{
+    const double r = std::nextafter((double)top / (double)c_int, 1e300);
+    for (uint32_t x : check_points(c_int, top))
+        if ((uint32_t)(int)std::fma(-(double)x, -r, 0.5) != true_index(x, c_int, top)) return false;
+    const double negr = -r;
+    uint64_t bits;
+    std::memcpy(&bits, &negr, 8);
+    hp->idx_mul = (uint32_t)bits;
+    hp->idx_add = (uint32_t)(bits >> 32);
+    hp->idx_shift = 0;
+    return true;
+}
+
 struct Derived {
     std::vector<HeadParams> hp;
     std::vector<float> alpha, svso;
@@ -282,10 +303,10 @@ int derive_all(intattn_ctx *ctx, const intattn_args *a, Derived *out)
     out->svso.assign((size_t)n, 0.f);
     // candidate index-map schemes in order of preference; a launch uses one scheme for all heads
     typedef bool (*finder)(uint32_t, uint32_t, HeadParams *);
-    const finder finders[3] = {find_mulhi24, find_mad24, find_fp32};
-    const int modes[3] = {IDX_MULHI24, IDX_MAD24, IDX_FP32};
-    bool all_ok[3] = {true, true, true};
-    std::vector<HeadParams> cand[3];
+    const finder finders[4] = {find_mulhi24, find_mad24, find_fp32, find_fp64};
+    const int modes[4] = {IDX_MULHI24, IDX_MAD24, IDX_FP32, IDX_FP64};
+    bool all_ok[4] = {true, true, true, true};
+    std::vector<HeadParams> cand[4];
     for (auto &c : cand) c.assign((size_t)n, HeadParams{});
     for (int h = 0; h < n; ++h) {
         const int kv = a->scale_mode ? h / g : 0;
@@ -297,22 +318,21 @@ int derive_all(intattn_ctx *ctx, const intattn_args *a, Derived *out)
         hp.c_int = (int32_t)derive_c_int(ctx->clip, sq, sk, a->d);
         if (!derive_requant(sv, so, &hp.rq_mult, &hp.rq_shift))
             return fail(ctx, INTATTN_ERR_INVALID_ARG, "s_V / (255 s_O) is outside the representable range");
-        for (int m = 0; m < 3; ++m) {
+        for (int m = 0; m < 4; ++m) {
             cand[m][(size_t)h] = hp;
             if (all_ok[m] && !finders[m]((uint32_t)hp.c_int, top, &cand[m][(size_t)h])) all_ok[m] = false;
         }
         out->alpha[(size_t)h] = (float)(((double)sq * (double)sk) / std::sqrt((double)a->d));
         out->svso[(size_t)h] = (float)((double)sv / (double)so);
     }
-    out->idx_mode = IDX_DIV;
-    for (int m = 0; m < 3; ++m) {
+    for (int m = 0; m < 4; ++m) {
         if (all_ok[m]) {
             out->idx_mode = modes[m];
             out->hp = cand[m];
-            break;
+            return INTATTN_OK;
         }
     }
-    return INTATTN_OK;
+    return fail(ctx, INTATTN_ERR_UNSUPPORTED, "no exact index map for these scales");
 }
 
 int ensure_tables(intattn_ctx *ctx, int n)
@@ -555,11 +575,20 @@ int intattn_derive_index_map(const intattn_ctx *ctx, int64_t c_int, int32_t *mod
     HeadParams hp{};
     const uint32_t top = (1u << ctx->lut_bits) - 1u;
     if (*mode == IDX_MAD24) {
-        *mode = find_mad24((uint32_t)c_int, top, &hp) ? IDX_MAD24 : IDX_DIV;
+        *mode = find_mad24((uint32_t)c_int, top, &hp) ? IDX_MAD24 : IDX_FP64;
     } else if (*mode == IDX_FP32) {
-        *mode = find_fp32((uint32_t)c_int, top, &hp) ? IDX_FP32 : IDX_DIV;
+        *mode = find_fp32((uint32_t)c_int, top, &hp) ? IDX_FP32 : IDX_FP64;
+    } else if (*mode == IDX_MULHI24) {
+        *mode = find_mulhi24((uint32_t)c_int, top, &hp) ? IDX_MULHI24 : IDX_FP64;
     } else {
-        *mode = find_mulhi24((uint32_t)c_int, top, &hp) ? IDX_MULHI24 : IDX_DIV;
+        *mode = IDX_FP64;
+    }
+    if (*mode == IDX_FP64) {
+        if (!find_fp64((uint32_t)c_int, top, &hp)) return INTATTN_ERR_UNSUPPORTED;
+        *mul = hp.idx_mul; // bits of +r: low word, high word
+        *add = hp.idx_add ^ 0x80000000u;
+        *shift = 0;
+        return INTATTN_OK;
     }
     // report the mathematical constants (the kernel-side fields hold them negated)
     if (*mode == IDX_FP32) {
@@ -568,7 +597,7 @@ int intattn_derive_index_map(const intattn_ctx *ctx, int64_t c_int, int32_t *mod
         *shift = 0;
         return INTATTN_OK;
     }
-    *mul = *mode == IDX_DIV ? 0u : (uint32_t)(-(int32_t)hp.idx_mul);
+    *mul = (uint32_t)(-(int32_t)hp.idx_mul);
     *add = *mode == IDX_MULHI24 ? (uint32_t)(-(int32_t)hp.idx_add) : hp.idx_add;
     *shift = hp.idx_shift;
     return INTATTN_OK;

@@ -495,7 +495,7 @@ int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
     else if (idx_mode == IDX_FP32)
         hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP32, PH>), grid, block, 0, st, p);
     else
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_DIV, PH>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP64, PH>), grid, block, 0, st, p);
     return (int)hipGetLastError();
 }
 

@@ -51,6 +51,12 @@ __device__ __forceinline__ WorkItem fwd_work_item(const FwdParams &p, int bid)
 }
 
 // ------------------------------------------------------------------ index map (Sec. 3.1)
+// The fp64 scheme's factor -r (its bits are split over idx_mul, low word, and idx_add).
+__device__ __forceinline__ double idx_fp64_factor(const HeadParams &hp)
+{
+    return __builtin_bit_cast(double, ((uint64_t)hp.idx_add << 32) | (uint64_t)hp.idx_mul);
+}
+
 // t = -min(Delta, c_int) in [-c_int, 0]; returns round(-t * top / c_int).
 template <int MODE>
 __device__ __forceinline__ uint32_t index_map(int t, const HeadParams &hp, uint32_t top)
@@ -71,8 +77,8 @@ __device__ __forceinline__ uint32_t index_map(int t, const HeadParams &hp, uint3
         // proved the result exact on the whole range with the same IEEE operations
         return (uint32_t)(int)__builtin_fmaf((float)t, __uint_as_float(hp.idx_mul), 0.5f);
     } else {
-        const uint64_t c = (uint64_t)(uint32_t)hp.c_int;
-        return (uint32_t)((2ull * top * (uint64_t)(uint32_t)(-t) + c) / (2ull * c));
+        // trunc(fma(t, -r, 0.5)) in IEEE fp64, r the double after top/c_int: exact for every c_int
+        return (uint32_t)(int)__builtin_fma((double)t, idx_fp64_factor(hp), 0.5);
     }
 }
 
@@ -87,7 +93,7 @@ template <int MODE> struct RowIndex {
     uint32_t addc;
     int mul;
     int shift;
-    uint32_t c_int, top;
+    double negr; // fp64 scheme only
 
     __device__ __forceinline__ void init(const HeadParams &hp, int row_max, uint32_t top_)
     {
@@ -95,8 +101,8 @@ template <int MODE> struct RowIndex {
         bound = row_max - hp.c_int;
         mul = (int)hp.idx_mul;
         shift = hp.idx_shift;
-        c_int = (uint32_t)hp.c_int;
-        top = top_;
+        negr = MODE == IDX_FP64 ? idx_fp64_factor(hp) : 0.0;
+        (void)top_;
         if (MODE == IDX_MULHI24) addc = hp.idx_add - ((uint32_t)row_max << hp.idx_shift);
         else if (MODE == IDX_MAD24) addc = hp.idx_add - (uint32_t)__mul24(row_max, (int)hp.idx_mul);
         else addc = 0;
@@ -113,8 +119,7 @@ template <int MODE> struct RowIndex {
         } else if (MODE == IDX_FP32) {
             return (uint32_t)(int)__builtin_fmaf((float)(sc - mx), __uint_as_float((uint32_t)mul), 0.5f);
         } else {
-            const uint64_t c = c_int;
-            return (uint32_t)((2ull * top * (uint64_t)(uint32_t)(mx - sc) + c) / (2ull * c));
+            return (uint32_t)(int)__builtin_fma((double)(sc - mx), negr, 0.5);
         }
     }
 };

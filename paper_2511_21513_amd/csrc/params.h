@@ -8,7 +8,8 @@ namespace intattn {
 // How a kernel turns a clipped distance Delta' in [0, c_int] into the table index
 // idx = round(Delta' * top / c_int)  (Sec. 3.1 index map), exactly.
 enum IdxMode : int32_t {
-    IDX_DIV = 0,    // integer division, any c_int (slow, always exact)
+    IDX_FP64 = 0,   // trunc(fma(Delta', r, 0.5)) in IEEE fp64, r = the double after top/c_int: exact for every c_int
+                    // (idx_mul, idx_add hold the low and high word of the bits of -r)
     IDX_MAD24 = 1,  // (Delta' * mul + add) >> shift, 24-bit operands, 32-bit result
     IDX_MULHI24 = 2,// high 32 bits of the 48-bit product ((Delta' << pre) + add) * mul
     IDX_FP32 = 3    // trunc(fma(Delta', top/c_int, 0.5)) in IEEE fp32 (idx_mul holds the bits of -top/c_int)
@@ -17,7 +18,7 @@ enum IdxMode : int32_t {
 // Per query head: everything the kernel needs that depends on the scales.
 struct HeadParams {
     int32_t c_int;     // clip threshold of Eq. clipping_thr, capped at 2^30
-    uint32_t idx_mul;  // index-map multiplier (modes MAD24 / MULHI24)
+    uint32_t idx_mul;  // index-map multiplier (see IdxMode)
     uint32_t idx_add;  // index-map addend
     int32_t idx_shift; // MAD24: right shift; MULHI24: left pre-shift of Delta'
     int32_t rq_mult;   // output requantization multiplier M in [2^30, 2^31)

@@ -381,7 +381,7 @@ int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
     else if (idx_mode == IDX_FP32)
         hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_FP32>), grid, block, 0, st, p);
     else
-        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_DIV>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_FP64>), grid, block, 0, st, p);
     return (int)hipGetLastError();
 }
 

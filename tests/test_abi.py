@@ -152,6 +152,32 @@ def test_index_map_constants_are_exact(host_ctx, oracle, mode):
             np.testing.assert_array_equal(apply_index_map(got_mode, mul, add, sh, x), (2 * 31 * x + c) // (2 * c))
 
 
+def test_fp64_index_map_is_exact_for_every_threshold(host_ctx):
+    """Scheme 0, the one without a search: trunc(fma(x, r, 0.5)) in IEEE double with r the double
+    after 31 / c_int.  The fma is emulated in exact rationals and rounded once; checked on both
+    sides of every index step (ties included: c_int even makes x = c_int / 2 one), at the ends of
+    the range and at random points, for thresholds up to the cap of 2^30."""
+    from fractions import Fraction
+
+    rng = np.random.default_rng(64)
+    cs = [1, 2, 3, 31, 62, 63, 5203, 55064, 390001, 10**6, 2**24 - 1, 2**24, 2**24 + 1, 31 * 2**20, 62 * 2**22,
+          2**30 - 1, 2**30]
+    cs += [int(c) for c in rng.integers(1, 2**30, 40)] + [2 * int(c) for c in rng.integers(1, 2**29, 20)]
+    for c in cs:
+        got_mode, lo, hi, sh = host_ctx.derive_index_map(c, 0)
+        assert got_mode == 0 and sh == 0
+        r = float(np.array([lo | (hi << 32)], dtype=np.uint64).view(np.float64)[0])
+        assert r == np.nextafter(31.0 / c, np.inf)
+        xs = {0, c, c // 2, (c + 1) // 2}
+        for k in range(1, 32):  # first x with index >= k is ceil((2k - 1) c / 62)
+            t = -((-(2 * k - 1) * c) // 62)
+            xs.update(x for x in (t - 1, t, t + 1) if 0 <= x <= c)
+        xs.update(int(x) for x in rng.integers(0, c + 1, 200))
+        for x in xs:
+            y = float(Fraction(x) * Fraction(r) + Fraction(1, 2))  # one rounding to nearest, as the fma does
+            assert int(y) == (62 * x + c) // (2 * c), (c, x)
+
+
 def test_forward_rejects_bad_arguments_without_a_gpu(host_ctx, lib):
     buf = np.zeros(1 << 14, dtype=np.int8)
     base = buf.ctypes.data

@@ -87,14 +87,15 @@ def test_small_shapes_bit_exact(torch_mod, ia, oracle, shape):
     check_full(torch_mod, ia, oracle, p, s_o)
 
 
-@pytest.mark.parametrize("scale", [0.5, 0.05, 0.004, 0.0005])
-def test_clip_threshold_range_bit_exact(torch_mod, ia, oracle, scale):
-    """Thresholds from a handful (coarse index steps) to far beyond the multiply-shift's reach
-    (the kernel's dividing path)."""
-    p = inputs.random_problem(7, 1, 2, 2, 160, 64, True)
+@pytest.mark.parametrize("scale,d", [(0.5, 64), (0.05, 64), (0.004, 64), (0.002, 64), (0.0005, 64), (0.01, 128),
+                                     (0.004, 128)])
+def test_clip_threshold_range_bit_exact(torch_mod, ia, oracle, scale, d):
+    """Thresholds from a handful (coarse index steps) to far beyond the reach of the 24-bit and
+    fp32 schemes (the kernels' fp64 index map), with and without the clip binding."""
+    p = inputs.random_problem(7, 1, 2, 2, 160, d, True)
     p.s_q = np.asarray([scale], dtype=np.float32)
     p.s_k = np.asarray([scale], dtype=np.float32)
-    print("c_int", oracle.c_int(6.6, p.s_q[0], p.s_k[0], 64), flush=True)
+    print("c_int", oracle.c_int(6.6, p.s_q[0], p.s_k[0], d), flush=True)
     check_full(torch_mod, ia, oracle, p)
 
 

@@ -112,6 +112,27 @@ def quantizer_bench(a, name, dev):
                         "algorithmic_bytes_per_step": alg_bytes},
            "cpu_baseline": {"value": xs[1].numel() * 5 / cpu_s / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
                             "sample": f"the K tensor ({xs[1].numel()} elements), {cpu_s:.2f} s"}}
+    # quantizer and attention back to back, nothing read by the host in between
+    causal = bool(inputs.CONFIGS[name][5])
+    att_out = torch.empty_like(outs[0])
+    dargs, dkeep = ia.make_args(outs[0], outs[1], outs[2], att_out, scs[0], scs[1], scs[2], None, causal=causal,
+                                per_head=False, device_scales=True)
+
+    def chain():
+        step()
+        ia.forward_dynamic_args(dargs, stream)
+
+    for _ in range(2):
+        chain()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(a.steps):
+        chain()
+    e1.record()
+    torch.cuda.synchronize()
+    res["chain_fp16_to_int8_attention"] = {"entries": "3 x intattn_quantize + intattn_forward_dynamic",
+                                           "ms_per_step": e0.elapsed_time(e1) / a.steps,
+                                           "status": ia.dynamic_status()}
     ia.close()
     print(json.dumps(res))
 
@@ -223,6 +244,14 @@ def main():
                      "hbm_algorithmic_bytes_per_launch": p.algorithmic_bytes,
                      "hbm_algorithmic_GBps": p.algorithmic_bytes / (ms * 1e-3) / 1e9},
     }
+    # the same step with the scales in device memory (parameters derived by a kernel, no host read)
+    dscales = [torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(dev) for x in (p.s_q, p.s_k, p.s_v, s_o)]
+    out_d = torch.empty_like(q)
+    dargs, dkeep = ia.make_args(q, k, v, out_d, *dscales, causal=p.causal, per_head=p.per_head, device_scales=True)
+    dms, _ = timed(lambda: ia.forward_dynamic_args(dargs, stream), a.steps, 2)
+    res["device_scales"] = {"entry": "intattn_forward_dynamic", "ms_per_step": dms, "TOPS": p.ops / (dms * 1e-3) / 1e12,
+                            "bytes_differing_from_host_scale_output": int((out_d != out).sum().item()),
+                            "status": ia.dynamic_status()}
     if not a.no_comparator:
         try:
             cms, _ = timed(lambda: ia.forward_args(args, stream, quantonly=True), max(3, a.steps // 3), 2)

@@ -107,6 +107,24 @@ INTATTN_API int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void
  * INTATTN_ERR_UNSUPPORTED when the kernel variant in use for this problem is a single launch. */
 INTATTN_API int intattn_forward_stage(intattn_ctx *ctx, const intattn_args *args, void *hip_stream, int32_t stage);
 
+/* intattn_forward for scales that live in DEVICE memory, e.g. where intattn_quantize left them
+ * (Sec. 2.1 dynamic quantization feeding Sec. 3): args->scale_q / scale_k / scale_v / scale_out
+ * are DEVICE pointers here (same counts as for intattn_forward; scale_out may be NULL), every
+ * other field is as there.  A small kernel on hip_stream derives each head's c_int (Sec. 3.1,
+ * Eq. clipping_thr), requantization multiplier and index-map constants from them with the host
+ * path's arithmetic, so the output is bit-identical to intattn_forward with the same scale
+ * values, and the host never reads the scales: quantizer and attention can be enqueued back to
+ * back.  Scales that are not finite and > 0 (or a ratio s_V / (255 s_O) outside the multiplier's
+ * range) cannot be reported by return code: the affected heads' output is then unspecified (no
+ * fault), and intattn_dynamic_status reports it.  Same workspace and no-overlap rules as
+ * intattn_forward. */
+INTATTN_API int intattn_forward_dynamic(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
+
+/* *status (HOST) = 1 if the last intattn_forward_dynamic on this context met an unusable scale,
+ * else 0.  Copies one word from the device with a blocking copy; call it after synchronizing the
+ * stream that call was enqueued on. */
+INTATTN_API int intattn_dynamic_status(intattn_ctx *ctx, int32_t *status);
+
 /* In-run comparator: the conventional INT8 pipeline the paper calls "Quant-Only"
  * (Sec. 2.2): INT8 Q.K^T, dequantize to fp32 with alpha, fp32 softmax, requantize P to
  * signed INT8 (x127), INT8 P.V, requantize the output with the same s_O.  Same arguments

@@ -21,6 +21,8 @@ SYMBOLS = (
     "intattn_create",
     "intattn_forward",
     "intattn_forward_stage",
+    "intattn_forward_dynamic",
+    "intattn_dynamic_status",
     "intattn_forward_quantonly",
     "intattn_quantize",
     "intattn_derive_params",
@@ -91,6 +93,10 @@ def load() -> ctypes.CDLL:
         lib.intattn_forward.restype = i32
         lib.intattn_forward_stage.argtypes = [vp, ctypes.POINTER(Args), vp, i32]
         lib.intattn_forward_stage.restype = i32
+        lib.intattn_forward_dynamic.argtypes = [vp, ctypes.POINTER(Args), vp]
+        lib.intattn_forward_dynamic.restype = ctypes.c_int
+        lib.intattn_dynamic_status.argtypes = [vp, ctypes.POINTER(i32)]
+        lib.intattn_dynamic_status.restype = ctypes.c_int
         lib.intattn_quantize.argtypes = [vp, ctypes.POINTER(QuantArgs), vp]
         lib.intattn_quantize.restype = i32
         lib.intattn_forward_quantonly.argtypes = [vp, ctypes.POINTER(Args), vp]
@@ -175,9 +181,10 @@ class IntAttn:
         return int(mode.value), int(mul.value), int(add.value), int(sh.value)
 
     def make_args(self, q, k, v, out, s_q, s_k, s_v, s_o=None, *, causal=False, per_head=False,
-                  row_max=None, row_sum=None, acc=None):
+                  row_max=None, row_sum=None, acc=None, device_scales=False):
         """Marshals torch int8 tensors [B,H,L,d] (last dim contiguous) into an ``Args``.  Returns
-        (args, keepalive): keepalive holds the host scale arrays the struct points at."""
+        (args, keepalive): keepalive holds the scale arrays the struct points at: host arrays, or
+        with ``device_scales`` the float32 device tensors given (for ``forward_dynamic_args``)."""
         B, Hq, L, d = q.shape
         Hkv = k.shape[1]
         for t in (q, k, v, out):
@@ -191,13 +198,25 @@ class IntAttn:
         a.v_stride = (ctypes.c_int64 * 3)(*v.stride()[:3])
         a.out_stride = (ctypes.c_int64 * 3)(*out.stride()[:3])
         a.scale_mode = int(bool(per_head))
-        keep = [_host_f32(s_q), _host_f32(s_k), _host_f32(s_v), _host_f32(s_o)]
-        if per_head:
-            if keep[0].size != Hq or keep[1].size != Hkv or keep[2].size != Hkv or (
-                    keep[3] is not None and keep[3].size != Hq):
+        if device_scales:
+            import torch
+
+            keep = [s_q, s_k, s_v, s_o]
+            for t in keep:
+                if t is not None and (t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous()):
+                    raise ValueError("device scales must be contiguous float32 tensors on the GPU")
+            sizes = [t.numel() if t is not None else None for t in keep]
+            ptr = lambda t: t.data_ptr()  # noqa: E731
+        else:
+            keep = [_host_f32(s_q), _host_f32(s_k), _host_f32(s_v), _host_f32(s_o)]
+            sizes = [t.size if t is not None else None for t in keep]
+            ptr = lambda t: t.ctypes.data  # noqa: E731
+        want = [Hq, Hkv, Hkv, Hq] if per_head else [1, 1, 1, 1]
+        for have, need in zip(sizes, want):
+            if have is not None and (have != need if per_head else have < 1):
                 raise ValueError("per-head scales must have Hq (q, out) / Hkv (k, v) entries")
-        a.scale_q, a.scale_k, a.scale_v = (x.ctypes.data for x in keep[:3])
-        a.scale_out = keep[3].ctypes.data if keep[3] is not None else None
+        a.scale_q, a.scale_k, a.scale_v = (ptr(x) for x in keep[:3])
+        a.scale_out = ptr(keep[3]) if keep[3] is not None else None
         a.dbg_row_max = row_max.data_ptr() if row_max is not None else None
         a.dbg_row_sum = row_sum.data_ptr() if row_sum is not None else None
         a.dbg_acc = acc.data_ptr() if acc is not None else None
@@ -208,6 +227,19 @@ class IntAttn:
         rc = fn(self._ctx, ctypes.byref(args), ctypes.c_void_p(stream))
         if rc != OK:
             raise IntAttnError(rc, self.last_error())
+
+    def forward_dynamic_args(self, args: Args, stream: int = 0):
+        """intattn_forward_dynamic: ``args`` built with ``device_scales=True``."""
+        rc = self._lib.intattn_forward_dynamic(self._ctx, ctypes.byref(args), ctypes.c_void_p(stream))
+        if rc != OK:
+            raise IntAttnError(rc, self.last_error())
+
+    def dynamic_status(self) -> int:
+        st = ctypes.c_int32(0)
+        rc = self._lib.intattn_dynamic_status(self._ctx, ctypes.byref(st))
+        if rc != OK:
+            raise IntAttnError(rc, self.last_error())
+        return int(st.value)
 
     def quantize(self, x, per_head: bool = False, out=None, scales=None, stream=None):
         """intattn_quantize on a [B, H, L, d] device tensor (torch float32 / float16 / bfloat16,

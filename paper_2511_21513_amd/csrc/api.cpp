@@ -29,6 +29,8 @@ struct intattn_ctx {
     // kernel workspace (row max and row sum between the two launches, V chunk sums), grown on demand
     int32_t *d_ws = nullptr;
     size_t ws_cap = 0; // in int32 elements
+    int32_t *d_status = nullptr; // per head: what the last derivation on the device found (intattn_dynamic_status)
+    int status_cap = 0, status_n = 0;
     float *d_amax = nullptr; // scratch of the quantizer: partial max|X| per workgroup of its first pass
     int64_t amax_cap = 0;
     std::vector<HeadParams> hp_host;  // what d_hp currently holds
@@ -379,13 +381,16 @@ int ensure_workspace(intattn_ctx *ctx, size_t n_int32)
     return INTATTN_OK;
 }
 
-int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, int stage = 0)
+// dynamic: the scale pointers of `a` are DEVICE memory; the per-head parameters are derived by a
+// kernel on the stream and each head's index-map scheme is chosen there.
+int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, int stage = 0, bool dynamic = false)
 {
     int rc = validate(ctx, a);
     if (rc) return rc;
     if (ctx->device < 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "host-only context (device -1) cannot launch");
     Derived dv;
-    rc = derive_all(ctx, a, &dv);
+    if (dynamic) dv.idx_mode = IDX_DEVICE;
+    else rc = derive_all(ctx, a, &dv);
     if (rc) return rc;
 
     DeviceGuard guard(ctx->device);
@@ -408,7 +413,36 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
     std::memcpy(p.lut, ctx->lut, 32);
     p.dbg_row_max = a->dbg_row_max; p.dbg_row_sum = a->dbg_row_sum; p.dbg_acc = a->dbg_acc;
 
-    if (a->scale_mode == 0) {
+    if (dynamic) {
+        rc = ensure_tables(ctx, a->Hq);
+        if (rc) return rc;
+        if (a->Hq > ctx->status_cap) {
+            int32_t *st = nullptr;
+            const hipError_t e = hipMalloc((void **)&st, sizeof(int32_t) * (size_t)a->Hq);
+            if (e != hipSuccess) return fail(ctx, INTATTN_ERR_NOMEM, std::string("hipMalloc of the status words: ") + hipGetErrorString(e));
+            if (ctx->d_status) (void)hipFree(ctx->d_status);
+            ctx->d_status = st;
+            ctx->status_cap = a->Hq;
+        }
+        ctx->status_n = a->Hq;
+        DeriveParams dp;
+        std::memset(&dp, 0, sizeof(dp));
+        dp.scale_q = a->scale_q; dp.scale_k = a->scale_k; dp.scale_v = a->scale_v; dp.scale_out = a->scale_out;
+        dp.per_head = a->scale_mode;
+        dp.Hq = a->Hq;
+        dp.group = p.group;
+        dp.top = p.top;
+        dp.clip = ctx->clip;
+        dp.sqrt_d = std::sqrt((double)a->d);
+        dp.hp_table = ctx->d_hp;
+        dp.status = ctx->d_status;
+        ctx->hp_host.clear(); // the table no longer holds what the host last sent
+        if (stage != 2) { // stage 2 reads what stage 1 derived
+            const int e = launch_derive(dp, stream);
+            if (e != 0) return hip_fail(ctx, (hipError_t)e, "launch(derive head parameters)");
+        }
+        p.hp_table = ctx->d_hp;
+    } else if (a->scale_mode == 0) {
         p.hp_table = nullptr;
         p.hp0 = dv.hp[0];
         p.alpha0 = dv.alpha[0];
@@ -501,6 +535,27 @@ int intattn_forward_stage(intattn_ctx *ctx, const intattn_args *args, void *hip_
 {
     if (stage < 0 || stage > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "stage must be 0, 1 or 2");
     return run(ctx, args, hip_stream, false, stage);
+}
+
+int intattn_forward_dynamic(intattn_ctx *ctx, const intattn_args *args, void *hip_stream)
+{
+    return run(ctx, args, hip_stream, false, 0, true);
+}
+
+int intattn_dynamic_status(intattn_ctx *ctx, int32_t *status)
+{
+    if (!ctx) return INTATTN_ERR_INVALID_ARG;
+    if (!status) return fail(ctx, INTATTN_ERR_INVALID_ARG, "status is NULL");
+    *status = 0;
+    if (!ctx->d_status || ctx->status_n < 1) return INTATTN_OK; // no dynamic call yet
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return hip_fail(ctx, guard.status, "hipSetDevice");
+    std::vector<int32_t> words((size_t)ctx->status_n, 0);
+    const hipError_t e = hipMemcpy(words.data(), ctx->d_status, sizeof(int32_t) * words.size(), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipMemcpy(status)");
+    for (int32_t w : words)
+        if (w != 0) *status = 1;
+    return INTATTN_OK;
 }
 
 int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *a, void *hip_stream)
@@ -624,6 +679,7 @@ void intattn_destroy(intattn_ctx *ctx)
         if (ctx->d_svso) (void)hipFree(ctx->d_svso);
         if (ctx->d_ws) (void)hipFree(ctx->d_ws);
         if (ctx->d_amax) (void)hipFree(ctx->d_amax);
+        if (ctx->d_status) (void)hipFree(ctx->d_status);
     }
     delete ctx;
 }

@@ -1,0 +1,125 @@
+// Per-head kernel parameters from scales that live in DEVICE memory (as the dynamic quantizer
+// leaves them), so that quantizer and attention follow each other on a stream without the host
+// reading anything back:
+//   c_int = round(c * sqrt(d) / (s_Q s_K))                    (Sec. 3.1, Eq. clipping_thr)
+//   (M, sh) with M * 2^-sh ~ s_V / (255 s_O), M in [2^30, 2^31)   (output requantization)
+//   constants of an exact index map idx = round(x * top / c_int)  (Sec. 3.1, index map)
+// The arithmetic is the host's, operation for operation, in IEEE double: products, quotients,
+// floor, frexp and the fma are exactly rounded on the GPU as on the CPU, and sqrt(d) comes from the
+// host.  One wave per query head, one check point of the index map per lane.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "params.h"
+
+namespace intattn {
+
+namespace {
+
+__device__ __forceinline__ bool good_scale(float s) { return s > 0.0f && s < __builtin_inff(); } // false for NaN
+
+__device__ __forceinline__ uint32_t exact_index(uint64_t x, uint64_t c_int, uint64_t top)
+{
+    return (uint32_t)((2 * top * x + c_int) / (2 * c_int));
+}
+
+// One wave per query head; lane l holds one check point x of the index map: x = 0, x = c_int, and
+// both sides of each of the (at most 31) steps of the exact map.  Every map in question is a
+// monotone step function, so agreement at these points is agreement on all of [0, c_int].
+__global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
+{
+    const int h = blockIdx.x, lane = threadIdx.x;
+    const int si = dp.per_head ? h : 0;
+    const int kv = dp.per_head ? h / dp.group : 0;
+    const float sq = dp.scale_q[si], sk = dp.scale_k[kv], sv = dp.scale_v[kv];
+    const float so = dp.scale_out ? dp.scale_out[si] : sv;
+    HeadParams hp;
+    hp.pad[1] = 0;
+    bool ok = good_scale(sq) && good_scale(sk) && good_scale(sv) && good_scale(so);
+    // clip threshold, capped at 2^30 (beyond 62 * 2 * 128*128*128 every index is 0 anyway)
+    double c = 1.0;
+    if (ok) {
+        const double alpha = ((double)sq * (double)sk) / dp.sqrt_d;
+        c = __builtin_floor(dp.clip / alpha + 0.5);
+        if (!(c >= 1.0)) c = 1.0;
+        if (c > 1073741824.0) c = 1073741824.0;
+    }
+    hp.c_int = (int32_t)c;
+    // requantization multiplier
+    hp.rq_mult = 1 << 30;
+    hp.rq_shift = 31;
+    if (ok) {
+        const double r = (double)sv / (255.0 * (double)so);
+        int e = 0;
+        const double m = __builtin_frexp(r, &e);
+        long long M = __builtin_llround(m * 2147483648.0);
+        if (M == 2147483648LL) {
+            M = 1073741824LL;
+            e += 1;
+        }
+        const int sh = 31 - e;
+        if (!(r > 0.0) || sh < 1 || sh > 62) ok = false;
+        else {
+            hp.rq_mult = (int32_t)M;
+            hp.rq_shift = sh;
+        }
+    }
+
+    // this lane's check point
+    const uint32_t c_int = (uint32_t)hp.c_int, top = (uint32_t)dp.top;
+    uint32_t x = lane == 0 ? 0u : c_int;
+    bool have = lane < 2;
+    if (lane >= 2) {
+        const uint64_t k = (uint64_t)((lane - 2) >> 1) + 1;
+        const uint64_t t = ((2 * k - 1) * (uint64_t)c_int + 2ull * top - 1) / (2ull * top); // first x whose index is >= k
+        const uint32_t below = (uint32_t)(lane & 1);
+        have = k <= top && t <= c_int && t >= below;
+        x = (uint32_t)t - below;
+    }
+    const uint32_t want = exact_index(have ? x : 0u, c_int, top);
+
+    // fp32: trunc(fma(x, r, 0.5)) with r one of the three floats around top / c_int (x must be exact in fp32)
+    const uint32_t bits0 = __float_as_uint((float)((double)top / (double)c_int)) - 1u; // the float before (r > 0)
+    int found = -1;
+    if (c_int < (1u << 24)) {
+#pragma unroll
+        for (int step = 0; step < 3; ++step) {
+            const float r = __uint_as_float(bits0 + (uint32_t)step);
+            const bool match = !have || (uint32_t)(int)__builtin_fmaf(-(float)x, -r, 0.5f) == want;
+            if (found < 0 && __all(match)) found = step;
+        }
+    }
+    if (found >= 0) {
+        hp.pad[0] = IDX_FP32;
+        hp.idx_mul = (bits0 + (uint32_t)found) ^ 0x80000000u; // bits of -r
+        hp.idx_add = 0;
+        hp.idx_shift = 0;
+    } else {
+        // fp64 with r the double after top / c_int: exact for every c_int (the excess of r is under
+        // two units in the last place and the fma rounds once, monotonically; values of
+        // x*top/c_int + 1/2 that are not integers stay 1/(2 c_int) away from the next integer)
+        const uint64_t bits = (uint64_t)__double_as_longlong((double)top / (double)c_int) + 1ull;
+        const double r = __longlong_as_double((long long)bits);
+        const bool match = !have || (uint32_t)(int)__builtin_fma(-(double)x, -r, 0.5) == want;
+        if (!__all(match)) ok = false;
+        const uint64_t neg = bits ^ 0x8000000000000000ull;
+        hp.pad[0] = IDX_FP64;
+        hp.idx_mul = (uint32_t)neg;
+        hp.idx_add = (uint32_t)(neg >> 32);
+        hp.idx_shift = 0;
+    }
+    if (lane == 0) {
+        dp.hp_table[h] = hp;
+        dp.status[h] = ok ? 0 : 1;
+    }
+}
+
+} // namespace
+
+int launch_derive(const DeriveParams &dp, void *stream)
+{
+    hipLaunchKernelGGL(derive_kernel, dim3((unsigned)dp.Hq), dim3(64), 0, (hipStream_t)stream, dp);
+    return (int)hipGetLastError();
+}
+
+} // namespace intattn

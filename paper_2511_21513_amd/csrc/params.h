@@ -12,7 +12,8 @@ enum IdxMode : int32_t {
                     // (idx_mul, idx_add hold the low and high word of the bits of -r)
     IDX_MAD24 = 1,  // (Delta' * mul + add) >> shift, 24-bit operands, 32-bit result
     IDX_MULHI24 = 2,// high 32 bits of the 48-bit product ((Delta' << pre) + add) * mul
-    IDX_FP32 = 3    // trunc(fma(Delta', top/c_int, 0.5)) in IEEE fp32 (idx_mul holds the bits of -top/c_int)
+    IDX_FP32 = 3,   // trunc(fma(Delta', top/c_int, 0.5)) in IEEE fp32 (idx_mul holds the bits of -top/c_int)
+    IDX_DEVICE = 4  // launchers only: each head's scheme (FP32 or FP64) is in its HeadParams, written on the device
 };
 
 // Per query head: everything the kernel needs that depends on the scales.
@@ -23,7 +24,7 @@ struct HeadParams {
     int32_t idx_shift; // MAD24: right shift; MULHI24: left pre-shift of Delta'
     int32_t rq_mult;   // output requantization multiplier M in [2^30, 2^31)
     int32_t rq_shift;  // output requantization shift sh in [1, 62]
-    int32_t pad[2];
+    int32_t pad[2];    // pad[0]: this head's IdxMode when the table was derived on the device
 };
 
 struct FwdParams {
@@ -35,7 +36,8 @@ struct FwdParams {
     int32_t group;       // Hq / Hkv
     int32_t top;         // 2^b - 1
     int32_t n_qtiles;    // ceil(L / rows per workgroup)
-    const HeadParams *hp_table; // device [Hq] when per-head, else nullptr
+    const HeadParams *hp_table; // device [Hq] when per-head or derived on the device, else nullptr
+    int32_t filter;             // 1: a workgroup whose head's HeadParams name another scheme than the kernel's returns at once
     HeadParams hp0;             // the single parameter set when hp_table == nullptr
     uint32_t lut[8];            // LUT_hat, 32 bytes packed little-endian (unused tail is 0)
     int32_t *dbg_row_max, *dbg_row_sum, *dbg_acc;
@@ -61,6 +63,16 @@ struct QuantParams {
     int32_t n_partial;
 };
 
+// Arguments of the derivation of HeadParams from device-resident scales.
+struct DeriveParams {
+    const float *scale_q, *scale_k, *scale_v, *scale_out; // device; scale_out may be null (= scale_v)
+    int32_t per_head;      // 0: one value each; 1: scale_q/out per query head, scale_k/v per KV head
+    int32_t Hq, group, top;
+    double clip, sqrt_d;
+    HeadParams *hp_table;  // device [Hq] (out; all heads also when the scales are per tensor)
+    int32_t *status;       // device [Hq] (out): 1 where a head's scales were unusable, else 0
+};
+
 // Launchers implemented in the .hip files.  Return a hipError_t cast to int.
 // stage 0: everything; 1: V column sums + sweeps A+B; 2: sweep C (two-launch variants only; else hipErrorNotSupported)
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, void *stream);
@@ -71,6 +83,7 @@ int fwd_rows_per_block(int variant);
 bool fwd_variant_known(int variant);
 int quantize_partials_per_slice(int B, int H, int L, int d);
 int launch_quantize(const QuantParams &p, void *stream);
+int launch_derive(const DeriveParams &dp, void *stream);
 int launch_quantonly(const FwdParams &p, int d, int variant, void *stream);
 
 } // namespace intattn

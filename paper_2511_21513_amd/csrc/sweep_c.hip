@@ -75,6 +75,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     const int b = wi.b, hq = wi.hq, kvh = wi.kvh, qt = wi.qt;
     const int bh = b * p.Hq + hq;
     const HeadParams hp = p.hp_table ? p.hp_table[hq] : p.hp0;
+    if (p.filter && hp.pad[0] != MODE) return; // another launch of this pair serves the head (uniform for the workgroup)
     const int L = p.L;
     const uint32_t top = (uint32_t)p.top;
 
@@ -374,6 +375,15 @@ template <int D, int RB, bool CAUSAL>
 int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
 {
     const dim3 grid((unsigned)fwd_grid_size(p.B, p.Hq, p.Hkv, p.n_qtiles)), block(NT);
+    if (idx_mode == IDX_DEVICE) {
+        // the scheme of each head is known on the device only: one launch per scheme, each
+        // skipping the heads of the other
+        FwdParams pf = p;
+        pf.filter = 1;
+        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_FP32>), grid, block, 0, st, pf);
+        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_FP64>), grid, block, 0, st, pf);
+        return (int)hipGetLastError();
+    }
     if (idx_mode == IDX_MAD24)
         hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_MAD24>), grid, block, 0, st, p);
     else if (idx_mode == IDX_MULHI24)

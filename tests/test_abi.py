@@ -225,3 +225,13 @@ def test_quantize_rejects_bad_arguments_without_a_gpu(host_ctx, lib):
     assert lib.intattn_quantize(ctx, None, None) == binding.ERR_INVALID_ARG
     assert lib.intattn_quantize(ctx, ctypes.byref(a), None) == binding.ERR_UNSUPPORTED
     assert lib.intattn_quantize(None, ctypes.byref(a), None) == binding.ERR_INVALID_ARG
+
+
+def test_dynamic_forward_needs_a_device(host_ctx, lib):
+    """The device-scale entry validates like the plain forward and refuses a host-only context;
+    the status word of a context that never ran it reads 0."""
+    a = binding.Args()
+    assert lib.intattn_forward_dynamic(host_ctx._ctx, None, None) == binding.ERR_INVALID_ARG
+    assert lib.intattn_forward_dynamic(host_ctx._ctx, ctypes.byref(a), None) == binding.ERR_INVALID_ARG
+    assert host_ctx.dynamic_status() == 0
+    assert lib.intattn_dynamic_status(host_ctx._ctx, None) == binding.ERR_INVALID_ARG

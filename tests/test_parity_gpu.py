@@ -350,3 +350,123 @@ def test_quantizer_feeds_the_forward(torch_mod, oracle):
     want = oracle.forward(oq, ok, ov, osq, osk, osv, None, causal=True)["out"]
     assert int((out.cpu().numpy() != want).sum()) == 0
     ia.close()
+
+
+# ---------------------------------------------------------------- forward with device-resident scales
+
+def dynamic_forward(torch, ia, p, s_o=None):
+    """intattn_forward_dynamic with the problem's scales copied to the GPU; returns (out, status)."""
+    dev = torch.device("cuda:0")
+    q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
+    scales = [torch.from_numpy(np.ascontiguousarray(s, dtype=np.float32)).to(dev) if s is not None else None
+              for s in (p.s_q, p.s_k, p.s_v, s_o)]
+    out = torch.empty_like(q)
+    args, keep = ia.make_args(q, k, v, out, *scales, causal=p.causal, per_head=p.per_head, device_scales=True)
+    ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), ia.dynamic_status()
+
+
+DYN_SHAPES = [
+    # B, Hq, Hkv, L, d, causal, per_head, scale multiplier on s_q (moves c_int between the schemes)
+    (1, 1, 1, 1, 64, False, False, 1.0),
+    (2, 4, 2, 97, 128, True, True, 1.0),
+    (1, 4, 1, 197, 64, False, False, 0.01),
+    (1, 2, 2, 300, 128, True, False, 1e-4),
+    (1, 6, 2, 515, 64, True, True, 1.0),
+]
+
+
+@pytest.mark.parametrize("shape", DYN_SHAPES, ids=lambda s: "B{}Hq{}Hkv{}L{}d{}c{}ph{}x{}".format(*s))
+def test_dynamic_forward_bit_exact(torch_mod, ia, oracle, shape):
+    """Scales in device memory, parameters derived by a kernel: the same bytes as the oracle computes
+    from the same scale values, for every kernel variant, with and without an output scale."""
+    B, Hq, Hkv, L, d, causal, per_head, mul = shape
+    print(f"case {shape}", flush=True)
+    p = inputs.random_problem(300 + L + d, B, Hq, Hkv, L, d, causal, per_head=per_head, spread=1.5)
+    p.s_q = (p.s_q * mul).astype(np.float32)
+    for s_o in (None, inputs.calibrated_out_scale(p)):
+        got, status = dynamic_forward(torch_mod, ia, p, s_o)
+        want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, s_o, causal=p.causal, per_head=p.per_head)["out"]
+        assert status == 0
+        assert int((got != want).sum()) == 0
+
+
+def test_dynamic_forward_mixed_schemes(torch_mod, ia, oracle):
+    """Per-head scales that put some heads in reach of the fp32 index map and others beyond it:
+    each head is served by exactly one of the two launches of a kernel."""
+    p = inputs.random_problem(41, 2, 8, 4, 260, 64, True, per_head=True, spread=1.5)
+    p.s_q = (p.s_q * np.asarray([1, 1e-2, 1, 1e-3, 3e-3, 1, 2e-5, 1], dtype=np.float32)).astype(np.float32)
+    cs = [oracle.c_int(6.6, p.s_q[h], p.s_k[h // 2], 64) for h in range(8)]
+    print("c_int per head", cs, flush=True)
+    assert min(cs) < 300000 and max(cs) > 2**24
+    got, status = dynamic_forward(torch_mod, ia, p)
+    want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, None, causal=True, per_head=True)["out"]
+    assert status == 0
+    assert int((got != want).sum()) == 0
+
+
+def test_dynamic_forward_on_the_workload_configs(torch_mod, oracle):
+    """Two of the workload configurations in full, through the automatic variant."""
+    from paper_2511_21513_amd import binding
+
+    ia = binding.IntAttn(device=0)
+    for name in ("c2_vit_b16", "c3_llm_prefill_2k"):
+        p = inputs.make_problem(name)
+        got, status = dynamic_forward(torch_mod, ia, p)
+        want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, None, causal=p.causal, per_head=p.per_head)["out"]
+        assert status == 0 and int((got != want).sum()) == 0, name
+    ia.close()
+
+
+def test_dynamic_forward_reports_unusable_scales(torch_mod, oracle):
+    """A zero, negative, infinite or NaN scale cannot come back as a return code (the host never
+    reads it): the status word says so, nothing faults, and the next good call clears it."""
+    from paper_2511_21513_amd import binding
+
+    ia = binding.IntAttn(device=0)
+    assert ia.dynamic_status() == 0  # before any call
+    p = inputs.random_problem(43, 1, 4, 2, 130, 64, False, per_head=True)
+    good = p.s_q.copy()
+    for bad in (0.0, -1.0, np.inf, np.nan):
+        p.s_q = good.copy()
+        p.s_q[2] = bad
+        got, status = dynamic_forward(torch_mod, ia, p)
+        assert status == 1
+        # the other heads are untouched by it
+        p.s_q = good.copy()
+        want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, None, causal=False, per_head=True)["out"]
+        keep = [0, 1, 3]
+        assert int((got[:, keep] != want[:, keep]).sum()) == 0
+    p.s_q = good
+    got, status = dynamic_forward(torch_mod, ia, p)
+    assert status == 0 and int((got != want).sum()) == 0
+    ia.close()
+
+
+def test_quantizer_to_dynamic_forward_without_host_reads(torch_mod, oracle):
+    """fp16 Q, K, V -> on-GPU quantizer (per head) -> dynamic forward, all enqueued before the
+    first synchronization: the bytes of the oracle quantizer followed by the oracle forward."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    rng = np.random.default_rng(79)
+    B, Hq, Hkv, L, d = 2, 4, 2, 333, 128
+    dev = torch.device("cuda:0")
+    qf = torch.from_numpy(rng.standard_normal((B, Hq, L, d)).astype(np.float32)).to(dev).half()
+    kf = torch.from_numpy(rng.standard_normal((B, Hkv, L, d)).astype(np.float32)).to(dev).half()
+    vf = torch.from_numpy(rng.standard_normal((B, Hkv, L, d)).astype(np.float32)).to(dev).half()
+    ia = binding.IntAttn(device=0)
+    for per_head in (False, True):
+        (q, sq), (k, sk), (v, sv) = (ia.quantize(t, per_head=per_head) for t in (qf, kf, vf))
+        out = torch.empty_like(q)
+        args, keep = ia.make_args(q, k, v, out, sq, sk, sv, None, causal=True, per_head=per_head, device_scales=True)
+        ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
+        torch.cuda.synchronize()
+        assert ia.dynamic_status() == 0
+        oq, osq = oracle.quantize(qf.float().cpu().numpy(), per_head=per_head)
+        ok, osk = oracle.quantize(kf.float().cpu().numpy(), per_head=per_head)
+        ov, osv = oracle.quantize(vf.float().cpu().numpy(), per_head=per_head)
+        want = oracle.forward(oq, ok, ov, osq, osk, osv, None, causal=True, per_head=per_head)["out"]
+        assert int((out.cpu().numpy() != want).sum()) == 0
+    ia.close()

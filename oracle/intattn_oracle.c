@@ -26,6 +26,11 @@
  *     has a scale.
  *   - causal masking: key j is visible to query i iff j <= i; hidden keys take
  *     no part in rowMax or rowSum and get P = 0.
+ *   - rectangular shapes (L query rows against Lk != L keys; the paper states
+ *     the square case only): every row is processed as before over its visible
+ *     keys; a causal mask is aligned to the end, key j visible to query i iff
+ *     j <= i + (Lk - L), which needs Lk >= L.  Pinned to the square problem (the
+ *     last L rows of the Lk x Lk problem are these rows).
  *   - grouped-query attention: query head h reads KV head h / (Hq/Hkv).
  *   - the output is requantized with a fixed-point multiplier (M, sh) that
  *     encodes r = s_V / (255 * s_O)  (Eq. pv-link with P = P_hat/255):
@@ -123,15 +128,15 @@ int64_t intattn_oracle_prob(int64_t e, int64_t row_sum)
 }
 
 typedef struct {
-    int L, d, causal, lut_bits;
+    int L, Lk, d, causal, lut_bits; /* L query rows, Lk keys */
     const int8_t *q;   /* [L, d] of this query head  */
-    const int8_t *k;   /* [L, d] of the KV head      */
-    const int8_t *v;   /* [L, d] of the KV head      */
+    const int8_t *k;   /* [Lk, d] of the KV head     */
+    const int8_t *v;   /* [Lk, d] of the KV head     */
     const uint8_t *lut;
     int64_t c_int;
     int64_t rq_mult;
     int32_t rq_shift;
-    /* scratch, length L each */
+    /* scratch, length Lk each */
     int64_t *a;
     int64_t *e;
     int64_t *p;
@@ -142,8 +147,10 @@ static void oracle_row(const head_ctx *h, int i, int8_t *out /* [d] */, int32_t 
                        int32_t *row_sum, int32_t *acc_out /* [d] or NULL */,
                        uint8_t *prob_out /* [L] or NULL */)
 {
-    const int L = h->L, d = h->d;
-    const int n_vis = h->causal ? (i + 1) : L; /* visible keys are 0 .. n_vis-1 */
+    const int L = h->Lk, d = h->d;
+    /* visible keys are 0 .. n_vis-1; with Lk != L the causal mask is aligned to the end (the last
+     * query row sees every key): row i sees keys j <= i + (Lk - L) */
+    const int n_vis = h->causal ? (i + (h->Lk - h->L) + 1) : L;
 
     /* Eq. logit-scale: A_hat[i, j] = sum_k Q_hat[i, k] * K_hat[j, k] */
     for (int j = 0; j < n_vis; ++j) {
@@ -188,18 +195,19 @@ static void oracle_row(const head_ctx *h, int i, int8_t *out /* [d] */, int32_t 
     }
 }
 
-static int check_problem(int B, int Hq, int Hkv, int L, int d, int lut_bits, double clip,
+static int check_problem(int B, int Hq, int Hkv, int L, int Lk, int causal, int d, int lut_bits, double clip,
                          const void *q, const void *k, const void *v, const float *sq,
                          const float *sk, const float *sv)
 {
-    if (B < 1 || Hq < 1 || Hkv < 1 || L < 1 || d < 1) return ORACLE_BAD_ARG;
+    if (B < 1 || Hq < 1 || Hkv < 1 || L < 1 || Lk < 1 || d < 1) return ORACLE_BAD_ARG;
+    if (causal && Lk < L) return ORACLE_BAD_ARG; /* a row without a visible key has no softmax */
     if (Hq % Hkv != 0) return ORACLE_BAD_ARG;
     if (lut_bits < 1 || lut_bits > 8 || !(clip > 0.0)) return ORACLE_BAD_ARG;
     if (!q || !k || !v || !sq || !sk || !sv) return ORACLE_BAD_ARG;
     return ORACLE_OK;
 }
 
-static int head_setup(head_ctx *hc, int Hq, int Hkv, int L, int d, int causal, int b, int hq,
+static int head_setup(head_ctx *hc, int Hq, int Hkv, int L, int Lk, int d, int causal, int b, int hq,
                       const int8_t *q, const int8_t *k, const int8_t *v, int scale_mode,
                       const float *sq, const float *sk, const float *sv, const float *so,
                       int lut_bits, double clip, const uint8_t *lut)
@@ -212,12 +220,13 @@ static int head_setup(head_ctx *hc, int Hq, int Hkv, int L, int d, int causal, i
     const float s_o = so ? (scale_mode ? so[hq] : so[0]) : s_v;
     if (!(s_q > 0.0f) || !(s_k > 0.0f)) return ORACLE_BAD_ARG;
     hc->L = L;
+    hc->Lk = Lk;
     hc->d = d;
     hc->causal = causal;
     hc->lut_bits = lut_bits;
     hc->q = q + ((size_t)b * Hq + hq) * (size_t)L * d;
-    hc->k = k + ((size_t)b * Hkv + kv) * (size_t)L * d;
-    hc->v = v + ((size_t)b * Hkv + kv) * (size_t)L * d;
+    hc->k = k + ((size_t)b * Hkv + kv) * (size_t)Lk * d;
+    hc->v = v + ((size_t)b * Hkv + kv) * (size_t)Lk * d;
     hc->lut = lut;
     hc->c_int = intattn_oracle_c_int(clip, s_q, s_k, d);
     return intattn_oracle_requant_params(s_v, s_o, &hc->rq_mult, &hc->rq_shift);
@@ -228,20 +237,22 @@ static int head_setup(head_ctx *hc, int Hq, int Hkv, int L, int d, int causal, i
  * the query rows [row_begin, row_end); everything outside is left untouched, so
  * a harness may fan disjoint ranges over host threads.
  *
- * q: [B,Hq,L,d]  k, v: [B,Hkv,L,d]  out: [B,Hq,L,d]   (contiguous, HOST pointers)
+ * q: [B,Hq,L,d]  k, v: [B,Hkv,Lk,d]  out: [B,Hq,L,d]   (contiguous, HOST pointers)
+ * Lk != L: rectangular attention (a chunk of queries, or one decoded token, against a longer
+ * key/value sequence); the causal mask is then aligned to the end and needs Lk >= L.
  * scale_mode 0: sq/sk/sv/so hold one float; 1: sq/so hold Hq floats, sk/sv hold Hkv.
  * so == NULL means s_O = s_V of the matching KV head.
  * Optional taps (NULL to skip): row_max, row_sum [B,Hq,L]; acc [B,Hq,L,d];
- * prob [B,Hq,L,L] (tiny problems only).
+ * prob [B,Hq,L,Lk] (tiny problems only).
  */
-int intattn_oracle_forward(int B, int Hq, int Hkv, int L, int d, int causal, const int8_t *q,
+int intattn_oracle_forward(int B, int Hq, int Hkv, int L, int Lk, int d, int causal, const int8_t *q,
                            const int8_t *k, const int8_t *v, int scale_mode, const float *sq,
                            const float *sk, const float *sv, const float *so, int lut_bits,
                            double clip, int bh_begin, int bh_end, int row_begin, int row_end,
                            int8_t *out, int32_t *row_max, int32_t *row_sum, int32_t *acc,
                            uint8_t *prob)
 {
-    int rc = check_problem(B, Hq, Hkv, L, d, lut_bits, clip, q, k, v, sq, sk, sv);
+    int rc = check_problem(B, Hq, Hkv, L, Lk, causal, d, lut_bits, clip, q, k, v, sq, sk, sv);
     if (rc) return rc;
     if (!out || bh_begin < 0 || bh_end > B * Hq || row_begin < 0 || row_end > L) return ORACLE_BAD_ARG;
 
@@ -250,23 +261,23 @@ int intattn_oracle_forward(int B, int Hq, int Hkv, int L, int d, int causal, con
     if (rc) return rc;
 
     head_ctx hc;
-    hc.a = (int64_t *)malloc(sizeof(int64_t) * (size_t)L);
-    hc.e = (int64_t *)malloc(sizeof(int64_t) * (size_t)L);
-    hc.p = (int64_t *)malloc(sizeof(int64_t) * (size_t)L);
+    hc.a = (int64_t *)malloc(sizeof(int64_t) * (size_t)Lk);
+    hc.e = (int64_t *)malloc(sizeof(int64_t) * (size_t)Lk);
+    hc.p = (int64_t *)malloc(sizeof(int64_t) * (size_t)Lk);
     if (!hc.a || !hc.e || !hc.p) {
         free(hc.a); free(hc.e); free(hc.p);
         return ORACLE_NO_MEM;
     }
     for (int bh = bh_begin; bh < bh_end && rc == ORACLE_OK; ++bh) {
         const int b = bh / Hq, hq = bh % Hq;
-        rc = head_setup(&hc, Hq, Hkv, L, d, causal, b, hq, q, k, v, scale_mode, sq, sk, sv, so,
+        rc = head_setup(&hc, Hq, Hkv, L, Lk, d, causal, b, hq, q, k, v, scale_mode, sq, sk, sv, so,
                         lut_bits, clip, lut);
         if (rc) break;
         for (int i = row_begin; i < row_end; ++i) {
             size_t row = (size_t)bh * L + i;
             oracle_row(&hc, i, out + row * d, row_max ? row_max + row : NULL,
                        row_sum ? row_sum + row : NULL, acc ? acc + row * d : NULL,
-                       prob ? prob + row * L : NULL);
+                       prob ? prob + row * Lk : NULL);
         }
     }
     free(hc.a); free(hc.e); free(hc.p);
@@ -278,13 +289,13 @@ int intattn_oracle_forward(int B, int Hq, int Hkv, int L, int d, int causal, con
  * sample: out [n_rows, d], row_max / row_sum [n_rows], acc [n_rows, d].
  * Used to check full-size problems on sampled rows.
  */
-int intattn_oracle_rows(int B, int Hq, int Hkv, int L, int d, int causal, const int8_t *q,
+int intattn_oracle_rows(int B, int Hq, int Hkv, int L, int Lk, int d, int causal, const int8_t *q,
                         const int8_t *k, const int8_t *v, int scale_mode, const float *sq,
                         const float *sk, const float *sv, const float *so, int lut_bits,
                         double clip, int b, int hq, int n_rows, const int32_t *rows, int8_t *out,
                         int32_t *row_max, int32_t *row_sum, int32_t *acc)
 {
-    int rc = check_problem(B, Hq, Hkv, L, d, lut_bits, clip, q, k, v, sq, sk, sv);
+    int rc = check_problem(B, Hq, Hkv, L, Lk, causal, d, lut_bits, clip, q, k, v, sq, sk, sv);
     if (rc) return rc;
     if (!out || !rows || b < 0 || b >= B || hq < 0 || hq >= Hq || n_rows < 0) return ORACLE_BAD_ARG;
 
@@ -293,14 +304,14 @@ int intattn_oracle_rows(int B, int Hq, int Hkv, int L, int d, int causal, const 
     if (rc) return rc;
 
     head_ctx hc;
-    hc.a = (int64_t *)malloc(sizeof(int64_t) * (size_t)L);
-    hc.e = (int64_t *)malloc(sizeof(int64_t) * (size_t)L);
-    hc.p = (int64_t *)malloc(sizeof(int64_t) * (size_t)L);
+    hc.a = (int64_t *)malloc(sizeof(int64_t) * (size_t)Lk);
+    hc.e = (int64_t *)malloc(sizeof(int64_t) * (size_t)Lk);
+    hc.p = (int64_t *)malloc(sizeof(int64_t) * (size_t)Lk);
     if (!hc.a || !hc.e || !hc.p) {
         free(hc.a); free(hc.e); free(hc.p);
         return ORACLE_NO_MEM;
     }
-    rc = head_setup(&hc, Hq, Hkv, L, d, causal, b, hq, q, k, v, scale_mode, sq, sk, sv, so,
+    rc = head_setup(&hc, Hq, Hkv, L, Lk, d, causal, b, hq, q, k, v, scale_mode, sq, sk, sv, so,
                     lut_bits, clip, lut);
     for (int s = 0; s < n_rows && rc == ORACLE_OK; ++s) {
         int i = rows[s];

@@ -47,11 +47,11 @@ def _load():
             lib.intattn_oracle_prob.argtypes = [i64, i64]
             lib.intattn_oracle_prob.restype = i64
             lib.intattn_oracle_forward.argtypes = (
-                [i32] * 6 + [vp] * 3 + [i32] + [vp] * 4 + [i32, dbl] + [i32] * 4 + [vp] * 5
+                [i32] * 7 + [vp] * 3 + [i32] + [vp] * 4 + [i32, dbl] + [i32] * 4 + [vp] * 5
             )
             lib.intattn_oracle_forward.restype = i32
             lib.intattn_oracle_rows.argtypes = (
-                [i32] * 6 + [vp] * 3 + [i32] + [vp] * 4 + [i32, dbl] + [i32] * 3 + [vp] * 5
+                [i32] * 7 + [vp] * 3 + [i32] + [vp] * 4 + [i32, dbl] + [i32] * 3 + [vp] * 5
             )
             lib.intattn_oracle_rows.restype = i32
             lib.intattn_oracle_quantize.argtypes = [i32] * 4 + [vp, i32, vp, vp]
@@ -104,19 +104,20 @@ def _check_inputs(q, k, v):
             raise ValueError(f"{name} must be a C-contiguous int8 [B,H,L,d] array")
     B, Hq, L, d = q.shape
     Bk, Hkv, Lk, dk = k.shape
-    if (Bk, Lk, dk) != (B, L, d) or v.shape != k.shape:
+    if (Bk, dk) != (B, d) or v.shape != k.shape:
         raise ValueError("shape mismatch between q, k, v")
-    return B, Hq, Hkv, L, d
+    return B, Hq, Hkv, L, Lk, d
 
 
 def forward(q, k, v, s_q, s_k, s_v, s_o=None, *, causal=False, per_head=False, lut_bits=5, clip=6.6,
             taps=False, want_prob=False, threads=1, rows_range=None):
     """Run the oracle over all (b, h).  Returns a dict with ``out`` (int8 [B,Hq,L,d]) and,
     with ``taps``, ``row_max``/``row_sum`` (int32 [B,Hq,L]) and ``acc`` (int32 [B,Hq,L,d]);
-    with ``want_prob``, ``prob`` (uint8 [B,Hq,L,L]).  ``threads`` fans heads over host threads
+    with ``want_prob``, ``prob`` (uint8 [B,Hq,L,Lk]).  k and v may hold Lk != L keys (then a causal
+    mask is aligned to the end: row i sees keys j <= i + Lk - L).  ``threads`` fans heads over host threads
     (the C call releases the GIL); each thread runs the same single-threaded row routine."""
     lib = _load()
-    B, Hq, Hkv, L, d = _check_inputs(q, k, v)
+    B, Hq, Hkv, L, Lk, d = _check_inputs(q, k, v)
     sq, sk, sv, so = _f32(s_q), _f32(s_k), _f32(s_v), _f32(s_o)
     if per_head:
         if sq.size != Hq or sk.size != Hkv or sv.size != Hkv or (so is not None and so.size != Hq):
@@ -128,12 +129,12 @@ def forward(q, k, v, s_q, s_k, s_v, s_o=None, *, causal=False, per_head=False, l
         res["row_sum"] = np.zeros((B, Hq, L), dtype=np.int32)
         res["acc"] = np.zeros((B, Hq, L, d), dtype=np.int32)
     if want_prob:
-        res["prob"] = np.zeros((B, Hq, L, L), dtype=np.uint8)
+        res["prob"] = np.zeros((B, Hq, L, Lk), dtype=np.uint8)
     r0, r1 = (0, L) if rows_range is None else rows_range
 
     def run(bh0, bh1):
         rc = lib.intattn_oracle_forward(
-            B, Hq, Hkv, L, d, int(bool(causal)), _ptr(q), _ptr(k), _ptr(v), int(bool(per_head)),
+            B, Hq, Hkv, L, Lk, d, int(bool(causal)), _ptr(q), _ptr(k), _ptr(v), int(bool(per_head)),
             _ptr(sq), _ptr(sk), _ptr(sv), _ptr(so), lut_bits, clip, bh0, bh1, r0, r1, _ptr(out),
             _ptr(res.get("row_max")), _ptr(res.get("row_sum")), _ptr(res.get("acc")), _ptr(res.get("prob")),
         )
@@ -157,7 +158,7 @@ def rows(q, k, v, s_q, s_k, s_v, s_o=None, *, b, hq, rows, causal=False, per_hea
     """Selected query rows of one (b, hq).  Returns dict: out [n,d] int8, row_max/row_sum [n] int32,
     acc [n,d] int32."""
     lib = _load()
-    B, Hq, Hkv, L, d = _check_inputs(q, k, v)
+    B, Hq, Hkv, L, Lk, d = _check_inputs(q, k, v)
     sq, sk, sv, so = _f32(s_q), _f32(s_k), _f32(s_v), _f32(s_o)
     idx = np.ascontiguousarray(np.asarray(rows, dtype=np.int32))
     n = idx.size
@@ -168,7 +169,7 @@ def rows(q, k, v, s_q, s_k, s_v, s_o=None, *, b, hq, rows, causal=False, per_hea
         "acc": np.zeros((n, d), dtype=np.int32),
     }
     rc = lib.intattn_oracle_rows(
-        B, Hq, Hkv, L, d, int(bool(causal)), _ptr(q), _ptr(k), _ptr(v), int(bool(per_head)), _ptr(sq),
+        B, Hq, Hkv, L, Lk, d, int(bool(causal)), _ptr(q), _ptr(k), _ptr(v), int(bool(per_head)), _ptr(sq),
         _ptr(sk), _ptr(sv), _ptr(so), lut_bits, clip, b, hq, n, _ptr(idx), _ptr(res["out"]),
         _ptr(res["row_max"]), _ptr(res["row_sum"]), _ptr(res["acc"]),
     )

@@ -472,3 +472,52 @@ def test_quantizer_reproduces_the_input_recipe(oracle):
         b, sb = inputs.quantize(x, per_head)
         np.testing.assert_array_equal(a, b)
         np.testing.assert_array_equal(sa, sb)
+
+
+# ----------------------------------------------------------------------------- rectangular shapes (Lq != Lk)
+# The paper states the method for square self-attention only; a chunk of queries or one decoded
+# token against a longer key/value sequence is this build's reading: nothing changes per row, and
+# a causal mask is aligned to the end (the last query sees every key).  Pinned to the square case.
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("lq", [1, 5, 22])
+def test_rectangular_is_the_tail_of_the_square_problem(oracle, causal, lq):
+    """Queries = the last lq rows of a square problem over the same keys: identical rows."""
+    p = inputs.random_problem(51, 2, 4, 2, 37, 8, causal, per_head=True)
+    sq = run(oracle, p, taps=True, want_prob=True)
+    q_tail = np.ascontiguousarray(p.q[:, :, p.L - lq:])
+    r = oracle.forward(q_tail, p.k, p.v, p.s_q, p.s_k, p.s_v, causal=causal, per_head=True, taps=True, want_prob=True)
+    for key in ("out", "row_max", "row_sum", "acc", "prob"):
+        np.testing.assert_array_equal(r[key], sq[key][:, :, p.L - lq:])
+
+
+def test_rectangular_against_rational_python(oracle):
+    """More queries than keys (no mask) and fewer (mask aligned to the end), row by row in exact rationals."""
+    lut = oracle.lut()
+    for (lq, lk, causal) in ((9, 4, False), (3, 11, True), (1, 6, True)):
+        base = inputs.random_problem(60 + lq, 1, 1, 1, max(lq, lk), 8, causal)
+        q = np.ascontiguousarray(base.q[:, :, :lq])
+        k = np.ascontiguousarray(base.k[:, :, :lk])
+        v = np.ascontiguousarray(base.v[:, :, :lk])
+        r = oracle.forward(q, k, v, base.s_q, base.s_k, base.s_v, causal=causal, taps=True, want_prob=True)
+        ci = oracle.c_int(CLIP, base.s_q[0], base.s_k[0], 8)
+        rq = oracle.requant_params(base.s_v[0], base.s_v[0])
+        assert r["prob"].shape == (1, 1, lq, lk)
+        for i in range(lq):
+            n_vis = i + (lk - lq) + 1 if causal else lk
+            m, s, pr, acc, out = python_reference_row(q[0, 0, i], k[0, 0], v[0, 0], n_vis, ci, lut, rq)
+            assert r["row_max"][0, 0, i] == m and r["row_sum"][0, 0, i] == s
+            assert list(r["prob"][0, 0, i, :n_vis]) == pr and not r["prob"][0, 0, i, n_vis:].any()
+            assert list(r["acc"][0, 0, i]) == acc and list(r["out"][0, 0, i]) == out
+
+
+def test_rectangular_rows_entry_and_bad_shapes(oracle):
+    p = inputs.random_problem(53, 1, 2, 1, 40, 8, True)
+    q = np.ascontiguousarray(p.q[:, :, 25:])
+    full = oracle.forward(q, p.k, p.v, p.s_q, p.s_k, p.s_v, causal=True, taps=True)
+    some = oracle.rows(q, p.k, p.v, p.s_q, p.s_k, p.s_v, b=0, hq=1, rows=[0, 7, 14], causal=True)
+    np.testing.assert_array_equal(some["out"], full["out"][0, 1, [0, 7, 14]])
+    np.testing.assert_array_equal(some["row_sum"], full["row_sum"][0, 1, [0, 7, 14]])
+    # a causal row without a visible key has no softmax: more queries than keys is refused
+    with pytest.raises(ValueError):
+        oracle.forward(p.q, np.ascontiguousarray(p.k[:, :, :30]), np.ascontiguousarray(p.v[:, :, :30]),
+                       p.s_q, p.s_k, p.s_v, causal=True)

@@ -68,15 +68,20 @@ typedef struct {
  * host scale arrays are read before the call returns.
  */
 typedef struct {
-    int32_t B, Hq, Hkv, L, d; /* Hq % Hkv == 0; d in {64, 128}; 1 <= L <= 131071            */
+    int32_t B, Hq, Hkv, L, d; /* Hq % Hkv == 0; d in {64, 128}; 1 <= L <= 131071 query rows   */
     int32_t causal;           /* 0 or 1                                                       */
     const int8_t *q;          /* DEVICE  [B, Hq,  L, d]                                       */
-    const int8_t *k;          /* DEVICE  [B, Hkv, L, d]                                       */
-    const int8_t *v;          /* DEVICE  [B, Hkv, L, d]                                       */
+    const int8_t *k;          /* DEVICE  [B, Hkv, Lkv, d]                                     */
+    const int8_t *v;          /* DEVICE  [B, Hkv, Lkv, d]                                     */
     int8_t *out;              /* DEVICE  [B, Hq,  L, d]                                       */
     int64_t q_stride[3], k_stride[3], v_stride[3], out_stride[3];
     int32_t scale_mode;       /* 0: one float per scale array; 1: per head ([Hq] for q and
                                  out, [Hkv] for k and v), shared over the batch               */
+    int32_t Lkv;              /* number of keys / values; 0 means L (square self-attention).
+                                 Lkv != L: a chunk of queries, or one decoded token, against a
+                                 longer (or, without mask, any) key sequence; the causal mask
+                                 is then aligned to the end, key j visible to query i iff
+                                 j <= i + Lkv - L, and needs Lkv >= L                         */
     const float *scale_q;     /* HOST */
     const float *scale_k;     /* HOST */
     const float *scale_v;     /* HOST */

@@ -56,7 +56,7 @@ class Args(ctypes.Structure):
         ("q", ctypes.c_void_p), ("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("out", ctypes.c_void_p),
         ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
         ("v_stride", ctypes.c_int64 * 3), ("out_stride", ctypes.c_int64 * 3),
-        ("scale_mode", ctypes.c_int32),
+        ("scale_mode", ctypes.c_int32), ("Lkv", ctypes.c_int32),
         ("scale_q", ctypes.c_void_p), ("scale_k", ctypes.c_void_p),
         ("scale_v", ctypes.c_void_p), ("scale_out", ctypes.c_void_p),
         ("dbg_row_max", ctypes.c_void_p), ("dbg_row_sum", ctypes.c_void_p), ("dbg_acc", ctypes.c_void_p),
@@ -187,6 +187,8 @@ class IntAttn:
         with ``device_scales`` the float32 device tensors given (for ``forward_dynamic_args``)."""
         B, Hq, L, d = q.shape
         Hkv = k.shape[1]
+        if k.shape != v.shape or k.shape[0] != B or k.shape[3] != d or out.shape != q.shape:
+            raise ValueError("q, out must be [B,Hq,L,d] and k, v [B,Hkv,Lkv,d]")
         for t in (q, k, v, out):
             if t.stride(-1) != 1:
                 raise ValueError("the head dimension must be contiguous")
@@ -198,6 +200,7 @@ class IntAttn:
         a.v_stride = (ctypes.c_int64 * 3)(*v.stride()[:3])
         a.out_stride = (ctypes.c_int64 * 3)(*out.stride()[:3])
         a.scale_mode = int(bool(per_head))
+        a.Lkv = k.shape[2]
         if device_scales:
             import torch
 

@@ -266,6 +266,10 @@ int validate(intattn_ctx *ctx, const intattn_args *a)
     if (a->Hq % a->Hkv != 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "Hq must be a multiple of Hkv");
     if (a->d != 64 && a->d != 128) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "d must be 64 or 128");
     if (a->L > 131071) return fail(ctx, INTATTN_ERR_INVALID_ARG, "L exceeds 131071 (int32 accumulator bound)");
+    if (a->Lkv < 0 || a->Lkv > 131071) return fail(ctx, INTATTN_ERR_INVALID_ARG, "Lkv must be 0 (= L) or in 1..131071 (int32 accumulator bound)");
+    const int Lk = a->Lkv ? a->Lkv : a->L;
+    if (a->causal == 1 && Lk < a->L)
+        return fail(ctx, INTATTN_ERR_INVALID_ARG, "a causal mask needs Lkv >= L (it is aligned to the end of the keys)");
     if (a->causal != 0 && a->causal != 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "causal must be 0 or 1");
     if (a->scale_mode != 0 && a->scale_mode != 1)
         return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode must be 0 or 1");
@@ -287,7 +291,7 @@ int validate(intattn_ctx *ctx, const intattn_args *a)
         if (s[2] > (1 << 24)) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "the L stride must not exceed 2^24 bytes");
     }
     const int64_t rows_per_block = fwd_rows_per_block(fwd_choose_variant(ctx->variant, a->B, a->Hq, a->L));
-    const int64_t n_qtiles = (a->L + rows_per_block - 1) / rows_per_block;
+    const int64_t n_qtiles = fwd_row_tiles(a->causal == 1 ? Lk - a->L : 0, a->L, (int)rows_per_block);
     // the launch grid pads the (batch, KV head) groups to a multiple of the 8 XCDs
     const int64_t groups_padded = (((int64_t)a->B * a->Hkv + 7) / 8) * 8;
     if (n_qtiles * groups_padded * (int64_t)(a->Hq / a->Hkv) > 2147483647LL)
@@ -404,12 +408,16 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
         p.vs[i] = a->v_stride[i]; p.os[i] = a->out_stride[i];
     }
     p.B = a->B; p.Hq = a->Hq; p.Hkv = a->Hkv; p.L = a->L;
+    p.Lk = a->Lkv ? a->Lkv : a->L;
+    p.row_lo = a->causal ? p.Lk - p.L : 0;
+    if (comparator && p.Lk != p.L) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "the comparator covers L == Lkv only");
     p.causal = a->causal;
     p.group = a->Hq / a->Hkv;
     p.top = (1 << ctx->lut_bits) - 1;
     const int variant = fwd_choose_variant(ctx->variant, a->B, a->Hq, a->L);
     const int rows_per_block = comparator ? 128 : fwd_rows_per_block(variant);
-    p.n_qtiles = (a->L + rows_per_block - 1) / rows_per_block;
+    p.n_qtiles = fwd_row_tiles(p.row_lo, p.L, rows_per_block);
+    p.n_chunks = (p.Lk + rows_per_block - 1) / rows_per_block;
     std::memcpy(p.lut, ctx->lut, 32);
     p.dbg_row_max = a->dbg_row_max; p.dbg_row_sum = a->dbg_row_sum; p.dbg_acc = a->dbg_acc;
 
@@ -475,7 +483,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
 
     if (!comparator) {
         const size_t rows = (size_t)a->B * a->Hq * a->L;
-        const size_t cs = (size_t)a->B * a->Hkv * p.n_qtiles * a->d;
+        const size_t cs = (size_t)a->B * a->Hkv * p.n_chunks * a->d;
         rc = ensure_workspace(ctx, 2 * rows + cs);
         if (rc) return rc;
         p.ws_row_max = ctx->d_ws;

@@ -20,7 +20,7 @@ using fwdk::launch_shape;
 namespace {
 
 // Sums of V over each chunk of `chunk` consecutive keys, per (batch, KV head) and channel:
-// out[((b * Hkv + kvh) * n_qtiles + c) * D + ch].  Keys past L do not count.  The forward kernel
+// out[((b * Hkv + kvh) * n_chunks + c) * D + ch].  Keys past Lk do not count.  The forward kernel
 // adds up the chunks its tiles cover.
 template <int D>
 __global__ __launch_bounds__(256) void colsum_kernel(const FwdParams p, int chunk)
@@ -29,12 +29,12 @@ __global__ __launch_bounds__(256) void colsum_kernel(const FwdParams p, int chun
     constexpr int KL = 256 / G; // key lanes
     __shared__ int32_t red[KL][D + 1];
     const int tid = threadIdx.x, c16 = tid % G, kl = tid / G;
-    const int c = blockIdx.x % p.n_qtiles, bk = blockIdx.x / p.n_qtiles, kvh = bk % p.Hkv, b = bk / p.Hkv;
+    const int c = blockIdx.x % p.n_chunks, bk = blockIdx.x / p.n_chunks, kvh = bk % p.Hkv, b = bk / p.Hkv;
     const int8_t *Vp = p.v + (int64_t)b * p.vs[0] + (int64_t)kvh * p.vs[1];
     int32_t acc[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0;
-    const int kend = min(p.L, (c + 1) * chunk);
+    const int kend = min(p.Lk, (c + 1) * chunk);
     for (int key = c * chunk + kl; key < kend; key += KL) {
         const v4i x = *(const v4i *)(Vp + (int64_t)key * p.vs[2] + c16 * 16);
 #pragma unroll
@@ -46,13 +46,13 @@ __global__ __launch_bounds__(256) void colsum_kernel(const FwdParams p, int chun
     if (tid < D) {
         int32_t t = 0;
         for (int j = 0; j < KL; ++j) t += red[j][tid];
-        p.ws_colsum[((int64_t)bk * p.n_qtiles + c) * D + tid] = t;
+        p.ws_colsum[((int64_t)bk * p.n_chunks + c) * D + tid] = t;
     }
 }
 
 int launch_colsum(const FwdParams &p, int d, int chunk, hipStream_t st)
 {
-    const dim3 grid((unsigned)(p.B * p.Hkv * p.n_qtiles)), block(256);
+    const dim3 grid((unsigned)(p.B * p.Hkv * p.n_chunks)), block(256);
     if (d == 64) hipLaunchKernelGGL(colsum_kernel<64>, grid, block, 0, st, p, chunk);
     else if (d == 128) hipLaunchKernelGGL(colsum_kernel<128>, grid, block, 0, st, p, chunk);
     else return (int)hipErrorInvalidValue;
@@ -93,7 +93,7 @@ int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, 
         // sweeps A+B leave row max and row sum in the workspace for sweep C
         if (stage != 2) {
             FwdParams pab = p;
-            if (variant != 8) pab.n_qtiles = (p.L + 255) / 256; // 64 query rows per wave in the first launch
+            if (variant != 8) pab.n_qtiles = fwd_row_tiles(p.row_lo, p.L, 256); // 64 query rows per wave in the first launch
             e = variant <= 6 ? launch_shape<2, 2, 1>(pab, d, idx_mode, st)
                              : launch_sweep_ab(pab, d, idx_mode, variant == 7 ? 64 : 32, stream);
             if (e != 0 || stage == 1) return e;

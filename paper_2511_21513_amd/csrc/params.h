@@ -31,18 +31,23 @@ struct FwdParams {
     const int8_t *q, *k, *v;
     int8_t *out;
     int64_t qs[3], ks[3], vs[3], os[3]; // byte strides of B, H, L
-    int32_t B, Hq, Hkv, L;
+    int32_t B, Hq, Hkv;
+    int32_t L;           // query rows
+    int32_t Lk;          // keys
+    int32_t row_lo;      // number of the first query row in the numbering where row r sees keys <= r under the
+                         // causal mask: Lk - L when causal, else 0; tiles are aligned to this numbering
     int32_t causal;
     int32_t group;       // Hq / Hkv
     int32_t top;         // 2^b - 1
-    int32_t n_qtiles;    // ceil(L / rows per workgroup)
+    int32_t n_qtiles;    // tiles of (rows per workgroup) rows that [row_lo, row_lo + L) touches
+    int32_t n_chunks;    // ceil(Lk / rows per workgroup of sweep C): chunks of V the column sums are kept for
     const HeadParams *hp_table; // device [Hq] when per-head or derived on the device, else nullptr
     int32_t filter;             // 1: a workgroup whose head's HeadParams name another scheme than the kernel's returns at once
     HeadParams hp0;             // the single parameter set when hp_table == nullptr
     uint32_t lut[8];            // LUT_hat, 32 bytes packed little-endian (unused tail is 0)
     int32_t *dbg_row_max, *dbg_row_sum, *dbg_acc;
     // workspace: [B*Hq*L] row max and [B*Hq*L] row sum (handed from the first to the second launch
-    // of the two-launch variants), [B*Hkv*n_qtiles*d] sums of V over each chunk of keys
+    // of the two-launch variants), [B*Hkv*n_chunks*d] sums of V over each chunk of keys
     int32_t *ws_row_max, *ws_row_sum, *ws_colsum;
     // comparator only
     float alpha0, sv_over_so0;  // per-tensor values when the float tables are null
@@ -80,6 +85,11 @@ int launch_sweep_ab(const FwdParams &p, int d, int idx_mode, int rows_per_wave, 
 int launch_sweep_c(const FwdParams &p, int d, int idx_mode, int rows_per_wave, void *stream);
 int fwd_choose_variant(int variant, int B, int Hq, int L); // resolves 0 (automatic) to a concrete variant
 int fwd_rows_per_block(int variant);
+// tiles of `rows_per_tile` rows, aligned to multiples of it, that rows [row_lo, row_lo + n_rows) touch
+inline int fwd_row_tiles(int row_lo, int n_rows, int rows_per_tile)
+{
+    return (row_lo + n_rows + rows_per_tile - 1) / rows_per_tile - row_lo / rows_per_tile;
+}
 bool fwd_variant_known(int variant);
 int quantize_partials_per_slice(int B, int H, int L, int d);
 int launch_quantize(const QuantParams &p, void *stream);

@@ -56,11 +56,13 @@ __global__ __launch_bounds__(NT, RB == 1 ? 3 : 2) void sweep_ab_kernel(const Fwd
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 31, h = lane >> 5;
     const WorkItem wi = fwd_work_item(p, (int)blockIdx.x);
     if (!wi.valid) return; // padding of the XCD-aware grid (uniform for the whole workgroup)
-    const int b = wi.b, hq = wi.hq, kvh = wi.kvh, qt = wi.qt;
+    const int b = wi.b, hq = wi.hq, kvh = wi.kvh, qt = wi.qt + p.row_lo / BQ;
     const int bh = b * p.Hq + hq;
     const HeadParams hp = p.hp_table ? p.hp_table[hq] : p.hp0;
     if (p.filter && hp.pad[0] != MODE) return; // another launch of this pair serves the head (uniform for the workgroup)
-    const int L = p.L;
+    const int L = p.Lk; // keys
+    // query rows: [rlo, rhi) of the numbering in which row r sees keys <= r under the causal mask
+    const int rlo = p.row_lo, rhi = p.row_lo + p.L, LQ = p.L;
     const uint32_t top = (uint32_t)p.top;
 
     const int q0 = qt * BQ, qw0 = q0 + wave * (RB * 32);
@@ -77,7 +79,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 3 : 2) void sweep_ab_kernel(const Fwd
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
             qf[rb][kb] = v4i{0, 0, 0, 0};
-            if (row < L) qf[rb][kb] = *(const v4i *)(Qp + (int64_t)row * p.qs[2] + kb * 32 + h * 16);
+            if (row >= rlo && row < rhi) qf[rb][kb] = *(const v4i *)(Qp + (int64_t)(row - rlo) * p.qs[2] + kb * 32 + h * 16);
         }
     }
 
@@ -249,9 +251,9 @@ __global__ __launch_bounds__(NT, RB == 1 ? 3 : 2) void sweep_ab_kernel(const Fwd
     for (int rb = 0; rb < RB; ++rb) {
         sum[rb] += __shfl_xor(sum[rb], 32);
         const int row = qw0 + 32 * rb + n;
-        if (h == 0 && row < L) {
-            p.ws_row_max[(int64_t)bh * L + row] = mx[rb];
-            p.ws_row_sum[(int64_t)bh * L + row] = (int32_t)sum[rb];
+        if (h == 0 && row >= rlo && row < rhi) {
+            p.ws_row_max[(int64_t)bh * LQ + (row - rlo)] = mx[rb];
+            p.ws_row_sum[(int64_t)bh * LQ + (row - rlo)] = (int32_t)sum[rb];
         }
     }
 }

@@ -72,11 +72,13 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 31, h = lane >> 5;
     const WorkItem wi = fwd_work_item(p, (int)blockIdx.x);
     if (!wi.valid) return; // padding of the XCD-aware grid (uniform for the whole workgroup)
-    const int b = wi.b, hq = wi.hq, kvh = wi.kvh, qt = wi.qt;
+    const int b = wi.b, hq = wi.hq, kvh = wi.kvh, qt = wi.qt + p.row_lo / BQ;
     const int bh = b * p.Hq + hq;
     const HeadParams hp = p.hp_table ? p.hp_table[hq] : p.hp0;
     if (p.filter && hp.pad[0] != MODE) return; // another launch of this pair serves the head (uniform for the workgroup)
-    const int L = p.L;
+    const int L = p.Lk; // keys
+    // query rows: [rlo, rhi) of the numbering in which row r sees keys <= r under the causal mask
+    const int rlo = p.row_lo, rhi = p.row_lo + p.L, LQ = p.L;
     const uint32_t top = (uint32_t)p.top;
 
     const int q0 = qt * BQ, qw0 = q0 + wave * (RB * 32);
@@ -94,7 +96,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
             qf[rb][kb] = v4i{0, 0, 0, 0};
-            if (row < L) qf[rb][kb] = *(const v4i *)(Qp + (int64_t)row * p.qs[2] + kb * 32 + h * 16);
+            if (row >= rlo && row < rhi) qf[rb][kb] = *(const v4i *)(Qp + (int64_t)(row - rlo) * p.qs[2] + kb * 32 + h * 16);
         }
     }
 
@@ -149,20 +151,20 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const int row = qw0 + 32 * rb + n;
-        const int mx = row < L ? p.ws_row_max[(int64_t)bh * L + row] : 0;
-        sum[rb] = row < L ? (uint32_t)p.ws_row_sum[(int64_t)bh * L + row] : 0u;
-        if (sum[rb] == 0) sum[rb] = 1; // only rows beyond L; never stored
+        const int mx = (row >= rlo && row < rhi) ? p.ws_row_max[(int64_t)bh * LQ + (row - rlo)] : 0;
+        sum[rb] = (row >= rlo && row < rhi) ? (uint32_t)p.ws_row_sum[(int64_t)bh * LQ + (row - rlo)] : 0u;
+        if (sum[rb] == 0) sum[rb] = 1; // only rows outside [rlo, rhi); never stored
         ri[rb].init(hp, mx, top);
-        if (p.dbg_row_max && h == 0 && row < L) p.dbg_row_max[(int64_t)bh * L + row] = mx;
-        if (p.dbg_row_sum && h == 0 && row < L) p.dbg_row_sum[(int64_t)bh * L + row] = (int32_t)sum[rb];
+        if (p.dbg_row_max && h == 0 && row >= rlo && row < rhi) p.dbg_row_max[(int64_t)bh * LQ + (row - rlo)] = mx;
+        if (p.dbg_row_sum && h == 0 && row >= rlo && row < rhi) p.dbg_row_sum[(int64_t)bh * LQ + (row - rlo)] = (int32_t)sum[rb];
     }
 
     // Column sums of V over every key the steps below cover (keys up to the end of this query tile
     // under the causal mask, else all): the correction for feeding the probabilities to the signed
     // MFMA as P - 128.  A small kernel ahead of this one left the sums of each BQ-key chunk.
     if (tid < D) {
-        const int32_t *cp = p.ws_colsum + (int64_t)(b * p.Hkv + kvh) * p.n_qtiles * D + tid;
-        const int nchunk = CAUSAL ? qt + 1 : p.n_qtiles;
+        const int32_t *cp = p.ws_colsum + (int64_t)(b * p.Hkv + kvh) * p.n_chunks * D + tid;
+        const int nchunk = CAUSAL ? min(qt + 1, p.n_chunks) : p.n_chunks;
         int32_t acc = 0;
 #pragma unroll 8
         for (int c = 0; c < nchunk; ++c) acc += cp[(int64_t)c * D];
@@ -348,8 +350,8 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const int row = qw0 + 32 * rb + n;
-        if (row >= L) continue;
-        int8_t *Op = p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)row * p.os[2];
+        if (row < rlo || row >= rhi) continue;
+        int8_t *Op = p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)(row - rlo) * p.os[2];
         const int64_t half = 1ll << (hp.rq_shift - 1);
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
@@ -360,7 +362,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int32_t acc = o[rb][cb][4 * g + r] + 128 * colsum[ch0 + r];
-                    if (p.dbg_acc) p.dbg_acc[((int64_t)bh * L + row) * D + ch0 + r] = acc;
+                    if (p.dbg_acc) p.dbg_acc[((int64_t)bh * LQ + (row - rlo)) * D + ch0 + r] = acc;
                     int64_t v = ((int64_t)acc * hp.rq_mult + half) >> hp.rq_shift;
                     v = v > 127 ? 127 : (v < -127 ? -127 : v);
                     packed |= ((uint32_t)(int)v & 0xffu) << (8 * r);

@@ -470,3 +470,89 @@ def test_quantizer_to_dynamic_forward_without_host_reads(torch_mod, oracle):
         want = oracle.forward(oq, ok, ov, osq, osk, osv, None, causal=True, per_head=per_head)["out"]
         assert int((out.cpu().numpy() != want).sum()) == 0
     ia.close()
+
+
+# ---------------------------------------------------------------- rectangular shapes (L query rows, Lkv keys)
+
+def rect_problem(seed, B, Hq, Hkv, lq, lk, d, causal, per_head=False):
+    """Seeded q [B,Hq,lq,d], k, v [B,Hkv,lk,d] with the value recipe of the square problems."""
+    base = inputs.random_problem(seed, B, Hq, Hkv, max(lq, lk), d, causal, per_head=per_head, spread=1.5)
+    q = np.ascontiguousarray(base.q[:, :, :lq])
+    k = np.ascontiguousarray(base.k[:, :, :lk])
+    v = np.ascontiguousarray(base.v[:, :, :lk])
+    return base, q, k, v
+
+
+def rect_forward(torch, ia, base, q, k, v, s_o=None, taps=True):
+    dev = torch.device("cuda:0")
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+    r = ia.forward(tq, tk, tv, base.s_q, base.s_k, base.s_v, s_o, causal=base.causal, per_head=base.per_head, taps=taps)
+    torch.cuda.synchronize()
+    return {k_: v_.cpu().numpy() for k_, v_ in r.items()} if taps else {"out": r.cpu().numpy()}
+
+
+RECT_SHAPES = [
+    # B, Hq, Hkv, Lq, Lkv, d, causal, per_head
+    (1, 1, 1, 1, 1, 64, True, False),
+    (2, 4, 2, 1, 300, 128, True, False),      # one decoded token
+    (2, 4, 2, 1, 300, 64, False, True),
+    (1, 2, 1, 5, 129, 64, True, False),
+    (1, 4, 4, 128, 1000, 128, True, False),   # a chunk of a prefill, tile-aligned start ...
+    (1, 2, 2, 100, 777, 64, True, True),      # ... and not
+    (1, 2, 1, 333, 334, 128, True, False),
+    (1, 3, 1, 200, 64, 64, False, False),     # more queries than keys (no mask)
+    (1, 2, 2, 40, 515, 128, False, False),
+]
+
+
+@pytest.mark.parametrize("shape", RECT_SHAPES, ids=lambda s: "B{}Hq{}Hkv{}Lq{}Lk{}d{}c{}ph{}".format(*[int(x) for x in s]))
+def test_rectangular_shapes_bit_exact(torch_mod, ia, oracle, shape):
+    """L != Lkv: every tap and the output equal the oracle's, for every kernel variant."""
+    B, Hq, Hkv, lq, lk, d, causal, per_head = shape
+    print(f"case {shape}", flush=True)
+    base, q, k, v = rect_problem(500 + lq + lk, B, Hq, Hkv, lq, lk, d, causal, per_head)
+    got = rect_forward(torch_mod, ia, base, q, k, v)
+    want = oracle.forward(q, k, v, base.s_q, base.s_k, base.s_v, None, causal=causal, per_head=per_head, taps=True)
+    for key in ("row_max", "row_sum", "acc", "out"):
+        assert got[key].shape == want[key].shape
+        assert int((got[key] != want[key]).sum()) == 0, key
+
+
+def test_decode_and_chunked_prefill_at_workload_size(torch_mod, oracle):
+    """The GQA prefill workload's heads and key length (32 / 8 heads, 8192 keys, d = 128): one
+    decoded token per sequence in full, and the last 2048-row chunk of the prefill on sampled rows,
+    through the automatic variant."""
+    from paper_2511_21513_amd import binding
+
+    ia = binding.IntAttn(device=0)
+    base, q, k, v = rect_problem(77, 1, 32, 8, 2048, 8192, 128, True, per_head=True)
+    q1 = np.ascontiguousarray(q[:, :, :1])
+    got = rect_forward(torch_mod, ia, base, q1, k, v, taps=False)["out"]
+    want = oracle.forward(q1, k, v, base.s_q, base.s_k, base.s_v, None, causal=True, per_head=True, threads=16)["out"]
+    assert int((got != want).sum()) == 0
+    got = rect_forward(torch_mod, ia, base, q, k, v, taps=False)["out"]
+    rng = np.random.default_rng(3)
+    for hq in (0, 13, 31):
+        rows = np.unique(np.concatenate([[0, 1, 127, 128, 2047], rng.integers(0, 2048, 6)])).astype(np.int32)
+        w = oracle.rows(q, k, v, base.s_q, base.s_k, base.s_v, None, b=0, hq=hq, rows=rows, causal=True, per_head=True)
+        assert int((got[0, hq][rows] != w["out"]).sum()) == 0, hq
+    ia.close()
+
+
+def test_rectangular_dynamic_forward(torch_mod, oracle):
+    """Device-resident scales with L != Lkv."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    ia = binding.IntAttn(device=0)
+    dev = torch.device("cuda:0")
+    base, q, k, v = rect_problem(91, 2, 4, 2, 7, 260, 64, True, per_head=True)
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+    sc = [torch.from_numpy(np.ascontiguousarray(s, dtype=np.float32)).to(dev) for s in (base.s_q, base.s_k, base.s_v)]
+    out = torch.empty_like(tq)
+    args, keep = ia.make_args(tq, tk, tv, out, sc[0], sc[1], sc[2], None, causal=True, per_head=True, device_scales=True)
+    ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
+    torch.cuda.synchronize()
+    want = oracle.forward(q, k, v, base.s_q, base.s_k, base.s_v, None, causal=True, per_head=True)["out"]
+    assert ia.dynamic_status() == 0 and int((out.cpu().numpy() != want).sum()) == 0
+    ia.close()

@@ -55,8 +55,9 @@ typedef struct {
                          (parameter derivation and LUT only; forward calls are rejected)     */
     int32_t lut_bits; /* b of Sec. 3.1: the table has 2^b entries; 1..5; paper default 5     */
     double clip;      /* c of Sec. 3.1: clip threshold in logit units; > 0; paper default 6.6 */
-    int32_t variant;  /* kernel variant: 0 = automatic choice; 1..8 = tuning knobs (launch split, rows per
-                         wave, tile size, instruction schedule), all bit-identical; others are rejected */
+    int32_t variant;  /* kernel variant: 0 = automatic choice; 1..9 = tuning knobs (launch split, rows per
+                         wave, tile size, instruction schedule; 9 = the split-key kernels for few query
+                         rows wherever the shape allows), all bit-identical; others are rejected       */
     int32_t reserved; /* must be 0                                                           */
 } intattn_config;
 

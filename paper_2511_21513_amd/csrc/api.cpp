@@ -421,6 +421,12 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
     std::memcpy(p.lut, ctx->lut, 32);
     p.dbg_row_max = a->dbg_row_max; p.dbg_row_sum = a->dbg_row_sum; p.dbg_acc = a->dbg_acc;
 
+    // Few query rows against many keys: the split-key kernels (all query heads of a KV head, times
+    // the query rows, packed into one MFMA operand of at most 31 rows).
+    const int64_t packed_rows = (int64_t)p.group * p.L;
+    const bool decode_ok = !comparator && stage == 0 && packed_rows <= 31 && (int64_t)a->B * a->Hkv <= 65535;
+    const bool decode = decode_ok && (ctx->variant == 9 || (ctx->variant == 0 && p.Lk >= 1024));
+
     if (dynamic) {
         rc = ensure_tables(ctx, a->Hq);
         if (rc) return rc;
@@ -448,6 +454,24 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
         if (stage != 2) { // stage 2 reads what stage 1 derived
             const int e = launch_derive(dp, stream);
             if (e != 0) return hip_fail(ctx, (hipError_t)e, "launch(derive head parameters)");
+        }
+        p.hp_table = ctx->d_hp;
+    } else if (decode) {
+        // every head's parameters in the device table, each with the scheme of its index map
+        rc = ensure_tables(ctx, a->Hq);
+        if (rc) return rc;
+        std::vector<HeadParams> tab((size_t)a->Hq);
+        for (int h = 0; h < a->Hq; ++h) {
+            tab[(size_t)h] = dv.hp[a->scale_mode ? (size_t)h : 0];
+            tab[(size_t)h].pad[0] = dv.idx_mode;
+        }
+        const bool same = ctx->hp_host.size() == tab.size() &&
+                          std::memcmp(ctx->hp_host.data(), tab.data(), tab.size() * sizeof(HeadParams)) == 0;
+        if (!same) {
+            const hipError_t e = hipMemcpyAsync(ctx->d_hp, tab.data(), tab.size() * sizeof(HeadParams), hipMemcpyHostToDevice,
+                                                (hipStream_t)stream);
+            if (e != hipSuccess) return hip_fail(ctx, e, "hipMemcpyAsync(head params)");
+            ctx->hp_host = tab;
         }
         p.hp_table = ctx->d_hp;
     } else if (a->scale_mode == 0) {
@@ -481,6 +505,25 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
         p.svso_table = ctx->d_svso;
     }
 
+    if (decode) {
+        const size_t groups = (size_t)a->B * a->Hkv, R = (size_t)packed_rows;
+        const size_t nt32 = 4 * (((size_t)p.Lk + 127) / 128);
+        const size_t n_scores = groups * nt32 * 2 * R * 16, n_idx = groups * nt32 * 2 * R * 4, n_part = groups * nt32 * R;
+        const size_t n_acc = (size_t)a->B * a->Hq * a->L * a->d;
+        rc = ensure_workspace(ctx, n_scores + n_idx + 2 * n_part + n_acc);
+        if (rc) return rc;
+        p.dec_rows = (int32_t)R;
+        p.dec_nt32 = (int32_t)nt32;
+        p.dec_scores = ctx->d_ws; // every part is a multiple of 4 words: 16-byte alignment holds
+        p.dec_idx = p.dec_scores + n_scores;
+        p.dec_acc = p.dec_idx + n_idx;
+        p.dec_pmax = p.dec_acc + n_acc;
+        p.dec_psum = p.dec_pmax + n_part;
+        const int herr = launch_decode(p, a->d, stream);
+        if (herr != 0) return hip_fail(ctx, (hipError_t)herr, "launch(split-key forward)");
+        ctx->err.clear();
+        return INTATTN_OK;
+    }
     if (!comparator) {
         const size_t rows = (size_t)a->B * a->Hq * a->L;
         const size_t cs = (size_t)a->B * a->Hkv * p.n_chunks * a->d;

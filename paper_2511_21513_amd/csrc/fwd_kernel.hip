@@ -67,15 +67,16 @@ int launch_colsum(const FwdParams &p, int d, int chunk, hipStream_t st)
 //   4  two launches: sweeps A+B (64 rows per wave), then sweep C (32 rows per wave), phase-ordered kernels
 //   5  as 4 with the software-pipelined sweep C kernel      6  as 5 with 64 rows per wave in sweep C
 //   7  software-pipelined sweeps A+B (64 rows per wave) and sweep C     8  as 7 with 32 rows per wave in A+B
-// Automatic choice: enough workgroups to amortise three launches -> variant 5; small problems
-// take the single launch.
+//   9  the split-key kernels of decode_kernel.hip whenever the shape allows them, else as 0
+// Automatic choice among the tiled kernels: enough workgroups to amortise three launches -> variant 5;
+// small problems take the single launch.
 int fwd_choose_variant(int variant, int B, int Hq, int L)
 {
-    if (variant != 0) return variant;
+    if (variant != 0 && variant != 9) return variant;
     const int64_t workgroups = (int64_t)B * Hq * ((L + 127) / 128);
     return workgroups >= 1024 ? 5 : 1;
 }
-bool fwd_variant_known(int variant) { return variant >= 0 && variant <= 8; }
+bool fwd_variant_known(int variant) { return variant >= 0 && variant <= 9; }
 int fwd_rows_per_block(int variant) { return (variant == 2 || variant == 6) ? 256 : 128; }
 
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, void *stream)

@@ -49,6 +49,11 @@ struct FwdParams {
     // workspace: [B*Hq*L] row max and [B*Hq*L] row sum (handed from the first to the second launch
     // of the two-launch variants), [B*Hkv*n_chunks*d] sums of V over each chunk of keys
     int32_t *ws_row_max, *ws_row_sum, *ws_colsum;
+    // split-key path for few query rows (decode): packed rows (Hq / Hkv) * L, 32-key sub-tiles 4 * ceil(Lk / 128);
+    // per (batch, KV head) group g and sub-tile j: raw scores [g][j][2][rows][16], table indices (16 bytes where the
+    // scores have 16 words), partial row max and row sum [g][j][rows]; the int32 accumulator [B, Hq, L, d]
+    int32_t dec_rows, dec_nt32;
+    int32_t *dec_scores, *dec_idx, *dec_pmax, *dec_psum, *dec_acc;
     // comparator only
     float alpha0, sv_over_so0;  // per-tensor values when the float tables are null
     const float *alpha_table;   // device [Hq]
@@ -93,6 +98,7 @@ inline int fwd_row_tiles(int row_lo, int n_rows, int rows_per_tile)
 bool fwd_variant_known(int variant);
 int quantize_partials_per_slice(int B, int H, int L, int d);
 int launch_quantize(const QuantParams &p, void *stream);
+int launch_decode(const FwdParams &p, int d, void *stream);
 int launch_derive(const DeriveParams &dp, void *stream);
 int launch_quantonly(const FwdParams &p, int d, int variant, void *stream);
 

@@ -23,8 +23,9 @@ def torch_mod():
 # kernel variants: 0 = automatic choice; 1-3 = one launch (32 query rows per wave with 64-key tiles,
 # 64 rows per wave, 32 rows per wave with 32-key tiles); 4 = two launches (sweeps A+B, then sweep C)
 # with the phase-ordered kernels; 5 / 6 = software-pipelined sweep C with 32 / 64 rows per wave;
-# 7 / 8 = software-pipelined sweeps A+B with 64 / 32 rows per wave, and sweep C
-@pytest.fixture(scope="module", params=[0, 1, 2, 3, 4, 5, 6, 7, 8], ids=lambda v: f"variant{v}")
+# 7 / 8 = software-pipelined sweeps A+B with 64 / 32 rows per wave, and sweep C; 9 = the split-key
+# kernels (few query rows against many keys) wherever (Hq / Hkv) * L <= 31, else as 0
+@pytest.fixture(scope="module", params=[0, 1, 2, 3, 4, 5, 6, 7, 8, 9], ids=lambda v: f"variant{v}")
 def ia(torch_mod, request):
     from paper_2511_21513_amd import binding
 

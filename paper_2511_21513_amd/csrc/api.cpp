@@ -508,12 +508,18 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
     if (decode) {
         const size_t groups = (size_t)a->B * a->Hkv, R = (size_t)packed_rows;
         const size_t nt32 = 4 * (((size_t)p.Lk + 127) / 128);
-        const size_t n_scores = groups * nt32 * 2 * R * 16, n_idx = groups * nt32 * 2 * R * 4, n_part = groups * nt32 * R;
-        const size_t n_acc = (size_t)a->B * a->Hq * a->L * a->d;
+        // tiles per workgroup: as many as leave about a thousand workgroups, at most 8
+        const size_t tiles = groups * (nt32 / 4);
+        const size_t tpw = tiles / 1024 < 1 ? 1 : (tiles / 1024 > 8 ? 8 : tiles / 1024);
+        const size_t chunks = (nt32 / 4 + tpw - 1) / tpw;
+        const size_t n_scores = groups * nt32 * 2 * R * 16, n_idx = groups * nt32 * 2 * R * 4, n_part = groups * chunks * 4 * R;
+        const size_t n_acc = groups * chunks * R * (size_t)a->d;
         rc = ensure_workspace(ctx, n_scores + n_idx + 2 * n_part + n_acc);
         if (rc) return rc;
         p.dec_rows = (int32_t)R;
         p.dec_nt32 = (int32_t)nt32;
+        p.dec_tpw = (int32_t)tpw;
+        p.dec_np = (int32_t)(chunks * 4);
         p.dec_scores = ctx->d_ws; // every part is a multiple of 4 words: 16-byte alignment holds
         p.dec_idx = p.dec_scores + n_scores;
         p.dec_acc = p.dec_idx + n_idx;

@@ -51,8 +51,9 @@ struct FwdParams {
     int32_t *ws_row_max, *ws_row_sum, *ws_colsum;
     // split-key path for few query rows (decode): packed rows (Hq / Hkv) * L, 32-key sub-tiles 4 * ceil(Lk / 128);
     // per (batch, KV head) group g and sub-tile j: raw scores [g][j][2][rows][16], table indices (16 bytes where the
-    // scores have 16 words), partial row max and row sum [g][j][rows]; the int32 accumulator [B, Hq, L, d]
+    // scores have 16 words), partial row max and row sum [g][dec_np][rows]; partial accumulators per workgroup [g][dec_np / 4][rows][d]
     int32_t dec_rows, dec_nt32;
+    int32_t dec_tpw, dec_np; // 128-key tiles per workgroup; partial maxima / sums per row = 4 * ceil(tiles / dec_tpw)
     int32_t *dec_scores, *dec_idx, *dec_pmax, *dec_psum, *dec_acc;
     // comparator only
     float alpha0, sv_over_so0;  // per-tensor values when the float tables are null

@@ -25,7 +25,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel (sweep C) measured with rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE, each scaled by the same counter's reading for a plain 1 GiB device copy
 # (profiles/sweep_c_kernel_c4_gqa_prefill_8k.md).  Only workloads that were profiled have an entry.
-MEASURED_HBM_TRAFFIC_BYTES = {"c4_gqa_prefill_8k": 54.85e6 + 33.55e6}
+MEASURED_HBM_TRAFFIC_BYTES = {"c4_gqa_prefill_8k": 54.85e6 + 33.55e6,
+                              # --decode, all four kernels of a step (profiles/decode_kernels_c4_gqa_shape_b32_lkv8192.md)
+                              "decode:c4_gqa_prefill_8k:B32": 633e6}
 
 ALIASES = {"c1": "c1_single_head", "c2": "c2_vit_b16", "c3": "c3_llm_prefill_2k",
            "c4": "c4_gqa_prefill_8k", "c5": "c5_batched_prefill_4k"}
@@ -137,6 +139,67 @@ def quantizer_bench(a, name, dev):
     print(json.dumps(res))
 
 
+def decode_bench(a, name, dev):
+    """One step = one decoded token for each of --decode-batch sequences: L = 1 query row per head
+    against the workload's key/value length, heads and head dimension, causal (the token sees every
+    key).  HBM-bound: K and V are read once; algorithmic bytes = K + V + Q + out."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2511_21513_amd import binding, inputs
+
+    _, Hq, Hkv, Lk, d = inputs.CONFIGS[name][:5]
+    B = a.decode_batch
+    g = torch.Generator(device=dev).manual_seed(0)
+    # the recipe's value range: symmetric INT8 with the extremes present
+    q = torch.randint(-127, 128, (B, Hq, 1, d), device=dev, dtype=torch.int8, generator=g)
+    k = torch.randint(-127, 128, (B, Hkv, Lk, d), device=dev, dtype=torch.int8, generator=g)
+    v = torch.randint(-127, 128, (B, Hkv, Lk, d), device=dev, dtype=torch.int8, generator=g)
+    out = torch.empty_like(q)
+    s_q = np.linspace(0.008, 0.012, Hq).astype(np.float32)
+    s_k = np.linspace(0.009, 0.011, Hkv).astype(np.float32)
+    s_v = np.linspace(0.02, 0.03, Hkv).astype(np.float32)
+    ia = binding.IntAttn(device=0, variant=a.variant)
+    args, keep = ia.make_args(q, k, v, out, s_q, s_k, s_v, None, causal=True, per_head=True)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    for _ in range(a.warmup):
+        ia.forward_args(args, stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(a.steps):
+        ia.forward_args(args, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / a.steps
+    alg_bytes = k.numel() + v.numel() + q.numel() + out.numel()
+    gbps = alg_bytes / (ms * 1e-3) / 1e9
+    # parity of the timed output on two sequences, and the oracle's own rate beside it
+    bs = sorted(set([0, B - 1] + list(range(0, B, max(1, B // 6)))))
+    qs, ks, vs = (x[bs].cpu().numpy() for x in (q, k, v))
+    t0 = time.perf_counter()
+    want = oracle.forward(qs, ks, vs, s_q, s_k, s_v, None, causal=True, per_head=True, threads=min(16, os.cpu_count() or 1))["out"]
+    cpu_s = time.perf_counter() - t0
+    mism = int((out[bs].cpu().numpy() != want).sum())
+    res = {"metric": "decode attention (one token per sequence), algorithmic GB/s", "value": gbps, "unit": "GB/s",
+           "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+           "config": {"workload": f"decode on the shape of {name}", "B": B, "Hq": Hq, "Hkv": Hkv, "L": 1, "Lkv": Lk, "d": d,
+                      "causal": True, "scales": "per-head", "variant": a.variant},
+           "tokens_per_s": B / (ms * 1e-3),
+           "parity_mismatching_bytes": mism,
+           "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBS,
+                        "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(f"decode:{name}:B{B}"),
+                        "kernel": "decode_scores_kernel + decode_lookup_kernel + decode_pv_kernel + decode_finish_kernel",
+                        "algorithmic_bytes_per_step": alg_bytes},
+           "cpu_baseline": {"value": (ks.nbytes + vs.nbytes + 2 * qs.nbytes) / cpu_s / 1e9, "unit": "GB/s",
+                            "cores": min(16, os.cpu_count() or 1, len(bs) * Hq), "kind": "oracle",
+                            "sample": f"{len(bs)} of {B} sequences, all heads, {cpu_s:.2f} s"}}
+    ia.close()
+    print(json.dumps(res))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -150,6 +213,10 @@ def main():
                     help="instead of the benchmark, run a plain device copy of this many MiB three times "
                          "(the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-heads", type=int, default=32)
+    ap.add_argument("--decode", action="store_true",
+                    help="instead of the prefill benchmark, time one decoded token per sequence against the "
+                         "workload's key/value length (split-key kernels, HBM-bound)")
+    ap.add_argument("--decode-batch", type=int, default=32)
     ap.add_argument("--quantizer", action="store_true",
                     help="instead of the attention benchmark, time the dynamic quantizer in front of it: "
                          "fp16 Q, K, V of the workload's shape to INT8 with per-tensor scales (HBM-bound)")
@@ -179,6 +246,8 @@ def main():
     torch.cuda.set_device(dev)
     if a.quantizer:
         return quantizer_bench(a, name, dev)
+    if a.decode:
+        return decode_bench(a, name, dev)
     p = inputs.make_problem(name)
     ia = binding.IntAttn(device=0, variant=a.variant)
     q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))

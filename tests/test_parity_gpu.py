@@ -557,3 +557,48 @@ def test_rectangular_dynamic_forward(torch_mod, oracle):
     want = oracle.forward(q, k, v, base.s_q, base.s_k, base.s_v, None, causal=True, per_head=True)["out"]
     assert ia.dynamic_status() == 0 and int((out.cpu().numpy() != want).sum()) == 0
     ia.close()
+
+
+SPLIT_KEY_SHAPES = [
+    # B, Hq, Hkv, Lq, Lkv, d, causal: all take the split-key kernels ((Hq/Hkv) * Lq <= 31)
+    (1, 31, 1, 1, 700, 64, True),        # 31 packed rows: the operand's last free row carries the ones
+    (2, 12, 2, 5, 1500, 128, True),      # 30 packed rows, masks that differ per query row
+    (4, 8, 4, 1, 20000, 128, True),      # 2512 tiles: two tiles per workgroup, odd tile count, ragged last tile
+    (24, 8, 8, 2, 5000, 64, False),      # 7680 tiles: seven tiles per workgroup, no mask
+    (1, 4, 4, 3, 131071, 64, True),      # the longest key sequence
+]
+
+
+@pytest.mark.parametrize("shape", SPLIT_KEY_SHAPES, ids=lambda s: "B{}Hq{}Hkv{}Lq{}Lk{}d{}c{}".format(*[int(x) for x in s]))
+def test_split_key_kernels_bit_exact(torch_mod, oracle, shape):
+    """Few query rows against many keys through the split-key kernels: several tiles per workgroup,
+    full and nearly full operand, per-row masks; taps and output equal the oracle's, with host and
+    with device-resident scales."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    B, Hq, Hkv, lq, lk, d, causal = shape
+    print(f"case {shape}", flush=True)
+    rng = np.random.default_rng(lk + lq)
+    q = rng.integers(-127, 128, size=(B, Hq, lq, d)).astype(np.int8)
+    k = rng.integers(-127, 128, size=(B, Hkv, lk, d)).astype(np.int8)
+    v = rng.integers(-127, 128, size=(B, Hkv, lk, d)).astype(np.int8)
+    s_q = rng.uniform(0.004, 0.02, Hq).astype(np.float32)
+    s_k = rng.uniform(0.004, 0.02, Hkv).astype(np.float32)
+    s_v = rng.uniform(0.01, 0.05, Hkv).astype(np.float32)
+    s_o = (s_v[np.arange(Hq) // (Hq // Hkv)] * np.float32(0.05)).astype(np.float32)
+    want = oracle.forward(q, k, v, s_q, s_k, s_v, s_o, causal=causal, per_head=True, taps=True, threads=16)
+    ia = binding.IntAttn(device=0, variant=9)
+    dev = torch.device("cuda:0")
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+    got = ia.forward(tq, tk, tv, s_q, s_k, s_v, s_o, causal=causal, per_head=True, taps=True)
+    torch.cuda.synchronize()
+    for key in ("row_max", "row_sum", "acc", "out"):
+        assert int((got[key].cpu().numpy() != want[key]).sum()) == 0, key
+    sc = [torch.from_numpy(x).to(dev) for x in (s_q, s_k, s_v, s_o)]
+    out = torch.empty_like(tq)
+    args, keep = ia.make_args(tq, tk, tv, out, *sc, causal=causal, per_head=True, device_scales=True)
+    ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
+    torch.cuda.synchronize()
+    assert ia.dynamic_status() == 0 and int((out.cpu().numpy() != want["out"]).sum()) == 0
+    ia.close()

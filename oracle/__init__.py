@@ -8,6 +8,7 @@ from .oracle import (  # noqa: F401
     c_int,
     forward,
     index_map,
+    index_softmax,
     lut,
     prob,
     quantize,

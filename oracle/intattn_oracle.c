@@ -323,6 +323,48 @@ int intattn_oracle_rows(int B, int Hq, int Hkv, int L, int Lk, int d, int causal
     return rc;
 }
 
+/* ------------------------------------------------------------------ IndexSoftmax as an operator */
+
+/*
+ * IndexSoftmax (Sec. 3.1-3.2) on caller-supplied INT32 logits, the paper's softmax-only setting:
+ * for every row  m = max, Delta = m - A, Delta' = min(Delta, c_int)  (Eq. int_clipping),
+ * idx = round(Delta' (2^b - 1) / c_int), E = LUT_hat[idx]  (Eq. gather16), S = rowSum(E),
+ * P = round(255 E / S)  (Eq. uint8-prob).
+ * logits, prob: [rows, cols] contiguous.  rows_per_matrix > 0 with causal = 1 treats the rows as
+ * stacked [rows_per_matrix, cols] matrices with the mask of the attention path (row r of a matrix
+ * sees columns j <= r + cols - rows_per_matrix; hidden columns get P = 0); otherwise every column
+ * is visible.
+ */
+int intattn_oracle_index_softmax(int64_t rows, int64_t cols, const int32_t *logits, int64_t c_int,
+                                 int lut_bits, double clip, int64_t rows_per_matrix, int causal,
+                                 uint8_t *prob)
+{
+    if (rows < 1 || cols < 1 || !logits || !prob || c_int < 1) return ORACLE_BAD_ARG;
+    if (causal && (rows_per_matrix < 1 || cols < rows_per_matrix || rows % rows_per_matrix != 0)) return ORACLE_BAD_ARG;
+    uint8_t lut[256];
+    int rc = intattn_oracle_lut(lut_bits, clip, lut);
+    if (rc) return rc;
+    int64_t *e = (int64_t *)malloc(sizeof(int64_t) * (size_t)cols);
+    if (!e) return ORACLE_NO_MEM;
+    for (int64_t r = 0; r < rows; ++r) {
+        const int32_t *a = logits + r * cols;
+        const int64_t n_vis = causal ? (r % rows_per_matrix) + (cols - rows_per_matrix) + 1 : cols;
+        int64_t m = a[0];
+        for (int64_t j = 1; j < n_vis; ++j)
+            if (a[j] > m) m = a[j];
+        int64_t S = 0;
+        for (int64_t j = 0; j < n_vis; ++j) {
+            int64_t delta = m - (int64_t)a[j];
+            int64_t dclip = delta < c_int ? delta : c_int;
+            e[j] = (int64_t)lut[intattn_oracle_index(dclip, c_int, lut_bits)];
+            S += e[j];
+        }
+        for (int64_t j = 0; j < cols; ++j) prob[r * cols + j] = j < n_vis ? (uint8_t)intattn_oracle_prob(e[j], S) : 0;
+    }
+    free(e);
+    return ORACLE_OK;
+}
+
 /* ------------------------------------------------------------------ dynamic quantizer (Sec. 2.1) */
 
 /* Eq. quant: s_X = max|X| / 127, quant(X) = clamp(round(X / s_X), -127, 127), symmetric, zero

@@ -54,6 +54,8 @@ def _load():
                 [i32] * 7 + [vp] * 3 + [i32] + [vp] * 4 + [i32, dbl] + [i32] * 3 + [vp] * 5
             )
             lib.intattn_oracle_rows.restype = i32
+            lib.intattn_oracle_index_softmax.argtypes = [i64, i64, vp, i64, i32, dbl, i64, i32, vp]
+            lib.intattn_oracle_index_softmax.restype = i32
             lib.intattn_oracle_quantize.argtypes = [i32] * 4 + [vp, i32, vp, vp]
             lib.intattn_oracle_quantize.restype = i32
             _lib = lib
@@ -176,6 +178,22 @@ def rows(q, k, v, s_q, s_k, s_v, s_o=None, *, b, hq, rows, causal=False, per_hea
     if rc:
         raise ValueError(f"intattn_oracle_rows rc={rc}")
     return res
+
+
+def index_softmax(logits, c_int_: int, *, lut_bits=5, clip=6.6, rows_per_matrix=0, causal=False):
+    """IndexSoftmax on int32 logits [..., cols] (rows are everything before the last axis): uint8
+    probabilities of the same shape.  ``causal`` with ``rows_per_matrix``: the attention path's mask
+    on stacked [rows_per_matrix, cols] matrices."""
+    lib = _load()
+    a = np.ascontiguousarray(logits, dtype=np.int32)
+    cols = a.shape[-1]
+    rows = a.size // cols
+    out = np.zeros(a.shape, dtype=np.uint8)
+    rc = lib.intattn_oracle_index_softmax(rows, cols, _ptr(a), int(c_int_), lut_bits, clip, int(rows_per_matrix),
+                                          int(bool(causal)), _ptr(out))
+    if rc:
+        raise ValueError(f"intattn_oracle_index_softmax rc={rc}")
+    return out
 
 
 def quantize(x, per_head: bool = False):

@@ -521,3 +521,43 @@ def test_rectangular_rows_entry_and_bad_shapes(oracle):
     with pytest.raises(ValueError):
         oracle.forward(p.q, np.ascontiguousarray(p.k[:, :, :30]), np.ascontiguousarray(p.v[:, :, :30]),
                        p.s_q, p.s_k, p.s_v, causal=True)
+
+
+# ----------------------------------------------------------------------------- IndexSoftmax as an operator
+@pytest.mark.parametrize("causal", [False, True])
+def test_index_softmax_operator_equals_the_pipeline_tap(oracle, causal):
+    """Fed with Q.K^T computed by numpy, the operator returns the probabilities the (pinned)
+    attention pipeline produces, square and rectangular, with and without mask."""
+    for (lq, lk) in ((23, 23), (7, 31)):
+        base = inputs.random_problem(70 + lq, 2, 2, 1, max(lq, lk), 8, causal)
+        q = np.ascontiguousarray(base.q[:, :, :lq])
+        k = np.ascontiguousarray(base.k[:, :, :lk])
+        v = np.ascontiguousarray(base.v[:, :, :lk])
+        want = oracle.forward(q, k, v, base.s_q, base.s_k, base.s_v, causal=causal, want_prob=True)["prob"]
+        logits = np.einsum("bhid,bjd->bhij", q.astype(np.int64), k[:, 0].astype(np.int64)).astype(np.int32)
+        ci = oracle.c_int(CLIP, base.s_q[0], base.s_k[0], 8)
+        got = oracle.index_softmax(logits, ci, rows_per_matrix=lq, causal=causal)
+        np.testing.assert_array_equal(got, want)
+
+
+def test_index_softmax_operator_exact_rational_and_invariants(oracle):
+    rng = np.random.default_rng(5)
+    lut = oracle.lut()
+    a = rng.integers(-40000, 40000, size=(6, 50)).astype(np.int32)
+    a[1] = 7                       # equal logits: uniform
+    a[2, 3] = 2**31 - 1            # extreme values: the distance needs more than 32 bits
+    a[2, 4] = -2**31
+    for ci in (1, 37, 5203, 2**30):
+        p = oracle.index_softmax(a, ci)
+        for r in range(a.shape[0]):
+            row = [int(x) for x in a[r]]
+            m = max(row)
+            e = [int(lut[round_half_up(Fraction(min(m - x, ci) * 31, ci))]) for x in row]
+            s = sum(e)
+            assert list(p[r]) == [round_half_up(Fraction(255 * x, s)) for x in e]
+        assert (p[1] == round_half_up(Fraction(255, 50))).all()
+        assert p[2, 3] == 255 or ci == 2**30  # the dominant logit takes everything unless nothing is clipped away
+    with pytest.raises(ValueError):
+        oracle.index_softmax(a, 0)
+    with pytest.raises(ValueError):
+        oracle.index_softmax(a, 5, rows_per_matrix=4, causal=True)  # 6 rows are not stacked 4-row matrices

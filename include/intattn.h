@@ -131,6 +131,31 @@ INTATTN_API int intattn_forward_dynamic(intattn_ctx *ctx, const intattn_args *ar
  * stream that call was enqueued on. */
 INTATTN_API int intattn_dynamic_status(intattn_ctx *ctx, int32_t *status);
 
+/*
+ * IndexSoftmax as an operator of its own (Sec. 3.1-3.2; the paper's softmax-only setting): INT32
+ * logits in, UINT8 probabilities out, per row
+ *   P = round(255 * LUT_hat[round(min(rowMax - A, c_int) * (2^b - 1) / c_int)] / rowSum(LUT_hat[...])).
+ * The table is the context's (lut_bits, clip); c_int comes from the caller (intattn_derive_params
+ * computes it from scales, Eq. clipping_thr).
+ */
+typedef struct {
+    int64_t rows;            /* >= 1                                                          */
+    int32_t cols;            /* 1 .. 2^29                                                     */
+    int32_t c_int;           /* clip threshold in logit units, 1 .. 2^30                      */
+    const int32_t *logits;   /* DEVICE [rows, cols]                                           */
+    uint8_t *prob;           /* DEVICE [rows, cols]; must not alias logits                    */
+    int64_t logits_stride;   /* BYTES between rows, >= 4 * cols, multiple of 4                */
+    int64_t prob_stride;     /* BYTES between rows, >= cols.  Rows that all start 16-byte
+                                (logits) and 4-byte (prob) aligned take the wide accesses     */
+    int32_t causal;          /* 0, or 1: the rows are stacked [rows_per_matrix, cols] matrices
+                                with the attention mask: row r of a matrix sees columns
+                                j <= r + cols - rows_per_matrix; hidden columns get 0          */
+    int32_t rows_per_matrix; /* used when causal: >= 1, <= cols, divides rows                 */
+} intattn_softmax_args;
+
+/* Enqueues the operator on hip_stream and returns without waiting.  Allocates nothing. */
+INTATTN_API int intattn_index_softmax(intattn_ctx *ctx, const intattn_softmax_args *args, void *hip_stream);
+
 /* In-run comparator: the conventional INT8 pipeline the paper calls "Quant-Only"
  * (Sec. 2.2): INT8 Q.K^T, dequantize to fp32 with alpha, fp32 softmax, requantize P to
  * signed INT8 (x127), INT8 P.V, requantize the output with the same s_O.  Same arguments

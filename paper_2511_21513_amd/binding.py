@@ -25,6 +25,7 @@ SYMBOLS = (
     "intattn_dynamic_status",
     "intattn_forward_quantonly",
     "intattn_quantize",
+    "intattn_index_softmax",
     "intattn_derive_params",
     "intattn_derive_index_map",
     "intattn_get_lut",
@@ -63,6 +64,15 @@ class Args(ctypes.Structure):
     ]
 
 
+class SoftmaxArgs(ctypes.Structure):
+    _fields_ = [
+        ("rows", ctypes.c_int64), ("cols", ctypes.c_int32), ("c_int", ctypes.c_int32),
+        ("logits", ctypes.c_void_p), ("prob", ctypes.c_void_p),
+        ("logits_stride", ctypes.c_int64), ("prob_stride", ctypes.c_int64),
+        ("causal", ctypes.c_int32), ("rows_per_matrix", ctypes.c_int32),
+    ]
+
+
 class QuantArgs(ctypes.Structure):
     _fields_ = [
         ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L", ctypes.c_int32), ("d", ctypes.c_int32),
@@ -97,6 +107,8 @@ def load() -> ctypes.CDLL:
         lib.intattn_forward_dynamic.restype = ctypes.c_int
         lib.intattn_dynamic_status.argtypes = [vp, ctypes.POINTER(i32)]
         lib.intattn_dynamic_status.restype = ctypes.c_int
+        lib.intattn_index_softmax.argtypes = [vp, ctypes.POINTER(SoftmaxArgs), vp]
+        lib.intattn_index_softmax.restype = ctypes.c_int
         lib.intattn_quantize.argtypes = [vp, ctypes.POINTER(QuantArgs), vp]
         lib.intattn_quantize.restype = i32
         lib.intattn_forward_quantonly.argtypes = [vp, ctypes.POINTER(Args), vp]
@@ -243,6 +255,33 @@ class IntAttn:
         if rc != OK:
             raise IntAttnError(rc, self.last_error())
         return int(st.value)
+
+    def index_softmax(self, logits, c_int: int, *, causal: bool = False, rows_per_matrix: int = 0, out=None, stream=None):
+        """intattn_index_softmax on a torch int32 tensor [..., cols] (rows contiguous, all leading
+        axes collapsible to one row stride): uint8 probabilities of the same shape."""
+        import torch
+
+        cols = logits.shape[-1]
+        flat = logits.reshape(-1, cols)  # a view, or torch raises on a copy below
+        if flat.data_ptr() != logits.data_ptr() or flat.stride(-1) != 1:
+            raise ValueError("logits must be viewable as [rows, cols] with contiguous rows")
+        if out is None:
+            out = torch.empty(logits.shape, dtype=torch.uint8, device=logits.device)
+        oflat = out.reshape(-1, cols)
+        if oflat.data_ptr() != out.data_ptr() or oflat.stride(-1) != 1 or oflat.shape[0] != flat.shape[0]:
+            raise ValueError("out must be viewable as [rows, cols] with contiguous rows")
+        a = SoftmaxArgs()
+        a.rows, a.cols, a.c_int = flat.shape[0], cols, int(c_int)
+        a.logits, a.prob = flat.data_ptr(), oflat.data_ptr()
+        a.logits_stride = (flat.stride(0) if flat.shape[0] > 1 else cols) * 4
+        a.prob_stride = oflat.stride(0) if oflat.shape[0] > 1 else cols
+        a.causal, a.rows_per_matrix = int(bool(causal)), int(rows_per_matrix)
+        if stream is None:
+            stream = torch.cuda.current_stream(logits.device).cuda_stream
+        rc = self._lib.intattn_index_softmax(self._ctx, ctypes.byref(a), ctypes.c_void_p(stream))
+        if rc != OK:
+            raise IntAttnError(rc, self.last_error())
+        return out
 
     def quantize(self, x, per_head: bool = False, out=None, scales=None, stream=None):
         """intattn_quantize on a [B, H, L, d] device tensor (torch float32 / float16 / bfloat16,

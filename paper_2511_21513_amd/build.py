@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libintattn.so")
 SOURCES = ["api.cpp", "fwd_kernel.hip", "fwd_single.hip", "fwd_split.hip", "sweep_ab.hip", "sweep_c.hip",
-           "quantize_kernel.hip", "derive_kernel.hip", "decode_kernel.hip", "quantonly_kernel.hip"]
+           "quantize_kernel.hip", "derive_kernel.hip", "decode_kernel.hip", "softmax_kernel.hip", "quantonly_kernel.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

@@ -615,6 +615,53 @@ int intattn_dynamic_status(intattn_ctx *ctx, int32_t *status)
     return INTATTN_OK;
 }
 
+int intattn_index_softmax(intattn_ctx *ctx, const intattn_softmax_args *a, void *hip_stream)
+{
+    if (!ctx) return INTATTN_ERR_INVALID_ARG;
+    if (!a) return fail(ctx, INTATTN_ERR_INVALID_ARG, "args is NULL");
+    if (ctx->device < 0) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "host-only context: no device to run on");
+    if (a->rows < 1 || a->cols < 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "rows and cols must be >= 1");
+    if (a->cols > (1 << 29)) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "cols must not exceed 2^29");
+    if (a->c_int < 1 || a->c_int > (1 << 30)) return fail(ctx, INTATTN_ERR_INVALID_ARG, "c_int must be in 1 .. 2^30");
+    if (!a->logits || !a->prob) return fail(ctx, INTATTN_ERR_INVALID_ARG, "logits and prob must be non-NULL");
+    if ((const void *)a->prob == (const void *)a->logits) return fail(ctx, INTATTN_ERR_INVALID_ARG, "prob must not alias logits");
+    if (((uintptr_t)a->logits) & 3u) return fail(ctx, INTATTN_ERR_INVALID_ARG, "logits must be 4-byte aligned");
+    if (a->logits_stride < 4 * (int64_t)a->cols || (a->logits_stride & 3) != 0)
+        return fail(ctx, INTATTN_ERR_INVALID_ARG, "logits_stride must be a multiple of 4 and at least 4 * cols");
+    if (a->prob_stride < (int64_t)a->cols) return fail(ctx, INTATTN_ERR_INVALID_ARG, "prob_stride must be at least cols");
+    if (a->causal != 0 && a->causal != 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "causal must be 0 or 1");
+    if (a->causal && (a->rows_per_matrix < 1 || a->rows_per_matrix > a->cols || a->rows % a->rows_per_matrix != 0))
+        return fail(ctx, INTATTN_ERR_INVALID_ARG, "rows_per_matrix must be in 1 .. cols and divide rows");
+    const int64_t blocks = a->cols <= 2048 ? (a->rows + 3) / 4 : a->rows;
+    if (blocks > 2147483647LL) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "problem needs more than 2^31-1 workgroups");
+    SoftmaxParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.logits = a->logits; p.prob = a->prob;
+    p.ls = a->logits_stride; p.ps = a->prob_stride;
+    p.rows = a->rows; p.cols = a->cols;
+    p.vec_in = ((((uintptr_t)a->logits) & 15u) == 0 && (a->logits_stride & 15) == 0) ? 1 : 0;
+    p.vec_out = ((((uintptr_t)a->prob) & 3u) == 0 && (a->prob_stride & 3) == 0) ? 1 : 0;
+    p.rows_per_matrix = a->causal ? a->rows_per_matrix : 1;
+    p.causal = a->causal;
+    p.top = (1 << ctx->lut_bits) - 1;
+    std::memcpy(p.lut, ctx->lut, 32);
+    // the cheapest exact index map for this threshold
+    p.hp.c_int = a->c_int;
+    typedef bool (*finder)(uint32_t, uint32_t, HeadParams *);
+    const finder finders[4] = {find_mulhi24, find_mad24, find_fp32, find_fp64};
+    const int modes[4] = {IDX_MULHI24, IDX_MAD24, IDX_FP32, IDX_FP64};
+    int m = 0;
+    while (m < 4 && !finders[m]((uint32_t)a->c_int, (uint32_t)p.top, &p.hp)) ++m;
+    if (m == 4) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "no exact index map for this c_int");
+    p.hp.pad[0] = modes[m];
+    DeviceGuard guard(ctx->device);
+    if (guard.status != hipSuccess) return hip_fail(ctx, guard.status, "hipSetDevice");
+    const int herr = launch_index_softmax(p, hip_stream);
+    if (herr != 0) return hip_fail(ctx, (hipError_t)herr, "launch(index softmax)");
+    ctx->err.clear();
+    return INTATTN_OK;
+}
+
 int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *a, void *hip_stream)
 {
     if (!ctx) return INTATTN_ERR_INVALID_ARG;

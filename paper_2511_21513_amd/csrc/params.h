@@ -74,6 +74,20 @@ struct QuantParams {
     int32_t n_partial;
 };
 
+// Arguments of IndexSoftmax as an operator on INT32 logits (Sec. 3.1-3.2).
+struct SoftmaxParams {
+    const int32_t *logits; // device [rows, cols]
+    uint8_t *prob;         // device [rows, cols]
+    int64_t ls, ps;        // byte strides of a row
+    int64_t rows;
+    int32_t cols;
+    int32_t rows_per_matrix, causal; // causal: row r of each stacked matrix sees columns j <= r % rows_per_matrix + cols - rows_per_matrix
+    int32_t top;           // 2^b - 1
+    int32_t vec_in, vec_out; // rows start 16-byte (logits) / 4-byte (prob) aligned: wide loads / stores
+    HeadParams hp;         // c_int and the index-map constants, scheme in pad[0]
+    uint32_t lut[8];
+};
+
 // Arguments of the derivation of HeadParams from device-resident scales.
 struct DeriveParams {
     const float *scale_q, *scale_k, *scale_v, *scale_out; // device; scale_out may be null (= scale_v)
@@ -100,6 +114,7 @@ bool fwd_variant_known(int variant);
 int quantize_partials_per_slice(int B, int H, int L, int d);
 int launch_quantize(const QuantParams &p, void *stream);
 int launch_decode(const FwdParams &p, int d, void *stream);
+int launch_index_softmax(const SoftmaxParams &p, void *stream);
 int launch_derive(const DeriveParams &dp, void *stream);
 int launch_quantonly(const FwdParams &p, int d, int variant, void *stream);
 

@@ -45,6 +45,7 @@ def test_struct_layout_matches_header(lib):
     fields_cfg = [f[0] for f in binding.Config._fields_]
     fields_arg = [f[0] for f in binding.Args._fields_]
     fields_qnt = [f[0] for f in binding.QuantArgs._fields_]
+    fields_smx = [f[0] for f in binding.SoftmaxArgs._fields_]
     src = ['#include <stdio.h>', '#include <stddef.h>', f'#include "{HEADER}"', "int main(void){"]
     src.append('printf("%zu\\n", sizeof(intattn_config));')
     src += [f'printf("%zu\\n", offsetof(intattn_config, {f}));' for f in fields_cfg]
@@ -52,6 +53,8 @@ def test_struct_layout_matches_header(lib):
     src += [f'printf("%zu\\n", offsetof(intattn_args, {f}));' for f in fields_arg]
     src.append('printf("%zu\\n", sizeof(intattn_quant_args));')
     src += [f'printf("%zu\\n", offsetof(intattn_quant_args, {f}));' for f in fields_qnt]
+    src.append('printf("%zu\\n", sizeof(intattn_softmax_args));')
+    src += [f'printf("%zu\\n", offsetof(intattn_softmax_args, {f}));' for f in fields_smx]
     src.append("return 0;}")
     with tempfile.TemporaryDirectory() as td:
         c = os.path.join(td, "probe.c")
@@ -62,6 +65,7 @@ def test_struct_layout_matches_header(lib):
     want = [ctypes.sizeof(binding.Config)] + [getattr(binding.Config, f).offset for f in fields_cfg]
     want += [ctypes.sizeof(binding.Args)] + [getattr(binding.Args, f).offset for f in fields_arg]
     want += [ctypes.sizeof(binding.QuantArgs)] + [getattr(binding.QuantArgs, f).offset for f in fields_qnt]
+    want += [ctypes.sizeof(binding.SoftmaxArgs)] + [getattr(binding.SoftmaxArgs, f).offset for f in fields_smx]
     assert vals == want
 
 
@@ -236,3 +240,9 @@ def test_dynamic_forward_needs_a_device(host_ctx, lib):
     assert lib.intattn_forward_dynamic(host_ctx._ctx, ctypes.byref(a), None) == binding.ERR_INVALID_ARG
     assert host_ctx.dynamic_status() == 0
     assert lib.intattn_dynamic_status(host_ctx._ctx, None) == binding.ERR_INVALID_ARG
+
+
+def test_index_softmax_rejects_bad_arguments_without_a_gpu(host_ctx, lib):
+    a = binding.SoftmaxArgs()
+    assert lib.intattn_index_softmax(host_ctx._ctx, None, None) == binding.ERR_INVALID_ARG
+    assert lib.intattn_index_softmax(host_ctx._ctx, ctypes.byref(a), None) == binding.ERR_UNSUPPORTED  # host-only context

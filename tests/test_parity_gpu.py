@@ -602,3 +602,48 @@ def test_split_key_kernels_bit_exact(torch_mod, oracle, shape):
     torch.cuda.synchronize()
     assert ia.dynamic_status() == 0 and int((out.cpu().numpy() != want["out"]).sum()) == 0
     ia.close()
+
+
+# ---------------------------------------------------------------- IndexSoftmax as an operator
+
+SOFTMAX_SHAPES = [
+    # rows, cols, c_int, causal rows_per_matrix (0: no mask)
+    (1, 1, 37, 0), (3, 5, 1, 0), (84, 197, 5203, 0), (64, 256, 55064, 0), (33, 257, 37, 0), (40, 1000, 10**6, 20),
+    (5, 2048, 5203, 5), (6, 2049, 2**30, 0), (4, 5000, 445, 2), (3, 16384, 5203, 3), (2, 16385, 28794, 0),
+    (2, 70001, 5203, 2),
+]
+
+
+@pytest.mark.parametrize("shape", SOFTMAX_SHAPES, ids=lambda s: "r{}c{}ci{}m{}".format(*s))
+def test_index_softmax_operator_bit_exact(torch_mod, oracle, shape):
+    """Every row layout of the operator (a wave or a workgroup per row, resident or streamed),
+    thresholds served by each index-map scheme, with and without the mask, rows with padding
+    between them, and logits at the ends of the int32 range."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    rows, cols, ci, rpm = shape
+    print(f"case {shape}", flush=True)
+    rng = np.random.default_rng(rows * 131 + cols)
+    spread = max(4 * ci, 50) if ci < 2**28 else 2**30
+    a = rng.integers(-spread, spread, size=(rows, cols), dtype=np.int64).astype(np.int32)
+    a[0, :] = 11                         # equal logits
+    if cols > 4:
+        a[-1, 3] = 2**31 - 1             # the distance to the maximum exceeds 31 bits
+        a[-1, 4] = -2**31
+    want = oracle.index_softmax(a, ci, rows_per_matrix=rpm, causal=rpm > 0)
+    ia = binding.IntAttn(device=0)
+    dev = torch.device("cuda:0")
+    got = ia.index_softmax(torch.from_numpy(a).to(dev), ci, causal=rpm > 0, rows_per_matrix=rpm)
+    torch.cuda.synchronize()
+    assert int((got.cpu().numpy() != want).sum()) == 0
+    # rows with padding between them (strides that are not the row length)
+    pad_c = (cols + 3) // 4 * 4 + 8
+    buf = torch.zeros((rows, pad_c), dtype=torch.int32, device=dev)
+    buf[:, :cols] = torch.from_numpy(a).to(dev)
+    outbuf = torch.full((rows, pad_c), 7, dtype=torch.uint8, device=dev)
+    ia.index_softmax(buf[:, :cols], ci, causal=rpm > 0, rows_per_matrix=rpm, out=outbuf[:, :cols])
+    torch.cuda.synchronize()
+    o = outbuf.cpu().numpy()
+    assert int((o[:, :cols] != want).sum()) == 0 and (o[:, cols:] == 7).all()
+    ia.close()

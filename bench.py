@@ -139,6 +139,53 @@ def quantizer_bench(a, name, dev):
     print(json.dumps(res))
 
 
+def softmax_bench(a, name, dev):
+    """One step = IndexSoftmax as an operator on INT32 logits of --softmax-heads heads of the
+    workload ([heads * L, L], no mask).  HBM-bound: 4 bytes in and 1 byte out per element."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2511_21513_amd import binding, inputs
+
+    L = inputs.CONFIGS[name][3]
+    rows, cols = a.softmax_heads * L, L
+    g = torch.Generator(device=dev).manual_seed(0)
+    c_int = 5203  # the workload's threshold
+    logits = torch.randint(-4 * c_int, 4 * c_int, (rows, cols), device=dev, dtype=torch.int32, generator=g)
+    prob = torch.empty((rows, cols), dtype=torch.uint8, device=dev)
+    ia = binding.IntAttn(device=0)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    for _ in range(a.warmup):
+        ia.index_softmax(logits, c_int, out=prob, stream=stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(a.steps):
+        ia.index_softmax(logits, c_int, out=prob, stream=stream)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / a.steps
+    alg_bytes = rows * cols * 5
+    gbps = alg_bytes / (ms * 1e-3) / 1e9
+    sample = np.unique(np.concatenate([[0, rows - 1], np.random.default_rng(0).integers(0, rows, 254)]))
+    t0 = time.perf_counter()
+    want = oracle.index_softmax(logits[sample].cpu().numpy(), c_int)
+    cpu_s = time.perf_counter() - t0
+    mism = int((prob[sample].cpu().numpy() != want).sum())
+    res = {"metric": "IndexSoftmax operator (INT32 logits -> UINT8 probabilities), algorithmic GB/s", "value": gbps,
+           "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+           "config": {"workload": f"logits of {a.softmax_heads} heads of {name}", "rows": rows, "cols": cols, "c_int": c_int},
+           "parity_mismatching_bytes": mism,
+           "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBS,
+                        "traffic": None, "kernel": "index_softmax_kernel", "algorithmic_bytes_per_step": alg_bytes},
+           "cpu_baseline": {"value": sample.size * cols * 5 / cpu_s / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                            "sample": f"{sample.size} of {rows} rows, {cpu_s:.2f} s"}}
+    ia.close()
+    print(json.dumps(res))
+
+
 def decode_bench(a, name, dev):
     """One step = one decoded token for each of --decode-batch sequences: L = 1 query row per head
     against the workload's key/value length, heads and head dimension, causal (the token sees every
@@ -213,6 +260,10 @@ def main():
                     help="instead of the benchmark, run a plain device copy of this many MiB three times "
                          "(the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-heads", type=int, default=32)
+    ap.add_argument("--softmax", action="store_true",
+                    help="instead of the attention benchmark, time IndexSoftmax as an operator on INT32 logits of "
+                         "the workload's length (HBM-bound)")
+    ap.add_argument("--softmax-heads", type=int, default=8)
     ap.add_argument("--decode", action="store_true",
                     help="instead of the prefill benchmark, time one decoded token per sequence against the "
                          "workload's key/value length (split-key kernels, HBM-bound)")
@@ -248,6 +299,8 @@ def main():
         return quantizer_bench(a, name, dev)
     if a.decode:
         return decode_bench(a, name, dev)
+    if a.softmax:
+        return softmax_bench(a, name, dev)
     p = inputs.make_problem(name)
     ia = binding.IntAttn(device=0, variant=a.variant)
     q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))

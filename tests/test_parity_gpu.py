@@ -647,3 +647,42 @@ def test_index_softmax_operator_bit_exact(torch_mod, oracle, shape):
     o = outbuf.cpu().numpy()
     assert int((o[:, :cols] != want).sum()) == 0 and (o[:, cols:] == 7).all()
     ia.close()
+
+
+# ---------------------------------------------------------------- other table resolutions b and clip bounds c
+
+@pytest.mark.parametrize("bc", [(1, 6.6), (2, 5.5), (3, 6.0), (4, 7.7), (5, 5.5), (5, 7.7)], ids=lambda t: f"b{t[0]}c{t[1]}")
+def test_other_lut_bits_and_clip(torch_mod, oracle, bc):
+    """The (b, c) settings of the paper's sweep (Sec. 4, table resolution and clip bound): tiled
+    kernels in one and in three launches, the split-key kernels, and the operator, against the
+    oracle with the same (b, c)."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    b, c = bc
+    dev = torch.device("cuda:0")
+    p = inputs.random_problem(600 + b, 1, 4, 2, 300, 64, True, per_head=True, spread=1.5)
+    want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, None, causal=True, per_head=True, lut_bits=b, clip=c, taps=True)
+    q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
+    for variant in (1, 5):
+        ia = binding.IntAttn(device=0, lut_bits=b, clip=c, variant=variant)
+        got = ia.forward(q, k, v, p.s_q, p.s_k, p.s_v, None, causal=True, per_head=True, taps=True)
+        torch.cuda.synchronize()
+        for key in ("row_sum", "acc", "out"):
+            assert int((got[key].cpu().numpy() != want[key]).sum()) == 0, (variant, key)
+        ia.close()
+    # one decoded token: the split-key kernels
+    ia = binding.IntAttn(device=0, lut_bits=b, clip=c, variant=9)
+    q1 = np.ascontiguousarray(p.q[:, :, :1])
+    w1 = oracle.forward(q1, p.k, p.v, p.s_q, p.s_k, p.s_v, None, causal=True, per_head=True, lut_bits=b, clip=c)["out"]
+    g1 = ia.forward(torch.from_numpy(q1).to(dev), k, v, p.s_q, p.s_k, p.s_v, None, causal=True, per_head=True)
+    torch.cuda.synchronize()
+    assert int((g1.cpu().numpy() != w1).sum()) == 0
+    # the operator on the logits of head 0
+    logits = (p.q[0, 0].astype(np.int64) @ p.k[0, 0].astype(np.int64).T).astype(np.int32)
+    ci = oracle.c_int(c, p.s_q[0], p.s_k[0], 64)
+    wp = oracle.index_softmax(logits, ci, lut_bits=b, clip=c, rows_per_matrix=300, causal=True)
+    gp = ia.index_softmax(torch.from_numpy(logits).to(dev), ci, causal=True, rows_per_matrix=300)
+    torch.cuda.synchronize()
+    assert int((gp.cpu().numpy() != wp).sum()) == 0
+    ia.close()

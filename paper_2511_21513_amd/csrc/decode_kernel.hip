@@ -67,18 +67,6 @@ __device__ __forceinline__ void stage_tile(const int8_t *base, int64_t stride, i
 #endif
 }
 
-// The index map of Sec. 3.1 with the scheme named in the head's parameters (chosen on the host,
-// or by the derivation kernel for device-resident scales).
-__device__ __forceinline__ uint32_t index_any(const HeadParams &hp, int t, uint32_t top)
-{
-    switch (hp.pad[0]) {
-    case IDX_MAD24: return index_map<IDX_MAD24>(t, hp, top);
-    case IDX_MULHI24: return index_map<IDX_MULHI24>(t, hp, top);
-    case IDX_FP32: return index_map<IDX_FP32>(t, hp, top);
-    default: return index_map<IDX_FP64>(t, hp, top);
-    }
-}
-
 // max (IS_MAX) or sum over all 32-key sub-tiles of the per-tile partials of every packed row:
 // red[r] for r < R.  src is [nt32][R].  Thread tid takes row tid % R of every (NT / R)-th sub-tile, so
 // all threads load (several loads in flight each), then one LDS atomic per thread.  Ends with a barrier.

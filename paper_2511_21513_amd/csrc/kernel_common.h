@@ -82,6 +82,18 @@ __device__ __forceinline__ uint32_t index_map(int t, const HeadParams &hp, uint3
     }
 }
 
+// The map with the scheme named in the parameters themselves (pad[0]: chosen on the host, or by
+// the derivation kernel for device-resident scales), for kernels where the map is not the hot loop.
+__device__ __forceinline__ uint32_t index_any(const HeadParams &hp, int t, uint32_t top)
+{
+    switch (hp.pad[0]) {
+    case IDX_MAD24: return index_map<IDX_MAD24>(t, hp, top);
+    case IDX_MULHI24: return index_map<IDX_MULHI24>(t, hp, top);
+    case IDX_FP32: return index_map<IDX_FP32>(t, hp, top);
+    default: return index_map<IDX_FP64>(t, hp, top);
+    }
+}
+
 // The same map applied to RAW scores of one query row (the lane's row): with the row maximum
 // mx, idx = round(min(mx - s, c_int) * top / c_int).  The subtraction of mx is folded into
 // per-row constants (all arithmetic is modulo 2^32 and the true values are small), so a

@@ -15,16 +15,6 @@ namespace intattn {
 
 namespace {
 
-__device__ __forceinline__ uint32_t index_any(const HeadParams &hp, int t, uint32_t top)
-{
-    switch (hp.pad[0]) {
-    case IDX_MAD24: return index_map<IDX_MAD24>(t, hp, top);
-    case IDX_MULHI24: return index_map<IDX_MULHI24>(t, hp, top);
-    case IDX_FP32: return index_map<IDX_FP32>(t, hp, top);
-    default: return index_map<IDX_FP64>(t, hp, top);
-    }
-}
-
 __device__ __forceinline__ int32_t wave_max(int32_t v)
 {
 #pragma unroll

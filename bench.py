@@ -260,6 +260,9 @@ def main():
                     help="instead of the benchmark, run a plain device copy of this many MiB three times "
                          "(the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-heads", type=int, default=32)
+    ap.add_argument("--batch", type=int, default=None,
+                    help="override the workload's batch size (e.g. --workload c2 --batch 512 shows the bandwidth the "
+                         "kernel reaches on short sequences once the GPU is filled)")
     ap.add_argument("--softmax", action="store_true",
                     help="instead of the attention benchmark, time IndexSoftmax as an operator on INT32 logits of "
                          "the workload's length (HBM-bound)")
@@ -301,7 +304,7 @@ def main():
         return decode_bench(a, name, dev)
     if a.softmax:
         return softmax_bench(a, name, dev)
-    p = inputs.make_problem(name)
+    p = inputs.make_problem(name, B=a.batch)  # --batch: a scaled-batch variant of a short workload (not the headline line)
     ia = binding.IntAttn(device=0, variant=a.variant)
     q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
     out = torch.empty_like(q)
@@ -353,7 +356,7 @@ def main():
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
-        "config": {"workload": name, "B": p.B, "Hq": p.Hq, "Hkv": p.Hkv, "L": p.L, "d": p.d,
+        "config": {"workload": name + (f" (batch scaled to {a.batch})" if a.batch else ""), "B": p.B, "Hq": p.Hq, "Hkv": p.Hkv, "L": p.L, "d": p.d,
                    "causal": p.causal, "scales": "per-head" if p.per_head else "per-tensor",
                    "lut_bits": 5, "clip": 6.6, "variant": a.variant},
         "pct_of_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,

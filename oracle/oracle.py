@@ -180,6 +180,36 @@ def rows(q, k, v, s_q, s_k, s_v, s_o=None, *, b, hq, rows, causal=False, per_hea
     return res
 
 
+def forward_row_groups(q, k, v, s_q, s_k, s_v, s_o=None, *, q_block, causal=False, lut_bits=5, clip=6.6, taps=False):
+    """Finer quantization groups over the QUERY rows (Sec. 3.3 with groups = blocks of ``q_block``
+    consecutive query rows of one (batch, head); ``q_block`` = 1 is per-token quantization of Q):
+    ``s_q`` (and ``s_o`` if given) hold one scale per group, [B, Hq, ceil(L / q_block)]; ``s_k``,
+    ``s_v`` one per KV head.  Rows never interact, so the definition is the per-tensor pipeline run
+    on each group's rows with that group's scales -- which is literally what this does."""
+    B, Hq, Hkv, L, Lk, d = _check_inputs(q, k, v)
+    nblk = (L + q_block - 1) // q_block
+    sq = np.asarray(s_q, dtype=np.float32).reshape(B, Hq, nblk)
+    so = None if s_o is None else np.asarray(s_o, dtype=np.float32).reshape(B, Hq, nblk)
+    sk, sv = _f32(s_k), _f32(s_v)
+    g = Hq // Hkv
+    res = {"out": np.zeros((B, Hq, L, d), dtype=np.int8)}
+    if taps:
+        res["row_max"] = np.zeros((B, Hq, L), dtype=np.int32)
+        res["row_sum"] = np.zeros((B, Hq, L), dtype=np.int32)
+        res["acc"] = np.zeros((B, Hq, L, d), dtype=np.int32)
+    for b in range(B):
+        for h in range(Hq):
+            kv = h // g
+            for blk in range(nblk):
+                r0, r1 = blk * q_block, min(L, (blk + 1) * q_block)
+                part = rows(q, k, v, sq[b, h, blk:blk + 1], sk[kv:kv + 1], sv[kv:kv + 1],
+                            None if so is None else so[b, h, blk:blk + 1], b=b, hq=h, rows=np.arange(r0, r1),
+                            causal=causal, per_head=False, lut_bits=lut_bits, clip=clip)
+                for key in res:
+                    res[key][b, h, r0:r1] = part[key]
+    return res
+
+
 def index_softmax(logits, c_int_: int, *, lut_bits=5, clip=6.6, rows_per_matrix=0, causal=False):
     """IndexSoftmax on int32 logits [..., cols] (rows are everything before the last axis): uint8
     probabilities of the same shape.  ``causal`` with ``rows_per_matrix``: the attention path's mask

@@ -561,3 +561,29 @@ def test_index_softmax_operator_exact_rational_and_invariants(oracle):
         oracle.index_softmax(a, 0)
     with pytest.raises(ValueError):
         oracle.index_softmax(a, 5, rows_per_matrix=4, causal=True)  # 6 rows are not stacked 4-row matrices
+
+
+# ----------------------------------------------------------------------------- finer groups over query rows
+def test_row_groups_reduce_to_per_head_and_follow_each_groups_scale(oracle):
+    """Sec. 3.3 with groups = blocks of query rows: equal group scales give the per-head result;
+    with distinct scales every row follows the exact-rational pipeline with ITS group's c_int."""
+    p = inputs.random_problem(81, 2, 4, 2, 29, 8, True, per_head=True)
+    qb = 4
+    nblk = (p.L + qb - 1) // qb
+    same = np.broadcast_to(p.s_q[None, :, None], (2, 4, nblk)).copy()
+    a = oracle.forward_row_groups(p.q, p.k, p.v, same, p.s_k, p.s_v, q_block=qb, causal=True, taps=True)
+    b = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, causal=True, per_head=True, taps=True)
+    for key in ("out", "row_max", "row_sum", "acc"):
+        np.testing.assert_array_equal(a[key], b[key])
+    rng = np.random.default_rng(2)
+    s_q = (same * rng.uniform(0.2, 3.0, size=same.shape)).astype(np.float32)
+    r = oracle.forward_row_groups(p.q, p.k, p.v, s_q, p.s_k, p.s_v, q_block=qb, causal=True, taps=True)
+    lut = oracle.lut()
+    for (bb, h, i) in ((0, 0, 0), (0, 1, 7), (1, 3, 28), (1, 2, 16)):
+        kv = h // 2
+        ci = oracle.c_int(CLIP, s_q[bb, h, i // qb], p.s_k[kv], 8)
+        rq = oracle.requant_params(p.s_v[kv], p.s_v[kv])
+        m, s, pr, acc, out = python_reference_row(p.q[bb, h, i], p.k[bb, kv], p.v[bb, kv], i + 1, ci, lut, rq)
+        assert r["row_max"][bb, h, i] == m and r["row_sum"][bb, h, i] == s
+        assert list(r["acc"][bb, h, i]) == acc and list(r["out"][bb, h, i]) == out
+    assert (r["row_sum"] != b["row_sum"]).any()  # the group scales do change the result

@@ -135,6 +135,28 @@ def quantizer_bench(a, name, dev):
     res["chain_fp16_to_int8_attention"] = {"entries": "3 x intattn_quantize + intattn_forward_dynamic",
                                            "ms_per_step": e0.elapsed_time(e1) / a.steps,
                                            "status": ia.dynamic_status()}
+    # the same chain with Q quantized per token (finer groups over the query rows, Sec. 3.3)
+    tok_scales = torch.empty((B, Hq, L), dtype=torch.float32, device=dev)
+    hk, hv = (torch.empty(Hkv, dtype=torch.float32, device=dev) for _ in range(2))
+    targs, tkeep = ia.make_args(outs[0], outs[1], outs[2], att_out, tok_scales, hk, hv, None, causal=causal,
+                                device_scales=True, q_block=1)
+
+    def chain_tok():
+        ia.quantize(xs[0], out=outs[0], scales=tok_scales, stream=stream, q_block=1)
+        ia.quantize(xs[1], True, out=outs[1], scales=hk, stream=stream)
+        ia.quantize(xs[2], True, out=outs[2], scales=hv, stream=stream)
+        ia.forward_dynamic_args(targs, stream)
+
+    for _ in range(2):
+        chain_tok()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(a.steps):
+        chain_tok()
+    e1.record()
+    torch.cuda.synchronize()
+    res["chain_per_token_q"] = {"entries": "intattn_quantize (Q, q_block 1) + 2 x intattn_quantize (K, V per head) + intattn_forward_dynamic (scale_mode 2)",
+                                "ms_per_step": e0.elapsed_time(e1) / a.steps, "status": ia.dynamic_status()}
     ia.close()
     print(json.dumps(res))
 

@@ -77,7 +77,12 @@ typedef struct {
     int8_t *out;              /* DEVICE  [B, Hq,  L, d]                                       */
     int64_t q_stride[3], k_stride[3], v_stride[3], out_stride[3];
     int32_t scale_mode;       /* 0: one float per scale array; 1: per head ([Hq] for q and
-                                 out, [Hkv] for k and v), shared over the batch               */
+                                 out, [Hkv] for k and v), shared over the batch; 2
+                                 (intattn_forward_dynamic only): finer groups over the query
+                                 rows, Sec. 3.3 -- scale_q and scale_out hold one value per
+                                 block of q_block consecutive query rows of every (batch,
+                                 head), [B, Hq, ceil(L / q_block)] (q_block = 1: per token);
+                                 scale_k and scale_v one per KV head                          */
     int32_t Lkv;              /* number of keys / values; 0 means L (square self-attention).
                                  Lkv != L: a chunk of queries, or one decoded token, against a
                                  longer (or, without mask, any) key sequence; the causal mask
@@ -90,6 +95,8 @@ typedef struct {
     int32_t *dbg_row_max;     /* optional DEVICE [B, Hq, L] contiguous: rowMax(A_hat); NULL off */
     int32_t *dbg_row_sum;     /* optional DEVICE [B, Hq, L] contiguous: rowSum(E_hat); NULL off */
     int32_t *dbg_acc;         /* optional DEVICE [B, Hq, L, d] contiguous: P_hat.V_hat; NULL off */
+    int32_t q_block;          /* scale_mode 2 only: query rows per quantization group, >= 1   */
+    int32_t reserved;         /* must be 0                                                    */
 } intattn_args;
 
 /* Builds LUT_hat for (lut_bits, clip) (Sec. 3.1 Eq. lut_re, Sec. 3.2 Eq. lut16) and binds the
@@ -116,7 +123,8 @@ INTATTN_API int intattn_forward_stage(intattn_ctx *ctx, const intattn_args *args
 /* intattn_forward for scales that live in DEVICE memory, e.g. where intattn_quantize left them
  * (Sec. 2.1 dynamic quantization feeding Sec. 3): args->scale_q / scale_k / scale_v / scale_out
  * are DEVICE pointers here (same counts as for intattn_forward; scale_out may be NULL), every
- * other field is as there.  A small kernel on hip_stream derives each head's c_int (Sec. 3.1,
+ * other field is as there.  scale_mode 2 (one scale per block of q_block query rows, Sec. 3.3) is
+ * served by this entry only.  A small kernel on hip_stream derives each head's c_int (Sec. 3.1,
  * Eq. clipping_thr), requantization multiplier and index-map constants from them with the host
  * path's arithmetic, so the output is bit-identical to intattn_forward with the same scale
  * values, and the host never reads the scales: quantizer and attention can be enqueued back to
@@ -165,17 +173,21 @@ INTATTN_API int intattn_forward_quantonly(intattn_ctx *ctx, const intattn_args *
 
 /* Arguments of intattn_quantize.  src and dst are DEVICE pointers to [B, H, L, d] tensors with byte
  * strides for B, H, L (d contiguous, d a multiple of 8; src and its strides multiples of 16
- * bytes, dst and its strides multiples of 8); scales is a DEVICE array of 1 (scale_mode 0) or H (scale_mode 1) floats that receives
- * the scales.  The caller owns all three. */
+ * bytes, dst and its strides multiples of 8); scales is a DEVICE array of 1 (scale_mode 0), H (scale_mode 1) or
+ * B * H * ceil(L / q_block) (scale_mode 2) floats that receives the scales.  The caller owns all three. */
 typedef struct intattn_quant_args {
     int32_t B, H, L, d;
     int32_t dtype;       /* element type of src: 0 = fp32, 1 = fp16, 2 = bf16 */
-    int32_t scale_mode;  /* 0 = one scale for the tensor, 1 = one per head index (shared over the batch) */
+    int32_t scale_mode;  /* 0 = one scale for the tensor, 1 = one per head index (shared over the batch),
+                            2 = one per block of q_block consecutive rows of every (b, h) slice
+                            (Sec. 3.3; q_block = 1: per token): scales is [B, H, ceil(L / q_block)] */
     const void *src;
     int8_t *dst;
     int64_t src_stride[3];
     int64_t dst_stride[3];
     float *scales;
+    int32_t q_block;     /* scale_mode 2 only: rows per group, >= 1 */
+    int32_t reserved;    /* must be 0 */
 } intattn_quant_args;
 
 /* Dynamic symmetric INT8 quantization of one of Q, K, V (Sec. 2.1, Eq. quant): s = max|X| / 127

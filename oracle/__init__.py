@@ -13,6 +13,7 @@ from .oracle import (  # noqa: F401
     lut,
     prob,
     quantize,
+    quantize_row_groups,
     requant_params,
     rows,
 )

@@ -210,6 +210,25 @@ def forward_row_groups(q, k, v, s_q, s_k, s_v, s_o=None, *, q_block, causal=Fals
     return res
 
 
+def quantize_row_groups(x, q_block: int):
+    """Eq. quant with one scale per block of ``q_block`` consecutive rows of every (b, h) slice of
+    x [B, H, L, d] (``q_block`` = 1: per token): the per-tensor quantizer applied to each block.
+    Returns (int8 array, float32 scales [B, H, ceil(L / q_block)])."""
+    a = np.ascontiguousarray(x, dtype=np.float32)
+    B, H, L, d = a.shape
+    nblk = (L + q_block - 1) // q_block
+    xq = np.zeros(a.shape, dtype=np.int8)
+    scales = np.zeros((B, H, nblk), dtype=np.float32)
+    for b in range(B):
+        for h in range(H):
+            for blk in range(nblk):
+                r0, r1 = blk * q_block, min(L, (blk + 1) * q_block)
+                part, sc = quantize(a[b:b + 1, h:h + 1, r0:r1], per_head=False)
+                xq[b, h, r0:r1] = part[0, 0]
+                scales[b, h, blk] = sc[0]
+    return xq, scales
+
+
 def index_softmax(logits, c_int_: int, *, lut_bits=5, clip=6.6, rows_per_matrix=0, causal=False):
     """IndexSoftmax on int32 logits [..., cols] (rows are everything before the last axis): uint8
     probabilities of the same shape.  ``causal`` with ``rows_per_matrix``: the attention path's mask

@@ -61,6 +61,7 @@ class Args(ctypes.Structure):
         ("scale_q", ctypes.c_void_p), ("scale_k", ctypes.c_void_p),
         ("scale_v", ctypes.c_void_p), ("scale_out", ctypes.c_void_p),
         ("dbg_row_max", ctypes.c_void_p), ("dbg_row_sum", ctypes.c_void_p), ("dbg_acc", ctypes.c_void_p),
+        ("q_block", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -80,6 +81,7 @@ class QuantArgs(ctypes.Structure):
         ("src", ctypes.c_void_p), ("dst", ctypes.c_void_p),
         ("src_stride", ctypes.c_int64 * 3), ("dst_stride", ctypes.c_int64 * 3),
         ("scales", ctypes.c_void_p),
+        ("q_block", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -193,10 +195,12 @@ class IntAttn:
         return int(mode.value), int(mul.value), int(add.value), int(sh.value)
 
     def make_args(self, q, k, v, out, s_q, s_k, s_v, s_o=None, *, causal=False, per_head=False,
-                  row_max=None, row_sum=None, acc=None, device_scales=False):
+                  row_max=None, row_sum=None, acc=None, device_scales=False, q_block=0):
         """Marshals torch int8 tensors [B,H,L,d] (last dim contiguous) into an ``Args``.  Returns
         (args, keepalive): keepalive holds the scale arrays the struct points at: host arrays, or
-        with ``device_scales`` the float32 device tensors given (for ``forward_dynamic_args``)."""
+        with ``device_scales`` the float32 device tensors given (for ``forward_dynamic_args``).
+        ``q_block`` > 0 (device scales only): scale mode 2, s_q and s_o hold one value per block of
+        ``q_block`` query rows of every (batch, head), s_k and s_v one per KV head."""
         B, Hq, L, d = q.shape
         Hkv = k.shape[1]
         if k.shape != v.shape or k.shape[0] != B or k.shape[3] != d or out.shape != q.shape:
@@ -226,10 +230,17 @@ class IntAttn:
             keep = [_host_f32(s_q), _host_f32(s_k), _host_f32(s_v), _host_f32(s_o)]
             sizes = [t.size if t is not None else None for t in keep]
             ptr = lambda t: t.ctypes.data  # noqa: E731
-        want = [Hq, Hkv, Hkv, Hq] if per_head else [1, 1, 1, 1]
+        if q_block:
+            if not device_scales:
+                raise ValueError("q_block needs device_scales")
+            n_grp = B * Hq * ((L + q_block - 1) // q_block)
+            a.scale_mode, a.q_block = 2, int(q_block)
+            want = [n_grp, Hkv, Hkv, n_grp]
+        else:
+            want = [Hq, Hkv, Hkv, Hq] if per_head else [1, 1, 1, 1]
         for have, need in zip(sizes, want):
-            if have is not None and (have != need if per_head else have < 1):
-                raise ValueError("per-head scales must have Hq (q, out) / Hkv (k, v) entries")
+            if have is not None and (have != need if (per_head or q_block) else have < 1):
+                raise ValueError("scale arrays do not have the number of entries the scale mode needs")
         a.scale_q, a.scale_k, a.scale_v = (ptr(x) for x in keep[:3])
         a.scale_out = ptr(keep[3]) if keep[3] is not None else None
         a.dbg_row_max = row_max.data_ptr() if row_max is not None else None
@@ -283,9 +294,10 @@ class IntAttn:
             raise IntAttnError(rc, self.last_error())
         return out
 
-    def quantize(self, x, per_head: bool = False, out=None, scales=None, stream=None):
+    def quantize(self, x, per_head: bool = False, out=None, scales=None, stream=None, q_block: int = 0):
         """intattn_quantize on a [B, H, L, d] device tensor (torch float32 / float16 / bfloat16,
-        last dimension contiguous): returns (int8 tensor, float32 device tensor of 1 or H scales).
+        last dimension contiguous): returns (int8 tensor, float32 device tensor of 1 or H scales;
+        with ``q_block`` > 0 one scale per block of ``q_block`` rows, [B, H, ceil(L / q_block)]).
         Argument marshalling only."""
         import torch
 
@@ -296,10 +308,12 @@ class IntAttn:
         if out is None:
             out = torch.empty((B, H, L, d), dtype=torch.int8, device=x.device)
         if scales is None:
-            scales = torch.empty(H if per_head else 1, dtype=torch.float32, device=x.device)
+            shape = (B, H, (L + q_block - 1) // q_block) if q_block else (H if per_head else 1,)
+            scales = torch.empty(shape, dtype=torch.float32, device=x.device)
         a = QuantArgs()
         a.B, a.H, a.L, a.d = B, H, L, d
-        a.dtype, a.scale_mode = dtypes[x.dtype], int(per_head)
+        a.dtype, a.scale_mode = dtypes[x.dtype], 2 if q_block else int(per_head)
+        a.q_block = int(q_block)
         a.src, a.dst, a.scales = x.data_ptr(), out.data_ptr(), scales.data_ptr()
         es = x.element_size()
         for i in range(3):

@@ -29,6 +29,8 @@ struct intattn_ctx {
     // kernel workspace (row max and row sum between the two launches, V chunk sums), grown on demand
     int32_t *d_ws = nullptr;
     size_t ws_cap = 0; // in int32 elements
+    HeadParams *d_rowtab = nullptr; // parameters per block of query rows (scale_mode 2), grown on demand
+    size_t rowtab_cap = 0;
     int32_t *d_status = nullptr; // per head: what the last derivation on the device found (intattn_dynamic_status)
     int status_cap = 0, status_n = 0;
     float *d_amax = nullptr; // scratch of the quantizer: partial max|X| per workgroup of its first pass
@@ -271,8 +273,9 @@ int validate(intattn_ctx *ctx, const intattn_args *a)
     if (a->causal == 1 && Lk < a->L)
         return fail(ctx, INTATTN_ERR_INVALID_ARG, "a causal mask needs Lkv >= L (it is aligned to the end of the keys)");
     if (a->causal != 0 && a->causal != 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "causal must be 0 or 1");
-    if (a->scale_mode != 0 && a->scale_mode != 1)
-        return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode must be 0 or 1");
+    if (a->scale_mode < 0 || a->scale_mode > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode must be 0, 1 or 2");
+    if (a->scale_mode == 2 && a->q_block < 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode 2 needs q_block >= 1");
+    if (a->reserved != 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "reserved must be 0");
     if (!a->q || !a->k || !a->v || !a->out) return fail(ctx, INTATTN_ERR_INVALID_ARG, "q, k, v, out must be non-NULL");
     if (!a->scale_q || !a->scale_k || !a->scale_v)
         return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_q, scale_k, scale_v must be non-NULL");
@@ -392,8 +395,10 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
     int rc = validate(ctx, a);
     if (rc) return rc;
     if (ctx->device < 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "host-only context (device -1) cannot launch");
+    if (a->scale_mode == 2 && (!dynamic || comparator))
+        return fail(ctx, INTATTN_ERR_UNSUPPORTED, "scale_mode 2 (groups of query rows) is served by intattn_forward_dynamic only");
     Derived dv;
-    if (dynamic) dv.idx_mode = IDX_DEVICE;
+    if (dynamic) dv.idx_mode = a->scale_mode == 2 ? IDX_ROW64 : IDX_DEVICE;
     else rc = derive_all(ctx, a, &dv);
     if (rc) return rc;
 
@@ -424,7 +429,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
     // Few query rows against many keys: the split-key kernels (all query heads of a KV head, times
     // the query rows, packed into one MFMA operand of at most 31 rows).
     const int64_t packed_rows = (int64_t)p.group * p.L;
-    const bool decode_ok = !comparator && stage == 0 && packed_rows <= 31 && (int64_t)a->B * a->Hkv <= 65535;
+    const bool decode_ok = !comparator && stage == 0 && a->scale_mode != 2 && packed_rows <= 31 && (int64_t)a->B * a->Hkv <= 65535;
     const bool decode = decode_ok && (ctx->variant == 9 || (ctx->variant == 0 && p.Lk >= 1024));
 
     if (dynamic) {
@@ -442,7 +447,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
         DeriveParams dp;
         std::memset(&dp, 0, sizeof(dp));
         dp.scale_q = a->scale_q; dp.scale_k = a->scale_k; dp.scale_v = a->scale_v; dp.scale_out = a->scale_out;
-        dp.per_head = a->scale_mode;
+        dp.per_head = a->scale_mode != 0;
         dp.Hq = a->Hq;
         dp.group = p.group;
         dp.top = p.top;
@@ -451,11 +456,31 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
         dp.hp_table = ctx->d_hp;
         dp.status = ctx->d_status;
         ctx->hp_host.clear(); // the table no longer holds what the host last sent
-        if (stage != 2) { // stage 2 reads what stage 1 derived
-            const int e = launch_derive(dp, stream);
-            if (e != 0) return hip_fail(ctx, (hipError_t)e, "launch(derive head parameters)");
+        if (a->scale_mode == 2) {
+            dp.n_rowblk = (a->L + a->q_block - 1) / a->q_block;
+            dp.n_entries = (int64_t)a->B * a->Hq * dp.n_rowblk;
+            if ((size_t)dp.n_entries > ctx->rowtab_cap) {
+                HeadParams *t = nullptr;
+                const hipError_t e = hipMalloc((void **)&t, sizeof(HeadParams) * (size_t)dp.n_entries);
+                if (e != hipSuccess) return fail(ctx, INTATTN_ERR_NOMEM, std::string("hipMalloc of the row-group table: ") + hipGetErrorString(e));
+                if (ctx->d_rowtab) (void)hipFree(ctx->d_rowtab); // waits for work that may still read it
+                ctx->d_rowtab = t;
+                ctx->rowtab_cap = (size_t)dp.n_entries;
+            }
+            dp.row_table = ctx->d_rowtab;
+            const int e = launch_derive_rows(dp, stream);
+            if (e != 0) return hip_fail(ctx, (hipError_t)e, "launch(derive row-group parameters)");
+            p.row_table = ctx->d_rowtab;
+            p.q_block = a->q_block;
+            p.n_rowblk = dp.n_rowblk;
+            p.hp_table = nullptr; // the kernels take every parameter from the row table
+        } else {
+            if (stage != 2) { // stage 2 reads what stage 1 derived
+                const int e = launch_derive(dp, stream);
+                if (e != 0) return hip_fail(ctx, (hipError_t)e, "launch(derive head parameters)");
+            }
+            p.hp_table = ctx->d_hp;
         }
-        p.hp_table = ctx->d_hp;
     } else if (decode) {
         // every head's parameters in the device table, each with the scheme of its index map
         rc = ensure_tables(ctx, a->Hq);
@@ -672,7 +697,11 @@ int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *a, void *hip_st
     if ((int64_t)a->B * a->H > 65535) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "B * H must not exceed 65535");
     if ((int64_t)a->L * (a->d / 8) > 2147483647LL) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "L * d / 8 must fit 31 bits");
     if (a->dtype < 0 || a->dtype > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "dtype must be 0 (fp32), 1 (fp16) or 2 (bf16)");
-    if (a->scale_mode != 0 && a->scale_mode != 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode must be 0 or 1");
+    if (a->scale_mode < 0 || a->scale_mode > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode must be 0, 1 or 2");
+    if (a->scale_mode == 2 && a->q_block < 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode 2 needs q_block >= 1");
+    if (a->reserved != 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "reserved must be 0");
+    if (a->scale_mode == 2 && (int64_t)a->B * a->H * ((a->L + a->q_block - 1) / a->q_block) > 2147483647LL)
+        return fail(ctx, INTATTN_ERR_UNSUPPORTED, "more than 2^31-1 groups");
     if (!a->src || !a->dst || !a->scales) return fail(ctx, INTATTN_ERR_INVALID_ARG, "src, dst, scales must be non-NULL");
     if ((const void *)a->dst == a->src) return fail(ctx, INTATTN_ERR_INVALID_ARG, "dst must not alias src");
     if ((((uintptr_t)a->src) & 15u) || (((uintptr_t)a->dst) & 7u))
@@ -702,6 +731,7 @@ int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *a, void *hip_st
     for (int i = 0; i < 3; ++i) { p.ss[i] = a->src_stride[i]; p.ds[i] = a->dst_stride[i]; }
     p.B = a->B; p.H = a->H; p.L = a->L; p.d = a->d;
     p.dtype = a->dtype; p.per_head = a->scale_mode;
+    p.q_block = a->q_block;
     p.scales = a->scales; p.partial = ctx->d_amax; p.n_partial = n_partial;
     const int herr = launch_quantize(p, hip_stream);
     if (herr != 0) return hip_fail(ctx, (hipError_t)herr, "launch(quantize)");
@@ -784,6 +814,7 @@ void intattn_destroy(intattn_ctx *ctx)
         if (ctx->d_ws) (void)hipFree(ctx->d_ws);
         if (ctx->d_amax) (void)hipFree(ctx->d_amax);
         if (ctx->d_status) (void)hipFree(ctx->d_status);
+        if (ctx->d_rowtab) (void)hipFree(ctx->d_rowtab);
     }
     delete ctx;
 }

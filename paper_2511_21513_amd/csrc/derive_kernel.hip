@@ -23,29 +23,21 @@ __device__ __forceinline__ uint32_t exact_index(uint64_t x, uint64_t c_int, uint
     return (uint32_t)((2 * top * x + c_int) / (2 * c_int));
 }
 
-// One wave per query head; lane l holds one check point x of the index map: x = 0, x = c_int, and
-// both sides of each of the (at most 31) steps of the exact map.  Every map in question is a
-// monotone step function, so agreement at these points is agreement on all of [0, c_int].
-__global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
+// c_int (capped at 2^30: beyond 62 * 2 * 128*128*128 every index is 0 anyway) and the requantization
+// multiplier of one parameter set; false (and harmless values) when a scale is unusable.
+__device__ __forceinline__ bool derive_scalars(float sq, float sk, float sv, float so, double clip, double sqrt_d, HeadParams &hp)
 {
-    const int h = blockIdx.x, lane = threadIdx.x;
-    const int si = dp.per_head ? h : 0;
-    const int kv = dp.per_head ? h / dp.group : 0;
-    const float sq = dp.scale_q[si], sk = dp.scale_k[kv], sv = dp.scale_v[kv];
-    const float so = dp.scale_out ? dp.scale_out[si] : sv;
-    HeadParams hp;
+    hp.pad[0] = IDX_FP64;
     hp.pad[1] = 0;
     bool ok = good_scale(sq) && good_scale(sk) && good_scale(sv) && good_scale(so);
-    // clip threshold, capped at 2^30 (beyond 62 * 2 * 128*128*128 every index is 0 anyway)
     double c = 1.0;
     if (ok) {
-        const double alpha = ((double)sq * (double)sk) / dp.sqrt_d;
-        c = __builtin_floor(dp.clip / alpha + 0.5);
+        const double alpha = ((double)sq * (double)sk) / sqrt_d;
+        c = __builtin_floor(clip / alpha + 0.5);
         if (!(c >= 1.0)) c = 1.0;
         if (c > 1073741824.0) c = 1073741824.0;
     }
     hp.c_int = (int32_t)c;
-    // requantization multiplier
     hp.rq_mult = 1 << 30;
     hp.rq_shift = 31;
     if (ok) {
@@ -64,6 +56,33 @@ __global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
             hp.rq_shift = sh;
         }
     }
+    return ok;
+}
+
+// the fp64 index map's factor for c_int: the bits of -(the double after top / c_int), low word in
+// idx_mul, high word in idx_add
+__device__ __forceinline__ uint64_t set_fp64_factor(HeadParams &hp, uint32_t top)
+{
+    const uint64_t bits = (uint64_t)__double_as_longlong((double)top / (double)(uint32_t)hp.c_int) + 1ull;
+    const uint64_t neg = bits ^ 0x8000000000000000ull;
+    hp.idx_mul = (uint32_t)neg;
+    hp.idx_add = (uint32_t)(neg >> 32);
+    hp.idx_shift = 0;
+    return bits;
+}
+
+// One wave per query head; lane l holds one check point x of the index map: x = 0, x = c_int, and
+// both sides of each of the (at most 31) steps of the exact map.  Every map in question is a
+// monotone step function, so agreement at these points is agreement on all of [0, c_int].
+__global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
+{
+    const int h = blockIdx.x, lane = threadIdx.x;
+    const int si = dp.per_head ? h : 0;
+    const int kv = dp.per_head ? h / dp.group : 0;
+    const float sq = dp.scale_q[si], sk = dp.scale_k[kv], sv = dp.scale_v[kv];
+    const float so = dp.scale_out ? dp.scale_out[si] : sv;
+    HeadParams hp;
+    bool ok = derive_scalars(sq, sk, sv, so, dp.clip, dp.sqrt_d, hp);
 
     // this lane's check point
     const uint32_t c_int = (uint32_t)hp.c_int, top = (uint32_t)dp.top;
@@ -114,7 +133,38 @@ __global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
     }
 }
 
+// Parameters per block of q_block query rows (finer quantization groups over the query rows,
+// Sec. 3.3): one thread per (batch, head, block); scale_q / scale_out hold one value per block,
+// scale_k / scale_v one per KV head.  Every block takes the fp64 index map, which is exact for
+// every c_int without a search.
+__global__ __launch_bounds__(256) void derive_rows_kernel(const DeriveParams dp)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= dp.n_entries) return;
+    const int hq = (int)((e / dp.n_rowblk) % dp.Hq), kv = hq / dp.group;
+    const float sq = dp.scale_q[e], sk = dp.scale_k[kv], sv = dp.scale_v[kv];
+    const float so = dp.scale_out ? dp.scale_out[e] : sv;
+    HeadParams hp;
+    const bool ok = derive_scalars(sq, sk, sv, so, dp.clip, dp.sqrt_d, hp);
+    set_fp64_factor(hp, (uint32_t)dp.top);
+    dp.row_table[e] = hp;
+    if (!ok) dp.status[hq] = 1; // every writer stores the same value
+}
+
+__global__ __launch_bounds__(256) void zero_status_kernel(int32_t *status, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) status[i] = 0;
+}
+
 } // namespace
+
+int launch_derive_rows(const DeriveParams &dp, void *stream)
+{
+    hipLaunchKernelGGL(zero_status_kernel, dim3((unsigned)((dp.Hq + 255) / 256)), dim3(256), 0, (hipStream_t)stream, dp.status, dp.Hq);
+    hipLaunchKernelGGL(derive_rows_kernel, dim3((unsigned)((dp.n_entries + 255) / 256)), dim3(256), 0, (hipStream_t)stream, dp);
+    return (int)hipGetLastError();
+}
 
 int launch_derive(const DeriveParams &dp, void *stream)
 {

@@ -251,9 +251,14 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
 
     // exact index map of each row block's lane row, applied to raw scores (no -rowMax start
     // value in the accumulators, which saves 16 registers per row block)
+    // parameters of the block of query rows that `row` lies in (finer groups over query rows, Sec. 3.3)
+    auto row_hp = [&](int row) __attribute__((always_inline)) {
+        const int lr = (row >= rlo && row < rhi) ? row - rlo : 0;
+        return p.row_table[(int64_t)bh * p.n_rowblk + lr / p.q_block];
+    };
     RowIndex<MODE> ri[RB];
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) ri[rb].init(hp, mx[rb], top);
+    for (int rb = 0; rb < RB; ++rb) ri[rb].init(MODE == IDX_ROW64 ? row_hp(qw0 + 32 * rb + n) : hp, mx[rb], top);
 
     // ================================================================= sweep B: row sum of E_hat
     // transposing read: lanes 2j, 2j+1 of a 16-lane group point at the two 8-byte halves of key
@@ -466,7 +471,8 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
         const int row = qw0 + 32 * rb + n;
         if (row < rlo || row >= rhi) continue;
         int8_t *Op = p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)(row - rlo) * p.os[2];
-        const int64_t half = 1ll << (hp.rq_shift - 1);
+        const HeadParams he = MODE == IDX_ROW64 ? row_hp(row) : hp;
+        const int64_t half = 1ll << (he.rq_shift - 1);
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
 #pragma unroll
@@ -477,7 +483,7 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
                 for (int r = 0; r < 4; ++r) {
                     const int32_t acc = o[rb][cb][4 * g + r] + 128 * colsum[ch0 + r];
                     if (p.dbg_acc) p.dbg_acc[((int64_t)bh * LQ + (row - rlo)) * D + ch0 + r] = acc;
-                    int64_t v = ((int64_t)acc * hp.rq_mult + half) >> hp.rq_shift;
+                    int64_t v = ((int64_t)acc * he.rq_mult + half) >> he.rq_shift;
                     v = v > 127 ? 127 : (v < -127 ? -127 : v);
                     packed |= ((uint32_t)(int)v & 0xffu) << (8 * r);
                 }
@@ -506,6 +512,8 @@ int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
         hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MULHI24, PH>), grid, block, 0, st, p);
     else if (idx_mode == IDX_FP32)
         hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP32, PH>), grid, block, 0, st, p);
+    else if (idx_mode == IDX_ROW64)
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_ROW64, PH>), grid, block, 0, st, p);
     else
         hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP64, PH>), grid, block, 0, st, p);
     return (int)hipGetLastError();

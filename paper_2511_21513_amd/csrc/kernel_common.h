@@ -105,7 +105,7 @@ template <int MODE> struct RowIndex {
     uint32_t addc;
     int mul;
     int shift;
-    double negr; // fp64 scheme only
+    double negr; // fp64 schemes only (per lane when the parameters are per block of rows)
 
     __device__ __forceinline__ void init(const HeadParams &hp, int row_max, uint32_t top_)
     {
@@ -113,7 +113,7 @@ template <int MODE> struct RowIndex {
         bound = row_max - hp.c_int;
         mul = (int)hp.idx_mul;
         shift = hp.idx_shift;
-        negr = MODE == IDX_FP64 ? idx_fp64_factor(hp) : 0.0;
+        negr = (MODE == IDX_FP64 || MODE == IDX_ROW64) ? idx_fp64_factor(hp) : 0.0;
         (void)top_;
         if (MODE == IDX_MULHI24) addc = hp.idx_add - ((uint32_t)row_max << hp.idx_shift);
         else if (MODE == IDX_MAD24) addc = hp.idx_add - (uint32_t)__mul24(row_max, (int)hp.idx_mul);

@@ -13,7 +13,9 @@ enum IdxMode : int32_t {
     IDX_MAD24 = 1,  // (Delta' * mul + add) >> shift, 24-bit operands, 32-bit result
     IDX_MULHI24 = 2,// high 32 bits of the 48-bit product ((Delta' << pre) + add) * mul
     IDX_FP32 = 3,   // trunc(fma(Delta', top/c_int, 0.5)) in IEEE fp32 (idx_mul holds the bits of -top/c_int)
-    IDX_DEVICE = 4  // launchers only: each head's scheme (FP32 or FP64) is in its HeadParams, written on the device
+    IDX_DEVICE = 4, // launchers only: each head's scheme (FP32 or FP64) is in its HeadParams, written on the device
+    IDX_ROW64 = 5   // the fp64 scheme with parameters per block of query rows (FwdParams::row_table): finer
+                    // quantization groups over the query rows, Sec. 3.3
 };
 
 // Per query head: everything the kernel needs that depends on the scales.
@@ -42,6 +44,8 @@ struct FwdParams {
     int32_t n_qtiles;    // tiles of (rows per workgroup) rows that [row_lo, row_lo + L) touches
     int32_t n_chunks;    // ceil(Lk / rows per workgroup of sweep C): chunks of V the column sums are kept for
     const HeadParams *hp_table; // device [Hq] when per-head or derived on the device, else nullptr
+    const HeadParams *row_table; // IDX_ROW64: device [B * Hq][n_rowblk], parameters of every block of q_block query rows
+    int32_t q_block, n_rowblk;
     int32_t filter;             // 1: a workgroup whose head's HeadParams name another scheme than the kernel's returns at once
     HeadParams hp0;             // the single parameter set when hp_table == nullptr
     uint32_t lut[8];            // LUT_hat, 32 bytes packed little-endian (unused tail is 0)
@@ -68,7 +72,8 @@ struct QuantParams {
     int64_t ss[3], ds[3];  // byte strides of B, H, L
     int32_t B, H, L, d;
     int32_t dtype;         // 0 fp32, 1 fp16, 2 bf16
-    int32_t per_head;      // 0: one scale; 1: one per head index
+    int32_t per_head;      // 0: one scale; 1: one per head index; 2: one per block of q_block rows of every (b, h)
+    int32_t q_block;
     float *scales;         // device, 1 or H values (out)
     float *partial;        // device scratch: max|X| of every workgroup of the first pass, [B * H][n_partial]
     int32_t n_partial;
@@ -96,6 +101,10 @@ struct DeriveParams {
     double clip, sqrt_d;
     HeadParams *hp_table;  // device [Hq] (out; all heads also when the scales are per tensor)
     int32_t *status;       // device [Hq] (out): 1 where a head's scales were unusable, else 0
+    // per block of query rows (launch_derive_rows): scale_q / scale_out hold n_entries = B * Hq * n_rowblk values
+    int64_t n_entries;
+    int32_t n_rowblk;
+    HeadParams *row_table; // device [n_entries] (out)
 };
 
 // Launchers implemented in the .hip files.  Return a hipError_t cast to int.
@@ -116,6 +125,7 @@ int launch_quantize(const QuantParams &p, void *stream);
 int launch_decode(const FwdParams &p, int d, void *stream);
 int launch_index_softmax(const SoftmaxParams &p, void *stream);
 int launch_derive(const DeriveParams &dp, void *stream);
+int launch_derive_rows(const DeriveParams &dp, void *stream);
 int launch_quantonly(const FwdParams &p, int d, int variant, void *stream);
 
 } // namespace intattn

@@ -146,9 +146,69 @@ __global__ __launch_bounds__(QNT) void quantize_kernel(const QuantParams p)
     }
 }
 
+// One scale per block of q_block rows of a (b, h) slice (Sec. 3.3; per token at q_block = 1).  A
+// group is small, so one team (a wave, or the workgroup for groups above 4096 elements) takes it
+// whole: max|X| over the group, then the same arithmetic as above; the second read of the group
+// comes from the caches.
+template <int DTYPE, int NTHR>
+__global__ __launch_bounds__(QNT) void quantize_rows_kernel(const QuantParams p)
+{
+    constexpr int ES = DTYPE == 0 ? 4 : 2;
+    __shared__ float wmax[QNT / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t = NTHR == 64 ? lane : tid;
+    const int nblk = (p.L + p.q_block - 1) / p.q_block;
+    const int64_t gi = NTHR == 64 ? (int64_t)blockIdx.x * (QNT / 64) + wave : (int64_t)blockIdx.x;
+    if (gi >= (int64_t)p.B * p.H * nblk) return; // a whole wave of the four-group layout
+    const int blk = (int)(gi % nblk), bh = (int)(gi / nblk), b = bh / p.H, h = bh % p.H;
+    const int r0 = blk * p.q_block, r1 = min(p.L, r0 + p.q_block);
+    const int ipr = p.d / 8, items = (r1 - r0) * ipr;
+    const uint8_t *src = (const uint8_t *)p.src + (int64_t)b * p.ss[0] + (int64_t)h * p.ss[1] + (int64_t)r0 * p.ss[2];
+    int8_t *dst = p.dst + (int64_t)b * p.ds[0] + (int64_t)h * p.ds[1] + (int64_t)r0 * p.ds[2];
+    float m = 0.0f;
+    for (int it = t; it < items; it += NTHR) {
+        const int row = it / ipr, c = it - row * ipr;
+        float x[8];
+        load8<DTYPE>(src + (int64_t)row * p.ss[2] + (int64_t)c * 8 * ES, x);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf(x[i]));
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (NTHR != 64) {
+        if (lane == 0) wmax[wave] = m;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < QNT / 64; ++w) m = fmaxf(m, wmax[w]);
+    }
+    const float s = fmaxf(m, 1e-12f) / 127.0f; // one IEEE fp32 division
+    if (t == 0) p.scales[gi] = s;
+    for (int it = t; it < items; it += NTHR) {
+        const int row = it / ipr, c = it - row * ipr;
+        float x[8];
+        load8<DTYPE>(src + (int64_t)row * p.ss[2] + (int64_t)c * 8 * ES, x);
+        uint32_t w[2] = {0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float r = __builtin_rintf(x[i] / s); // IEEE division; nearest integer, ties to even
+            r = fminf(fmaxf(r, -127.0f), 127.0f);
+            w[i / 4] |= ((uint32_t)(int)r & 0xffu) << (8 * (i % 4));
+        }
+        *(uint2 *)(dst + (int64_t)row * p.ds[2] + (int64_t)c * 8) = make_uint2(w[0], w[1]);
+    }
+}
+
 template <int DTYPE>
 int launch_dtype(const QuantParams &p, hipStream_t st)
 {
+    if (p.per_head == 2) {
+        const int64_t groups = (int64_t)p.B * p.H * ((p.L + p.q_block - 1) / p.q_block);
+        if ((int64_t)p.q_block * p.d <= 4096)
+            hipLaunchKernelGGL((quantize_rows_kernel<DTYPE, 64>), dim3((unsigned)((groups + 3) / 4)), dim3(QNT), 0, st, p);
+        else
+            hipLaunchKernelGGL((quantize_rows_kernel<DTYPE, QNT>), dim3((unsigned)groups), dim3(QNT), 0, st, p);
+        return (int)hipGetLastError();
+    }
     const int64_t items = (int64_t)p.L * (p.d / 8);
     const dim3 grid((unsigned)((items + QNT * QITEMS - 1) / (QNT * QITEMS)), (unsigned)(p.B * p.H)), block(QNT);
     const dim3 rgrid((unsigned)p.n_partial, grid.y); // the reduction pass: each workgroup walks its part of a slice

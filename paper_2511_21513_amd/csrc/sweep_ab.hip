@@ -63,6 +63,11 @@ __global__ __launch_bounds__(NT, RB == 1 ? 3 : 2) void sweep_ab_kernel(const Fwd
     const int L = p.Lk; // keys
     // query rows: [rlo, rhi) of the numbering in which row r sees keys <= r under the causal mask
     const int rlo = p.row_lo, rhi = p.row_lo + p.L, LQ = p.L;
+    // parameters of the block of query rows that `row` lies in (finer groups over query rows, Sec. 3.3)
+    auto row_hp = [&](int row) __attribute__((always_inline)) {
+        const int lr = (row >= rlo && row < rhi) ? row - rlo : 0;
+        return p.row_table[(int64_t)bh * p.n_rowblk + lr / p.q_block];
+    };
     const uint32_t top = (uint32_t)p.top;
 
     const int q0 = qt * BQ, qw0 = q0 + wave * (RB * 32);
@@ -235,7 +240,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 3 : 2) void sweep_ab_kernel(const Fwd
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         mx[rb] = max(mx[rb], __shfl_xor(mx[rb], 32));
-        ri[rb].init(hp, mx[rb], top);
+        ri[rb].init(MODE == IDX_ROW64 ? row_hp(qw0 + 32 * rb + n) : hp, mx[rb], top);
         sum[rb] = 0;
     }
 
@@ -277,6 +282,8 @@ int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
         hipLaunchKernelGGL((sweep_ab_kernel<D, RB, CAUSAL, IDX_MULHI24>), grid, block, 0, st, p);
     else if (idx_mode == IDX_FP32)
         hipLaunchKernelGGL((sweep_ab_kernel<D, RB, CAUSAL, IDX_FP32>), grid, block, 0, st, p);
+    else if (idx_mode == IDX_ROW64)
+        hipLaunchKernelGGL((sweep_ab_kernel<D, RB, CAUSAL, IDX_ROW64>), grid, block, 0, st, p);
     else
         hipLaunchKernelGGL((sweep_ab_kernel<D, RB, CAUSAL, IDX_FP64>), grid, block, 0, st, p);
     return (int)hipGetLastError();

@@ -79,6 +79,11 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     const int L = p.Lk; // keys
     // query rows: [rlo, rhi) of the numbering in which row r sees keys <= r under the causal mask
     const int rlo = p.row_lo, rhi = p.row_lo + p.L, LQ = p.L;
+    // parameters of the block of query rows that `row` lies in (finer groups over query rows, Sec. 3.3)
+    auto row_hp = [&](int row) __attribute__((always_inline)) {
+        const int lr = (row >= rlo && row < rhi) ? row - rlo : 0;
+        return p.row_table[(int64_t)bh * p.n_rowblk + lr / p.q_block];
+    };
     const uint32_t top = (uint32_t)p.top;
 
     const int q0 = qt * BQ, qw0 = q0 + wave * (RB * 32);
@@ -154,7 +159,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
         const int mx = (row >= rlo && row < rhi) ? p.ws_row_max[(int64_t)bh * LQ + (row - rlo)] : 0;
         sum[rb] = (row >= rlo && row < rhi) ? (uint32_t)p.ws_row_sum[(int64_t)bh * LQ + (row - rlo)] : 0u;
         if (sum[rb] == 0) sum[rb] = 1; // only rows outside [rlo, rhi); never stored
-        ri[rb].init(hp, mx, top);
+        ri[rb].init(MODE == IDX_ROW64 ? row_hp(row) : hp, mx, top);
         if (p.dbg_row_max && h == 0 && row >= rlo && row < rhi) p.dbg_row_max[(int64_t)bh * LQ + (row - rlo)] = mx;
         if (p.dbg_row_sum && h == 0 && row >= rlo && row < rhi) p.dbg_row_sum[(int64_t)bh * LQ + (row - rlo)] = (int32_t)sum[rb];
     }
@@ -352,7 +357,8 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
         const int row = qw0 + 32 * rb + n;
         if (row < rlo || row >= rhi) continue;
         int8_t *Op = p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)(row - rlo) * p.os[2];
-        const int64_t half = 1ll << (hp.rq_shift - 1);
+        const HeadParams he = MODE == IDX_ROW64 ? row_hp(row) : hp;
+        const int64_t half = 1ll << (he.rq_shift - 1);
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
 #pragma unroll
@@ -363,7 +369,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
                 for (int r = 0; r < 4; ++r) {
                     const int32_t acc = o[rb][cb][4 * g + r] + 128 * colsum[ch0 + r];
                     if (p.dbg_acc) p.dbg_acc[((int64_t)bh * LQ + (row - rlo)) * D + ch0 + r] = acc;
-                    int64_t v = ((int64_t)acc * hp.rq_mult + half) >> hp.rq_shift;
+                    int64_t v = ((int64_t)acc * he.rq_mult + half) >> he.rq_shift;
                     v = v > 127 ? 127 : (v < -127 ? -127 : v);
                     packed |= ((uint32_t)(int)v & 0xffu) << (8 * r);
                 }
@@ -392,6 +398,8 @@ int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
         hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_MULHI24>), grid, block, 0, st, p);
     else if (idx_mode == IDX_FP32)
         hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_FP32>), grid, block, 0, st, p);
+    else if (idx_mode == IDX_ROW64)
+        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_ROW64>), grid, block, 0, st, p);
     else
         hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_FP64>), grid, block, 0, st, p);
     return (int)hipGetLastError();

@@ -587,3 +587,20 @@ def test_row_groups_reduce_to_per_head_and_follow_each_groups_scale(oracle):
         assert r["row_max"][bb, h, i] == m and r["row_sum"][bb, h, i] == s
         assert list(r["acc"][bb, h, i]) == acc and list(r["out"][bb, h, i]) == out
     assert (r["row_sum"] != b["row_sum"]).any()  # the group scales do change the result
+
+
+def test_row_group_quantizer_is_the_per_tensor_quantizer_per_block(oracle):
+    rng = np.random.default_rng(9)
+    x = (rng.standard_normal((2, 2, 11, 8)) * rng.uniform(0.1, 9.0, size=(2, 2, 11, 1))).astype(np.float32)
+    xq, sc = oracle.quantize_row_groups(x, 1)
+    assert sc.shape == (2, 2, 11)
+    amax = np.abs(x).max(axis=-1)
+    np.testing.assert_array_equal(sc, (amax / np.float32(127.0)).astype(np.float32))
+    assert (np.abs(xq).max(axis=-1) == 127).all()  # every token's largest element maps to +-127
+    xq4, sc4 = oracle.quantize_row_groups(x, 4)
+    assert sc4.shape == (2, 2, 3)
+    np.testing.assert_array_equal(sc4[:, :, 2], (np.abs(x[:, :, 8:]).max(axis=(-1, -2)) / np.float32(127.0)).astype(np.float32))
+    whole, s1 = oracle.quantize_row_groups(x[:1, :1], 11)
+    ref, s0 = oracle.quantize(x[:1, :1])
+    np.testing.assert_array_equal(whole, ref)
+    assert s1[0, 0, 0] == s0[0]

@@ -686,3 +686,97 @@ def test_other_lut_bits_and_clip(torch_mod, oracle, bc):
     torch.cuda.synchronize()
     assert int((gp.cpu().numpy() != wp).sum()) == 0
     ia.close()
+
+
+# ---------------------------------------------------------------- finer quantization groups over query rows
+
+ROW_GROUP_SHAPES = [
+    # B, Hq, Hkv, Lq, Lkv, d, causal, q_block, with an output scale per group
+    (1, 2, 1, 37, 37, 64, True, 1, False),       # per token
+    (2, 4, 2, 150, 150, 128, True, 1, True),
+    (1, 4, 4, 300, 300, 64, False, 7, True),     # blocks that straddle waves and tiles
+    (1, 2, 2, 260, 260, 128, True, 64, False),
+    (2, 2, 1, 40, 333, 64, True, 16, True),      # a chunk of queries against a longer key sequence
+]
+
+
+@pytest.mark.parametrize("shape", ROW_GROUP_SHAPES, ids=lambda s: "B{}Hq{}Hkv{}Lq{}Lk{}d{}c{}qb{}so{}".format(*[int(x) for x in s]))
+def test_row_group_scales_bit_exact(torch_mod, ia, oracle, shape):
+    """Scale mode 2 (Sec. 3.3, groups = blocks of query rows, per token at q_block = 1): every row
+    follows its group's c_int and requantization; all kernel variants, device-resident scales."""
+    torch = torch_mod
+    B, Hq, Hkv, lq, lk, d, causal, qb, with_so = shape
+    print(f"case {shape}", flush=True)
+    base, q, k, v = rect_problem(700 + lq + qb, B, Hq, Hkv, lq, lk, d, causal, per_head=True)
+    rng = np.random.default_rng(qb + lq)
+    nblk = (lq + qb - 1) // qb
+    s_q = (base.s_q[None, :, None] * rng.uniform(0.3, 2.5, size=(B, Hq, nblk))).astype(np.float32)
+    s_q[0, 0, 0] *= np.float32(1e-3)  # one group far beyond the reach of the 24-bit and fp32 index maps
+    s_o = (base.s_v[np.arange(Hq) // (Hq // Hkv)][None, :, None] * rng.uniform(0.02, 0.2, size=(B, Hq, nblk))).astype(np.float32) if with_so else None
+    want = oracle.forward_row_groups(q, k, v, s_q, base.s_k, base.s_v, s_o, q_block=qb, causal=causal, taps=True)
+    dev = torch.device("cuda:0")
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+    sc = [torch.from_numpy(np.ascontiguousarray(x)).to(dev) if x is not None else None for x in (s_q, base.s_k, base.s_v, s_o)]
+    out = torch.empty_like(tq)
+    taps = {"row_max": torch.zeros((B, Hq, lq), dtype=torch.int32, device=dev),
+            "row_sum": torch.zeros((B, Hq, lq), dtype=torch.int32, device=dev),
+            "acc": torch.zeros((B, Hq, lq, d), dtype=torch.int32, device=dev)}
+    args, keep = ia.make_args(tq, tk, tv, out, *sc, causal=causal, device_scales=True, q_block=qb, **taps)
+    ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
+    torch.cuda.synchronize()
+    assert ia.dynamic_status() == 0
+    for key in ("row_max", "row_sum", "acc"):
+        assert int((taps[key].cpu().numpy() != want[key]).sum()) == 0, key
+    assert int((out.cpu().numpy() != want["out"]).sum()) == 0
+
+
+@pytest.mark.parametrize("case", [(2, 3, 50, 64, "float16", 1), (1, 2, 77, 128, "float32", 5), (1, 4, 300, 128, "bfloat16", 64),
+                                  (2, 2, 33, 8, "float32", 1), (1, 1, 100, 64, "float16", 1000)],
+                         ids=lambda c: "B{}H{}L{}d{}{}qb{}".format(*c))
+def test_row_group_quantizer_bit_exact(torch_mod, oracle, case):
+    """Eq. quant with one scale per block of rows (per token at q_block = 1): bytes and scales equal
+    the per-tensor oracle quantizer applied to each block; a wave or a workgroup per group."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    B, H, L, d, dt, qb = case
+    rng = np.random.default_rng(L + d + qb)
+    x = (rng.standard_normal((B, H, L, d)) * rng.uniform(0.1, 10.0, size=(B, H, L, 1))).astype(np.float32)
+    x[0, 0, 0] = 0.0  # an all-zero token
+    tx = torch.from_numpy(x).to("cuda:0").to(getattr(torch, dt))
+    ia = binding.IntAttn(device=0)
+    got, sc = ia.quantize(tx, q_block=qb)
+    torch.cuda.synchronize()
+    want, wsc = oracle.quantize_row_groups(tx.float().cpu().numpy(), qb)
+    assert sc.shape == wsc.shape
+    assert int((sc.cpu().numpy() != wsc).sum()) == 0
+    assert int((got.cpu().numpy() != want).sum()) == 0
+    ia.close()
+
+
+def test_per_token_quantizer_feeds_the_row_group_forward(torch_mod, oracle):
+    """fp16 Q quantized per token on the GPU, K and V per head, then the forward on those
+    device-resident scales: the bytes of the oracle quantizers followed by the row-group oracle."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    rng = np.random.default_rng(83)
+    B, Hq, Hkv, L, d = 2, 4, 2, 200, 128
+    dev = torch.device("cuda:0")
+    qf = torch.from_numpy((rng.standard_normal((B, Hq, L, d)) * rng.uniform(0.2, 5.0, size=(B, Hq, L, 1))).astype(np.float32)).to(dev).half()
+    kf = torch.from_numpy(rng.standard_normal((B, Hkv, L, d)).astype(np.float32)).to(dev).half()
+    vf = torch.from_numpy(rng.standard_normal((B, Hkv, L, d)).astype(np.float32)).to(dev).half()
+    ia = binding.IntAttn(device=0)
+    q, sq = ia.quantize(qf, q_block=1)
+    (k, sk), (v, sv) = (ia.quantize(t, per_head=True) for t in (kf, vf))
+    out = torch.empty_like(q)
+    args, keep = ia.make_args(q, k, v, out, sq, sk, sv, None, causal=True, device_scales=True, q_block=1)
+    ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
+    torch.cuda.synchronize()
+    assert ia.dynamic_status() == 0
+    oq, osq = oracle.quantize_row_groups(qf.float().cpu().numpy(), 1)
+    ok, osk = oracle.quantize(kf.float().cpu().numpy(), per_head=True)
+    ov, osv = oracle.quantize(vf.float().cpu().numpy(), per_head=True)
+    want = oracle.forward_row_groups(oq, ok, ov, osq, osk, osv, None, q_block=1, causal=True)["out"]
+    assert int((out.cpu().numpy() != want).sum()) == 0
+    ia.close()

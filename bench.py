@@ -9,6 +9,11 @@ with grouped-query attention, B=1, 32 query heads over 8 KV heads, L=8192, d=128
 Prints ONE JSON line.  `value` is int8 attention TOPS counting the two contractions only
 (4*d*pairs*B*Hq operations, pairs = L(L+1)/2 under the causal mask); recomputation sweeps and
 masked halves of diagonal tiles are executed but not counted.
+
+Other modes, each with its own JSON line against the HBM roofline: --quantizer (Eq. quant on fp16
+Q, K, V, and the chains quantizer -> attention on device-resident scales), --decode (one token
+per sequence through the split-key kernels), --softmax (IndexSoftmax as an operator on INT32
+logits).  --workload / --batch select another configuration for the default mode.
 """
 import argparse
 import json

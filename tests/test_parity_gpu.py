@@ -780,3 +780,72 @@ def test_per_token_quantizer_feeds_the_row_group_forward(torch_mod, oracle):
     want = oracle.forward_row_groups(oq, ok, ov, osq, osk, osv, None, q_block=1, causal=True)["out"]
     assert int((out.cpu().numpy() != want).sum()) == 0
     ia.close()
+
+
+# ---------------------------------------------------------------- seeded random sweep over shapes, modes and variants
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        g = int(rng.choice([1, 1, 2, 4, 8]))
+        Hkv = int(rng.integers(1, 4))
+        causal = bool(rng.integers(0, 2))
+        lk = int(rng.choice([1, 2, 31, 33, 64, 127, 129, 200, 257, 400, 1100]))
+        lq = int(rng.integers(1, lk + 1)) if causal else int(rng.choice([1, 3, 32, 65, 130, 300]))
+        if rng.integers(0, 3) == 0:
+            lq = lk
+        cases.append((int(rng.integers(1, 3)), g * Hkv, Hkv, lq, lk, int(rng.choice([64, 128])), causal,
+                      int(rng.integers(0, 3)),           # scale mode: per tensor, per head, per block of rows
+                      int(rng.choice([1, 3, 32, 50])),   # q_block (mode 2)
+                      int(rng.integers(0, 10)),          # kernel variant
+                      bool(rng.integers(0, 2)),          # with an output scale
+                      float(rng.choice([1.0, 1.0, 0.05, 1e-3]))))  # multiplier on s_q: moves c_int between the schemes
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(48, 2024), ids=lambda c: "B{}Hq{}Hkv{}Lq{}Lk{}d{}c{}m{}qb{}v{}so{}x{}".format(*[int(x) if not isinstance(x, float) else x for x in c]))
+def test_random_shapes_modes_variants(torch_mod, oracle, case):
+    """A seeded sweep over shapes (square, rectangular, single rows), masks, GQA ratios, scale modes,
+    kernel variants and thresholds: host scales through intattn_forward where the mode has them,
+    device scales through intattn_forward_dynamic, both against the oracle."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    B, Hq, Hkv, lq, lk, d, causal, mode, qb, variant, with_so, mul = case
+    print(f"case {case}", flush=True)
+    base, q, k, v = rect_problem(900 + lq + lk + Hq, B, Hq, Hkv, lq, lk, d, causal, per_head=(mode != 0))
+    rng = np.random.default_rng(lq * 7 + lk)
+    grp = np.arange(Hq) // (Hq // Hkv)
+    dev = torch.device("cuda:0")
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+    ia = binding.IntAttn(device=0, variant=variant)
+    up = lambda x: None if x is None else torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(dev)
+    if mode == 2:
+        nblk = (lq + qb - 1) // qb
+        s_q = (base.s_q[None, :, None] * mul * rng.uniform(0.5, 2.0, size=(B, Hq, nblk))).astype(np.float32)
+        s_o = (base.s_v[grp][None, :, None] * rng.uniform(0.02, 0.3, size=(B, Hq, nblk))).astype(np.float32) if with_so else None
+        want = oracle.forward_row_groups(q, k, v, s_q, base.s_k, base.s_v, s_o, q_block=qb, causal=causal)["out"]
+        out = torch.empty_like(tq)
+        args, keep = ia.make_args(tq, tk, tv, out, up(s_q), up(base.s_k), up(base.s_v), up(s_o), causal=causal,
+                                  device_scales=True, q_block=qb)
+        ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
+        torch.cuda.synchronize()
+        assert ia.dynamic_status() == 0 and int((out.cpu().numpy() != want).sum()) == 0
+    else:
+        per_head = mode == 1
+        s_q = (base.s_q * mul).astype(np.float32)
+        s_o = None
+        if with_so:
+            s_o = (base.s_v[grp] * 0.1).astype(np.float32) if per_head else (base.s_v * 0.1).astype(np.float32)
+        want = oracle.forward(q, k, v, s_q, base.s_k, base.s_v, s_o, causal=causal, per_head=per_head)["out"]
+        got = ia.forward(tq, tk, tv, s_q, base.s_k, base.s_v, s_o, causal=causal, per_head=per_head)
+        torch.cuda.synchronize()
+        assert int((got.cpu().numpy() != want).sum()) == 0, "host scales"
+        out = torch.empty_like(tq)
+        args, keep = ia.make_args(tq, tk, tv, out, up(s_q), up(base.s_k), up(base.s_v), up(s_o), causal=causal,
+                                  per_head=per_head, device_scales=True)
+        ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
+        torch.cuda.synchronize()
+        assert ia.dynamic_status() == 0 and int((out.cpu().numpy() != want).sum()) == 0, "device scales"
+    ia.close()

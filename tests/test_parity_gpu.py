@@ -849,3 +849,29 @@ def test_random_shapes_modes_variants(torch_mod, oracle, case):
         torch.cuda.synchronize()
         assert ia.dynamic_status() == 0 and int((out.cpu().numpy() != want).sum()) == 0, "device scales"
     ia.close()
+
+
+def test_parameter_cache_follows_the_scales(torch_mod, oracle):
+    """The context keeps the parameters derived from the last call's host scales; a call with other
+    scales (any one value, the output scale appearing or disappearing, the scale mode) must not
+    see them."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    p = inputs.random_problem(123, 1, 4, 2, 140, 64, True, per_head=True, spread=1.5)
+    dev = torch.device("cuda:0")
+    q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
+    ia = binding.IntAttn(device=0)
+    s_o = inputs.calibrated_out_scale(p)
+    sq2 = p.s_q.copy()
+    sq2[3] *= np.float32(1.0000001) if sq2[3] * np.float32(1.0000001) != sq2[3] else np.float32(1.001)
+    runs = [(p.s_q, None, True), (p.s_q, None, True), (sq2, None, True), (p.s_q, s_o, True), (p.s_q, None, True),
+            (p.s_q[:1], None, False), (p.s_q, None, True)]
+    for s_q, so, per_head in runs:
+        sk, sv = (p.s_k, p.s_v) if per_head else (p.s_k[:1], p.s_v[:1])
+        so_ = so if per_head or so is None else so[:1]
+        got = ia.forward(q, k, v, s_q, sk, sv, so_, causal=True, per_head=per_head)
+        torch.cuda.synchronize()
+        want = oracle.forward(p.q, p.k, p.v, s_q, sk, sv, so_, causal=True, per_head=per_head)["out"]
+        assert int((got.cpu().numpy() != want).sum()) == 0
+    ia.close()

@@ -86,6 +86,14 @@ int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, 
     if (stage != 0 && !two_launches) return (int)hipErrorNotSupported;
     // all launches go to the same stream: V chunk sums first, then the sweeps
     int e = 0;
+    if (!two_launches && p.Lk <= 512) {
+        // short key sequences: the single-launch kernels sum V themselves (one launch less)
+        FwdParams ps = p;
+        ps.ws_colsum = nullptr;
+        if (variant == 2) return launch_shape<2, 2, 0>(ps, d, idx_mode, st);
+        if (variant == 3) return launch_shape<1, 1, 0>(ps, d, idx_mode, st);
+        return launch_shape<1, 2, 0>(ps, d, idx_mode, st);
+    }
     if (stage != 2) e = launch_colsum(p, d, fwd_rows_per_block(variant), st);
     if (e != 0) return e;
     if (variant == 2) return launch_shape<2, 2, 0>(p, d, idx_mode, st);

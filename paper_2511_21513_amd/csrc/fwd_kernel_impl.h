@@ -75,6 +75,7 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     __shared__ uint32_t PT[WAVES][RB][32 * 32]; // [idx][row] per wave and row block
     __shared__ uint32_t lut_lds[8];
     __shared__ int32_t colsum[D];
+    __shared__ int32_t cs4[PH == 0 ? WAVES : 1][D]; // in-kernel column sums of V (short sequences, single launch)
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 31, h = lane >> 5;
     const WorkItem wi = fwd_work_item(p, (int)blockIdx.x);
@@ -354,13 +355,38 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     // tile under the causal mask, else all): the correction for feeding the probabilities to the
     // signed MFMA as P - 128.  A small kernel ahead of this one left the sums of each BQ-key chunk
     // per (batch, KV head); visible to all waves after sweep C's barriers.
-    if (tid < D) {
-        const int32_t *cp = p.ws_colsum + (int64_t)(b * p.Hkv + kvh) * p.n_chunks * D + tid;
-        const int nchunk = CAUSAL ? min(qt + 1, p.n_chunks) : p.n_chunks;
-        int32_t acc = 0;
+    if (PH != 0 || p.ws_colsum) {
+        if (tid < D) {
+            const int32_t *cp = p.ws_colsum + (int64_t)(b * p.Hkv + kvh) * p.n_chunks * D + tid;
+            const int nchunk = CAUSAL ? min(qt + 1, p.n_chunks) : p.n_chunks;
+            int32_t acc = 0;
 #pragma unroll 8
-        for (int c = 0; c < nchunk; ++c) acc += cp[(int64_t)c * D];
-        colsum[tid] = acc;
+            for (int c = 0; c < nchunk; ++c) acc += cp[(int64_t)c * D];
+            colsum[tid] = acc;
+        }
+    } else {
+        // Short key sequences: the launch of the small kernel costs more than summing V over the
+        // keys [0, kmax) here (thread = 16 channels of every KL-th key row, then the key lanes of
+        // a wave by lane exchange, then the four waves through LDS).
+        constexpr int G = D / 16, KL = NT / G;
+        const int c16 = tid % G, kl = tid / G;
+        int32_t a16[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) a16[i] = 0;
+        for (int key = kl; key < kmax; key += KL) {
+            const v4i x = *(const v4i *)(Vp + (int64_t)key * p.vs[2] + c16 * 16);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) a16[i] += (int32_t)(int8_t)((uint32_t)x[i / 4] >> (8 * (i % 4)));
+        }
+#pragma unroll
+        for (int o = G; o < 64; o <<= 1)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) a16[i] += __shfl_xor(a16[i], o);
+        if (lane < G)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) cs4[wave][c16 * 16 + i] = a16[i];
+        __syncthreads();
+        if (tid < D) colsum[tid] = cs4[0][tid] + cs4[1][tid] + cs4[2][tid] + cs4[3][tid];
     }
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {

@@ -20,15 +20,22 @@
  * r = s_V / (255 s_O) = m * 2^e, m in [0.5, 1), M = round(m * 2^31), sh = 31 - e,
  * out = clamp(floor((acc * M + 2^(sh-1)) / 2^sh), -127, 127).  The paper states no
  * requantization formula; this one follows from Eq. pv-link with P = P_hat / 255.
- * With causal != 0, key j is visible to query i iff j <= i; hidden keys take no part in
- * rowMax / rowSum and get P_hat = 0.  Query head h reads KV head h / (Hq / Hkv).
- * Per-head scales are the group-wise form of Sec. 3.3 with one group per head.
+ * With causal != 0, key j is visible to query i iff j <= i (j <= i + Lkv - L when the
+ * key sequence is longer than the query block); hidden keys take no part in rowMax /
+ * rowSum and get P_hat = 0.  Query head h reads KV head h / (Hq / Hkv).
+ * Per-head scales are the group-wise form of Sec. 3.3 with one group per head; scale
+ * mode 2 has one group per block of query rows (per token at block size 1).
+ *
+ * Around that path: intattn_quantize (Sec. 2.1, Eq. quant, scales left in device memory),
+ * intattn_forward_dynamic (the forward on such device-resident scales) and
+ * intattn_index_softmax (Sec. 3.1-3.2 alone, on INT32 logits).
  *
  * The L x L score matrix never reaches HBM.  Results are a deterministic integer
  * function of the inputs (no dependence on tiling or launch shape).
  *
  * All entry points return 0 on success or a negative INTATTN_ERR_* code; none throws,
- * aborts or synchronizes the stream.  A context is bound to one device and is not
+ * aborts or synchronizes the stream (intattn_dynamic_status, which reads a word back, aside).
+ * A context is bound to one device and is not
  * thread-safe; calls that share a context must be issued on one stream at a time.
  */
 #ifndef INTATTN_H

@@ -77,7 +77,8 @@ def quantizer_bench(a, name, dev):
     import torch
 
     import oracle
-    from paper_2511_21513_amd import binding, inputs
+    import workloads as inputs
+    from paper_2511_21513_amd import binding
 
     B, Hq, Hkv, L, d = inputs.CONFIGS[name][:5]
     g = torch.Generator(device=dev).manual_seed(0)
@@ -173,7 +174,8 @@ def softmax_bench(a, name, dev):
     import torch
 
     import oracle
-    from paper_2511_21513_amd import binding, inputs
+    import workloads as inputs
+    from paper_2511_21513_amd import binding
 
     L = inputs.CONFIGS[name][3]
     rows, cols = a.softmax_heads * L, L
@@ -221,7 +223,8 @@ def decode_bench(a, name, dev):
     import torch
 
     import oracle
-    from paper_2511_21513_amd import binding, inputs
+    import workloads as inputs
+    from paper_2511_21513_amd import binding
 
     _, Hq, Hkv, Lk, d = inputs.CONFIGS[name][:5]
     B = a.decode_batch
@@ -320,7 +323,8 @@ def main():
         print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 3}))
         return
 
-    from paper_2511_21513_amd import binding, inputs
+    import workloads as inputs
+    from paper_2511_21513_amd import binding
 
     name = ALIASES.get(a.workload, a.workload)
     dev = torch.device("cuda:0")

@@ -6,7 +6,7 @@ import functools
 import numpy as np
 import pytest
 
-from paper_2511_21513_amd import inputs
+import workloads as inputs
 
 pytestmark = pytest.mark.gpu
 

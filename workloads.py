@@ -1,11 +1,13 @@
 """Seeded synthetic inputs for the five benchmark configurations.
 
-This module holds no arithmetic of the attention method itself: it draws
-floating-point Q, K, V with the stated distributions and quantizes them with
-the paper's symmetric INT8 quantizer (Sec. 2.1, Eq. quant:
-``s_X = max|X| / 127``, ``X_hat = clamp(round(X / s_X), -127, 127)``), which is
-the step *before* the attention path.  Both the tests of the CPU oracle and the
-callers of the HIP library draw their inputs from here; it imports neither.
+Harness code, not part of the library package: tests, ``bench.py`` and the smoke run
+import it; the package imports nothing from it.  It holds no arithmetic of the attention
+path: it draws floating-point Q, K, V with the stated distributions and turns them into
+the INT8 tensors the path starts from with the workload recipe (``s_X = max|X| / 127``,
+``numpy.rint``, clamp to [-127, 127] -- the same operation as Sec. 2.1, Eq. quant, written
+with numpy; a CPU test checks this recipe against the pinned oracle quantizer, never the
+other way round).  The quantizer tests of the oracle and of the HIP library draw their own
+floating-point tensors and do not come here.  It imports neither the oracle nor the library.
 
 The shapes stand in for the paper's language models (causal, long L) and vision
 transformers (non-causal, L = 197) by shape only.

@@ -33,10 +33,14 @@
  * The L x L score matrix never reaches HBM.  Results are a deterministic integer
  * function of the inputs (no dependence on tiling or launch shape).
  *
- * All entry points return 0 on success or a negative INTATTN_ERR_* code; none throws,
- * aborts or synchronizes the stream (intattn_dynamic_status, which reads a word back, aside).
- * A context is bound to one device and is not
- * thread-safe; calls that share a context must be issued on one stream at a time.
+ * All entry points return 0 on success or a negative INTATTN_ERR_* code; none throws or aborts.
+ * A forward call enqueues its kernels and returns; it allocates device memory (hipMalloc / hipFree,
+ * which wait for the device) only when the problem needs a larger workspace or table than any call
+ * before it on this context did -- intattn_reserve does that ahead of time.  Small per-head tables reach the device through pinned
+ * staging buffers of the context (two of them; a third upload while two are still in flight waits
+ * for the oldest).  intattn_dynamic_status reads a word back and so waits for its copy.
+ * A context is bound to one device and is not thread-safe; calls that share a context must be
+ * issued on one stream at a time.
  */
 #ifndef INTATTN_H
 #define INTATTN_H
@@ -62,9 +66,11 @@ typedef struct {
                          (parameter derivation and LUT only; forward calls are rejected)     */
     int32_t lut_bits; /* b of Sec. 3.1: the table has 2^b entries; 1..5; paper default 5     */
     double clip;      /* c of Sec. 3.1: clip threshold in logit units; > 0; paper default 6.6 */
-    int32_t variant;  /* kernel variant: 0 = automatic choice; 1..9 = tuning knobs (launch split, rows per
-                         wave, tile size, instruction schedule; 9 = the split-key kernels for few query
-                         rows wherever the shape allows), all bit-identical; others are rejected       */
+    int32_t variant;  /* kernel variant: 0 = automatic choice.  Tuning knobs, all bit-identical: 1, 2 = one
+                         launch with 32 / 64 query rows per wave; 4, 5 = two launches (row max and row
+                         sum, then P.V) with the phase-ordered / the software-pipelined second kernel;
+                         9 = the split-key kernels for few query rows wherever the shape allows.
+                         Other values are rejected                                                    */
     int32_t reserved; /* must be 0                                                           */
 } intattn_config;
 
@@ -113,13 +119,21 @@ INTATTN_API int intattn_create(intattn_ctx **out, const intattn_config *cfg);
 /* Enqueues the fused IntAttention forward (Sec. 3) on hip_stream (a hipStream_t; NULL is
  * the default stream) and returns without waiting for it.  The context owns a device workspace
  * (8 bytes per query row plus d int32 per 128 keys and KV head) that the first call allocates and
- * a later, larger call re-allocates (hipMalloc / hipFree: not for use under graph capture); the
+ * a later, larger call re-allocates (hipMalloc / hipFree wait for the device and are not for use
+ * under graph capture: call intattn_reserve first); the
  * kernels of a call pass intermediate results through it, so calls on ONE context must not
  * overlap in time (same stream, or ordered by the caller); use one context per concurrent stream. */
 INTATTN_API int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
 
-/* The same forward cut at the point where the row maxima and row sums of IndexSoftmax
- * (Sec. 3.1-3.2) are complete, for timing its kernels separately.  stage 0: everything, as
+/* Pre-sizes the context's device memory (workspace, per-head tables) for a problem of the shape and
+ * scale mode of `args`, so that later forward calls with problems no larger allocate nothing and
+ * never wait for the device.  dynamic != 0: for intattn_forward_dynamic (scale pointers are not read
+ * either way).  May call hipMalloc / hipFree; launches nothing. */
+INTATTN_API int intattn_reserve(intattn_ctx *ctx, const intattn_args *args, int32_t dynamic);
+
+/* Timing hook for benchmarks, not part of the serving interface: the forward cut at the point where
+ * the row maxima and row sums of IndexSoftmax (Sec. 3.1-3.2) are complete, so that the two launches of
+ * the tiled path can be timed separately.  stage 0: everything, as
  * intattn_forward.  stage 1: V column sums and sweeps A+B only (row max, row sum of E_hat go to
  * the context's workspace; args->out is not written).  stage 2: sweep C only (P_hat, P_hat.V_hat,
  * requantization), reading what the last stage-1 call on this context left: it must have had the
@@ -136,9 +150,8 @@ INTATTN_API int intattn_forward_stage(intattn_ctx *ctx, const intattn_args *args
  * path's arithmetic, so the output is bit-identical to intattn_forward with the same scale
  * values, and the host never reads the scales: quantizer and attention can be enqueued back to
  * back.  Scales that are not finite and > 0 (or a ratio s_V / (255 s_O) outside the multiplier's
- * range) cannot be reported by return code: the affected heads' output is then unspecified (no
- * fault), and intattn_dynamic_status reports it.  Same workspace and no-overlap rules as
- * intattn_forward. */
+ * range) cannot be reported by return code: the affected heads' output is then all zeros, and
+ * intattn_dynamic_status reports it.  Same workspace and no-overlap rules as intattn_forward. */
 INTATTN_API int intattn_forward_dynamic(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
 
 /* *status (HOST) = 1 if the last intattn_forward_dynamic on this context met an unusable scale,
@@ -218,7 +231,8 @@ INTATTN_API int intattn_derive_params(const intattn_ctx *ctx, float s_q, float s
  *   mode 0: idx = trunc(fma(x, r, 0.5)) in IEEE fp64, *mul / *add = low / high word of the bits of r
  *   mode 1: idx = (x * mul + add) >> shift                 (32-bit sum, 24-bit factors)
  *   mode 2: idx = (((x << shift) + add) * mul) >> 32       (48-bit product of 24-bit factors)
- *   mode 3: idx = trunc(fma(x, r, 0.5)) in IEEE fp32, *mul = the bits of r; add = shift = 0 */
+ *   mode 3: idx = trunc(fma(x, r, 0.5)) in IEEE fp32, *mul = the bits of r; add = shift = 0
+ *   mode 6: mode 1 with shift = 24: the index is the top byte of x * mul + add */
 INTATTN_API int intattn_derive_index_map(const intattn_ctx *ctx, int64_t c_int, int32_t *mode, uint32_t *mul,
                                          uint32_t *add, int32_t *shift);
 

@@ -20,6 +20,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = 0, -1, -2, -3, -4
 SYMBOLS = (
     "intattn_create",
     "intattn_forward",
+    "intattn_reserve",
     "intattn_forward_stage",
     "intattn_forward_dynamic",
     "intattn_dynamic_status",
@@ -103,6 +104,8 @@ def load() -> ctypes.CDLL:
         lib.intattn_create.restype = i32
         lib.intattn_forward.argtypes = [vp, ctypes.POINTER(Args), vp]
         lib.intattn_forward.restype = i32
+        lib.intattn_reserve.argtypes = [vp, ctypes.POINTER(Args), i32]
+        lib.intattn_reserve.restype = i32
         lib.intattn_forward_stage.argtypes = [vp, ctypes.POINTER(Args), vp, i32]
         lib.intattn_forward_stage.restype = i32
         lib.intattn_forward_dynamic.argtypes = [vp, ctypes.POINTER(Args), vp]
@@ -251,6 +254,12 @@ class IntAttn:
     def forward_args(self, args: Args, stream: int = 0, quantonly: bool = False):
         fn = self._lib.intattn_forward_quantonly if quantonly else self._lib.intattn_forward
         rc = fn(self._ctx, ctypes.byref(args), ctypes.c_void_p(stream))
+        if rc != OK:
+            raise IntAttnError(rc, self.last_error())
+
+    def reserve(self, args: Args, dynamic: bool = False):
+        """intattn_reserve: pre-size the context's device memory for problems up to this one."""
+        rc = self._lib.intattn_reserve(self._ctx, ctypes.byref(args), int(bool(dynamic)))
         if rc != OK:
             raise IntAttnError(rc, self.last_error())
 

@@ -2,11 +2,12 @@
 // integer parameters from the scales (Eq. logit-scale, Eq. clipping_thr), LUT_hat
 // (Eq. lut_re, Eq. lut16), and kernel launches.  No CPU fallback exists: if a launch
 // fails, the error is returned.
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -15,6 +16,15 @@
 #include "params.h"
 
 using namespace intattn;
+
+// Pinned host staging for small host-to-device uploads (per-head tables): the bytes are copied here
+// first, so the asynchronous copy never reads memory that the caller, or a returning function, owns.
+struct Staging {
+    unsigned char *host = nullptr;
+    hipEvent_t done = nullptr;
+    bool pending = false;
+};
+constexpr size_t STAGING_BYTES = 65536;
 
 struct intattn_ctx {
     int device = 0;
@@ -43,6 +53,8 @@ struct intattn_ctx {
     int dv_mode = 0;
     std::vector<HeadParams> hp_host;  // what d_hp currently holds
     std::vector<float> alpha_host, svso_host;
+    Staging stage[2];
+    int stage_next = 0;
     std::string err;
 };
 
@@ -60,6 +72,28 @@ int fail(intattn_ctx *ctx, int code, const std::string &msg)
 int hip_fail(intattn_ctx *ctx, hipError_t e, const char *what)
 {
     return fail(ctx, INTATTN_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+// Stream-ordered upload of a small table through the context's pinned staging buffers.  Two slots
+// alternate; a slot is reused only after the copy that last read it has completed (an event per
+// slot), so the call blocks only when more than two uploads are in flight -- tables change rarely.
+int upload(intattn_ctx *ctx, void *dst, const void *src, size_t bytes, hipStream_t st, const char *what)
+{
+    if (bytes > STAGING_BYTES) return fail(ctx, INTATTN_ERR_UNSUPPORTED, std::string(what) + ": table exceeds the staging buffer");
+    Staging &sg = ctx->stage[ctx->stage_next];
+    ctx->stage_next ^= 1;
+    if (!sg.host) return fail(ctx, INTATTN_ERR_NOMEM, "no staging buffer (host-only context)");
+    if (sg.pending) {
+        const hipError_t e = hipEventSynchronize(sg.done);
+        if (e != hipSuccess) return hip_fail(ctx, e, "hipEventSynchronize(staging)");
+        sg.pending = false;
+    }
+    std::memcpy(sg.host, src, bytes);
+    hipError_t e = hipMemcpyAsync(dst, sg.host, bytes, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipEventRecord(sg.done, st);
+    if (e != hipSuccess) return hip_fail(ctx, e, what);
+    sg.pending = true;
+    return INTATTN_OK;
 }
 
 // Scoped "make ctx->device current", restoring the caller's device afterwards.
@@ -162,6 +196,38 @@ bool find_mad24(uint32_t c_int, uint32_t top, HeadParams *hp)
                 hp->idx_shift = s;
                 return true;
             }
+        }
+    }
+    return false;
+}
+
+// The MAD24 form with the shift fixed at 24, so that the index is the top byte of x * mul + add (the
+// sum stays below 2^30): mul ~ top * 2^24 / c_int, and every check point x with exact index k confines
+// add to k * 2^24 <= x * mul + add < (k + 1) * 2^24.  Exists for thresholds from about 2 * top up to
+// several thousand (beyond that a 24-bit fraction no longer separates the steps).
+// Stored as idx_mul = -mul, idx_add = add, idx_shift = 24.
+bool find_top24(uint32_t c_int, uint32_t top, HeadParams *hp)
+{
+    if (c_int >= (1u << 23)) return false;
+    const std::vector<uint32_t> pts = check_points(c_int, top);
+    const int64_t m0 = (int64_t)(((uint64_t)top << 24) / c_int);
+    for (int64_t dm = 0; dm < 40; ++dm) {
+        for (int sgn = 0; sgn < 2; ++sgn) {
+            const int64_t mul = sgn ? m0 - dm : m0 + 1 + dm;
+            if (mul < 1 || mul >= (1ll << 23)) continue;
+            int64_t lo = 0, hi = (1ll << 31) - 1 - (int64_t)c_int * mul;
+            for (uint32_t x : pts) {
+                const int64_t k = (int64_t)true_index(x, c_int, top);
+                const int64_t need_lo = (k << 24) - (int64_t)x * mul, need_hi = ((k + 1) << 24) - 1 - (int64_t)x * mul;
+                if (need_lo > lo) lo = need_lo;
+                if (need_hi < hi) hi = need_hi;
+                if (lo > hi) break;
+            }
+            if (lo > hi) continue;
+            hp->idx_mul = (uint32_t)(-(int32_t)mul);
+            hp->idx_add = (uint32_t)(lo + (hi - lo) / 2);
+            hp->idx_shift = 24;
+            return true;
         }
     }
     return false;
@@ -318,10 +384,10 @@ int derive_all(intattn_ctx *ctx, const intattn_args *a, Derived *out)
     out->svso.assign((size_t)n, 0.f);
     // candidate index-map schemes in order of preference; a launch uses one scheme for all heads
     typedef bool (*finder)(uint32_t, uint32_t, HeadParams *);
-    const finder finders[4] = {find_mulhi24, find_mad24, find_fp32, find_fp64};
-    const int modes[4] = {IDX_MULHI24, IDX_MAD24, IDX_FP32, IDX_FP64};
-    bool all_ok[4] = {true, true, true, true};
-    std::vector<HeadParams> cand[4];
+    const finder finders[5] = {find_top24, find_mulhi24, find_mad24, find_fp32, find_fp64};
+    const int modes[5] = {IDX_TOP24, IDX_MULHI24, IDX_MAD24, IDX_FP32, IDX_FP64};
+    bool all_ok[5] = {true, true, true, true, true};
+    std::vector<HeadParams> cand[5];
     for (auto &c : cand) c.assign((size_t)n, HeadParams{});
     for (int h = 0; h < n; ++h) {
         const int kv = a->scale_mode ? h / g : 0;
@@ -333,14 +399,14 @@ int derive_all(intattn_ctx *ctx, const intattn_args *a, Derived *out)
         hp.c_int = (int32_t)derive_c_int(ctx->clip, sq, sk, a->d);
         if (!derive_requant(sv, so, &hp.rq_mult, &hp.rq_shift))
             return fail(ctx, INTATTN_ERR_INVALID_ARG, "s_V / (255 s_O) is outside the representable range");
-        for (int m = 0; m < 4; ++m) {
+        for (int m = 0; m < 5; ++m) {
             cand[m][(size_t)h] = hp;
             if (all_ok[m] && !finders[m]((uint32_t)hp.c_int, top, &cand[m][(size_t)h])) all_ok[m] = false;
         }
         out->alpha[(size_t)h] = (float)(((double)sq * (double)sk) / std::sqrt((double)a->d));
         out->svso[(size_t)h] = (float)((double)sv / (double)so);
     }
-    for (int m = 0; m < 4; ++m) {
+    for (int m = 0; m < 5; ++m) {
         if (all_ok[m]) {
             out->idx_mode = modes[m];
             out->hp = cand[m];
@@ -394,10 +460,18 @@ int ensure_workspace(intattn_ctx *ctx, size_t n_int32)
     return INTATTN_OK;
 }
 
-// dynamic: the scale pointers of `a` are DEVICE memory; the per-head parameters are derived by a
-// kernel on the stream and each head's index-map scheme is chosen there.
-int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, int stage = 0, bool dynamic = false)
+// What a call may do beyond the plain forward.
+struct RunMode {
+    bool comparator = false; // the conventional INT8 pipeline instead of the integer one
+    int stage = 0;           // 0: everything; 1 / 2: the two launches of the tiled path separately
+    bool dynamic = false;    // the scale pointers of the arguments are DEVICE memory: parameters derived by a kernel
+    bool reserve = false;    // allocate what the call would need and return without deriving or launching
+};
+
+int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm)
 {
+    const bool comparator = rm.comparator, dynamic = rm.dynamic;
+    const int stage = rm.stage;
     int rc = validate(ctx, a);
     if (rc) return rc;
     if (ctx->device < 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "host-only context (device -1) cannot launch");
@@ -406,7 +480,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
     Derived dv;
     if (dynamic) {
         dv.idx_mode = a->scale_mode == 2 ? IDX_ROW64 : IDX_DEVICE;
-    } else {
+    } else if (!rm.reserve) {
         // everything the derivation depends on, bit for bit
         const int n_q = a->scale_mode ? a->Hq : 1, n_kv = a->scale_mode ? a->Hkv : 1;
         std::vector<uint32_t> key;
@@ -442,6 +516,32 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
 
     DeviceGuard guard(ctx->device);
     if (guard.status != hipSuccess) return hip_fail(ctx, guard.status, "hipSetDevice");
+    hipStream_t st = (hipStream_t)stream;
+
+    // device memory of the call: the context's, allocated on demand
+    HeadParams *d_hp = nullptr; // per-head parameter table in use
+    auto get_tables = [&](int n) -> int {
+        const int r = ensure_tables(ctx, n);
+        d_hp = ctx->d_hp;
+        return r;
+    };
+    int32_t *d_ws = nullptr; // kernel workspace in use
+    auto get_ws = [&](size_t n_int32) -> int {
+        const int r = ensure_workspace(ctx, n_int32);
+        d_ws = ctx->d_ws;
+        return r;
+    };
+    // the table the kernels read: uploaded only when it differs from what the context's copy holds
+    // (calls on a context are ordered by the caller)
+    auto put_table = [&](const std::vector<HeadParams> &tab) -> int {
+        const bool same = ctx->hp_host.size() == tab.size() &&
+                          std::memcmp(ctx->hp_host.data(), tab.data(), tab.size() * sizeof(HeadParams)) == 0;
+        if (same) return INTATTN_OK;
+        const int r = upload(ctx, d_hp, tab.data(), tab.size() * sizeof(HeadParams), st, "hipMemcpyAsync(head params)");
+        if (r == INTATTN_OK) ctx->hp_host = tab;
+        else ctx->hp_host.clear();
+        return r;
+    };
 
     FwdParams p;
     std::memset(&p, 0, sizeof(p));
@@ -471,17 +571,16 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
     const bool decode = decode_ok && (ctx->variant == 9 || (ctx->variant == 0 && p.Lk >= 1024));
 
     if (dynamic) {
-        rc = ensure_tables(ctx, a->Hq);
+        rc = get_tables(a->Hq);
         if (rc) return rc;
         if (a->Hq > ctx->status_cap) {
-            int32_t *st = nullptr;
-            const hipError_t e = hipMalloc((void **)&st, sizeof(int32_t) * (size_t)a->Hq);
+            int32_t *stw = nullptr;
+            const hipError_t e = hipMalloc((void **)&stw, sizeof(int32_t) * (size_t)a->Hq);
             if (e != hipSuccess) return fail(ctx, INTATTN_ERR_NOMEM, std::string("hipMalloc of the status words: ") + hipGetErrorString(e));
             if (ctx->d_status) (void)hipFree(ctx->d_status);
-            ctx->d_status = st;
+            ctx->d_status = stw;
             ctx->status_cap = a->Hq;
         }
-        ctx->status_n = a->Hq;
         DeriveParams dp;
         std::memset(&dp, 0, sizeof(dp));
         dp.scale_q = a->scale_q; dp.scale_k = a->scale_k; dp.scale_v = a->scale_v; dp.scale_out = a->scale_out;
@@ -491,9 +590,8 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
         dp.top = p.top;
         dp.clip = ctx->clip;
         dp.sqrt_d = std::sqrt((double)a->d);
-        dp.hp_table = ctx->d_hp;
+        dp.hp_table = d_hp;
         dp.status = ctx->d_status;
-        ctx->hp_host.clear(); // the table no longer holds what the host last sent
         if (a->scale_mode == 2) {
             dp.n_rowblk = (a->L + a->q_block - 1) / a->q_block;
             dp.n_entries = (int64_t)a->B * a->Hq * dp.n_rowblk;
@@ -505,67 +603,65 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
                 ctx->d_rowtab = t;
                 ctx->rowtab_cap = (size_t)dp.n_entries;
             }
-            dp.row_table = ctx->d_rowtab;
-            const int e = launch_derive_rows(dp, stream);
-            if (e != 0) return hip_fail(ctx, (hipError_t)e, "launch(derive row-group parameters)");
-            p.row_table = ctx->d_rowtab;
-            p.q_block = a->q_block;
-            p.n_rowblk = dp.n_rowblk;
-            p.hp_table = nullptr; // the kernels take every parameter from the row table
-        } else {
-            if (stage != 2) { // stage 2 reads what stage 1 derived
-                const int e = launch_derive(dp, stream);
-                if (e != 0) return hip_fail(ctx, (hipError_t)e, "launch(derive head parameters)");
+        }
+        if (!rm.reserve) {
+            ctx->status_n = a->Hq;
+            ctx->hp_host.clear(); // the table no longer holds what the host last sent
+            if (a->scale_mode == 2) {
+                dp.row_table = ctx->d_rowtab;
+                const int e = launch_derive_rows(dp, stream);
+                if (e != 0) return hip_fail(ctx, (hipError_t)e, "launch(derive row-group parameters)");
+                p.row_table = ctx->d_rowtab;
+                p.q_block = a->q_block;
+                p.n_rowblk = dp.n_rowblk;
+                p.hp_table = nullptr; // the kernels take every parameter from the row table
+            } else {
+                if (stage != 2) { // stage 2 reads what stage 1 derived
+                    const int e = launch_derive(dp, stream);
+                    if (e != 0) return hip_fail(ctx, (hipError_t)e, "launch(derive head parameters)");
+                }
+                p.hp_table = d_hp;
             }
-            p.hp_table = ctx->d_hp;
         }
     } else if (decode) {
         // every head's parameters in the device table, each with the scheme of its index map
-        rc = ensure_tables(ctx, a->Hq);
+        rc = get_tables(a->Hq);
         if (rc) return rc;
-        std::vector<HeadParams> tab((size_t)a->Hq);
-        for (int h = 0; h < a->Hq; ++h) {
-            tab[(size_t)h] = dv.hp[a->scale_mode ? (size_t)h : 0];
-            tab[(size_t)h].pad[0] = dv.idx_mode;
+        if (!rm.reserve) {
+            std::vector<HeadParams> tab((size_t)a->Hq);
+            for (int h = 0; h < a->Hq; ++h) {
+                tab[(size_t)h] = dv.hp[a->scale_mode ? (size_t)h : 0];
+                tab[(size_t)h].pad[0] = dv.idx_mode;
+            }
+            rc = put_table(tab);
+            if (rc) return rc;
+            p.hp_table = d_hp;
         }
-        const bool same = ctx->hp_host.size() == tab.size() &&
-                          std::memcmp(ctx->hp_host.data(), tab.data(), tab.size() * sizeof(HeadParams)) == 0;
-        if (!same) {
-            const hipError_t e = hipMemcpyAsync(ctx->d_hp, tab.data(), tab.size() * sizeof(HeadParams), hipMemcpyHostToDevice,
-                                                (hipStream_t)stream);
-            if (e != hipSuccess) return hip_fail(ctx, e, "hipMemcpyAsync(head params)");
-            ctx->hp_host = tab;
-        }
-        p.hp_table = ctx->d_hp;
     } else if (a->scale_mode == 0) {
-        p.hp_table = nullptr;
-        p.hp0 = dv.hp[0];
-        p.alpha0 = dv.alpha[0];
-        p.sv_over_so0 = dv.svso[0];
+        if (!rm.reserve) {
+            p.hp_table = nullptr;
+            p.hp0 = dv.hp[0];
+            p.alpha0 = dv.alpha[0];
+            p.sv_over_so0 = dv.svso[0];
+        }
     } else {
-        rc = ensure_tables(ctx, a->Hq);
+        rc = get_tables(a->Hq);
         if (rc) return rc;
-        hipStream_t st = (hipStream_t)stream;
-        const size_t n = (size_t)a->Hq;
-        const bool same_hp = ctx->hp_host.size() == n &&
-                             std::memcmp(ctx->hp_host.data(), dv.hp.data(), n * sizeof(HeadParams)) == 0;
-        if (!same_hp) {
-            hipError_t e = hipMemcpyAsync(ctx->d_hp, dv.hp.data(), n * sizeof(HeadParams), hipMemcpyHostToDevice, st);
-            if (e != hipSuccess) return hip_fail(ctx, e, "hipMemcpyAsync(head params)");
-            ctx->hp_host = dv.hp;
+        if (!rm.reserve) {
+            rc = put_table(dv.hp);
+            if (rc) return rc;
+            if (comparator && !(ctx->alpha_host == dv.alpha && ctx->svso_host == dv.svso)) {
+                const size_t n = (size_t)a->Hq;
+                rc = upload(ctx, ctx->d_alpha, dv.alpha.data(), n * sizeof(float), st, "hipMemcpyAsync(comparator scales)");
+                if (rc == INTATTN_OK) rc = upload(ctx, ctx->d_svso, dv.svso.data(), n * sizeof(float), st, "hipMemcpyAsync(comparator scales)");
+                if (rc) return rc;
+                ctx->alpha_host = dv.alpha;
+                ctx->svso_host = dv.svso;
+            }
+            p.hp_table = d_hp;
+            p.alpha_table = ctx->d_alpha;
+            p.svso_table = ctx->d_svso;
         }
-        const bool same_f = ctx->alpha_host == dv.alpha && ctx->svso_host == dv.svso;
-        if (comparator && !same_f) {
-            hipError_t e = hipMemcpyAsync(ctx->d_alpha, dv.alpha.data(), n * sizeof(float), hipMemcpyHostToDevice, st);
-            if (e == hipSuccess)
-                e = hipMemcpyAsync(ctx->d_svso, dv.svso.data(), n * sizeof(float), hipMemcpyHostToDevice, st);
-            if (e != hipSuccess) return hip_fail(ctx, e, "hipMemcpyAsync(comparator scales)");
-            ctx->alpha_host = dv.alpha;
-            ctx->svso_host = dv.svso;
-        }
-        p.hp_table = ctx->d_hp;
-        p.alpha_table = ctx->d_alpha;
-        p.svso_table = ctx->d_svso;
     }
 
     if (decode) {
@@ -577,13 +673,14 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
         const size_t chunks = (nt32 / 4 + tpw - 1) / tpw;
         const size_t n_scores = groups * nt32 * 2 * R * 16, n_idx = groups * nt32 * 2 * R * 4, n_part = groups * chunks * 4 * R;
         const size_t n_acc = groups * chunks * R * (size_t)a->d;
-        rc = ensure_workspace(ctx, n_scores + n_idx + 2 * n_part + n_acc);
+        rc = get_ws(n_scores + n_idx + 2 * n_part + n_acc);
         if (rc) return rc;
+        if (rm.reserve) return INTATTN_OK;
         p.dec_rows = (int32_t)R;
         p.dec_nt32 = (int32_t)nt32;
         p.dec_tpw = (int32_t)tpw;
         p.dec_np = (int32_t)(chunks * 4);
-        p.dec_scores = ctx->d_ws; // every part is a multiple of 4 words: 16-byte alignment holds
+        p.dec_scores = d_ws; // every part is a multiple of 4 words: 16-byte alignment holds
         p.dec_idx = p.dec_scores + n_scores;
         p.dec_acc = p.dec_idx + n_idx;
         p.dec_pmax = p.dec_acc + n_acc;
@@ -596,12 +693,13 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, bool comparator, 
     if (!comparator) {
         const size_t rows = (size_t)a->B * a->Hq * a->L;
         const size_t cs = (size_t)a->B * a->Hkv * p.n_chunks * a->d;
-        rc = ensure_workspace(ctx, 2 * rows + cs);
+        rc = get_ws(2 * rows + cs);
         if (rc) return rc;
-        p.ws_row_max = ctx->d_ws;
+        p.ws_row_max = d_ws;
         p.ws_row_sum = p.ws_row_max + rows;
         p.ws_colsum = p.ws_row_sum + rows;
     }
+    if (rm.reserve) return INTATTN_OK;
 
     const int herr = comparator ? launch_quantonly(p, a->d, ctx->variant, stream)
                                 : launch_fwd(p, a->d, dv.idx_mode, variant, stage, stream);
@@ -642,24 +740,50 @@ int intattn_create(intattn_ctx **out, const intattn_config *cfg)
     for (int i = 0; i < n - 1; ++i)
         ctx->lut[i] = (uint8_t)std::floor(255.0 * std::exp(-cfg->clip * (double)i / (double)(n - 1)) + 0.5);
     ctx->lut[n - 1] = 0;
+    if (ctx->device >= 0) {
+        DeviceGuard guard(ctx->device);
+        hipError_t e = guard.status;
+        // pinned staging for table uploads
+        for (Staging &sg : ctx->stage) {
+            if (e == hipSuccess) e = hipHostMalloc((void **)&sg.host, STAGING_BYTES, hipHostMallocDefault);
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&sg.done, hipEventDisableTiming);
+        }
+        if (e != hipSuccess) {
+            const int rc = hip_fail(nullptr, e, "intattn_create (staging buffers)");
+            intattn_destroy(ctx);
+            return rc;
+        }
+    }
     *out = ctx;
     return INTATTN_OK;
 }
 
 int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void *hip_stream)
 {
-    return run(ctx, args, hip_stream, false);
+    return run(ctx, args, hip_stream, RunMode{});
+}
+
+int intattn_reserve(intattn_ctx *ctx, const intattn_args *args, int32_t dynamic)
+{
+    RunMode rm;
+    rm.reserve = true;
+    rm.dynamic = dynamic != 0;
+    return run(ctx, args, nullptr, rm);
 }
 
 int intattn_forward_stage(intattn_ctx *ctx, const intattn_args *args, void *hip_stream, int32_t stage)
 {
     if (stage < 0 || stage > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "stage must be 0, 1 or 2");
-    return run(ctx, args, hip_stream, false, stage);
+    RunMode rm;
+    rm.stage = stage;
+    return run(ctx, args, hip_stream, rm);
 }
 
 int intattn_forward_dynamic(intattn_ctx *ctx, const intattn_args *args, void *hip_stream)
 {
-    return run(ctx, args, hip_stream, false, 0, true);
+    RunMode rm;
+    rm.dynamic = true;
+    return run(ctx, args, hip_stream, rm);
 }
 
 int intattn_dynamic_status(intattn_ctx *ctx, int32_t *status)
@@ -779,7 +903,9 @@ int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *a, void *hip_st
 
 int intattn_forward_quantonly(intattn_ctx *ctx, const intattn_args *args, void *hip_stream)
 {
-    return run(ctx, args, hip_stream, true);
+    RunMode rm;
+    rm.comparator = true;
+    return run(ctx, args, hip_stream, rm);
 }
 
 int intattn_derive_params(const intattn_ctx *ctx, float s_q, float s_k, float s_v, float s_o, int32_t d,
@@ -807,6 +933,8 @@ int intattn_derive_index_map(const intattn_ctx *ctx, int64_t c_int, int32_t *mod
         *mode = find_fp32((uint32_t)c_int, top, &hp) ? IDX_FP32 : IDX_FP64;
     } else if (*mode == IDX_MULHI24) {
         *mode = find_mulhi24((uint32_t)c_int, top, &hp) ? IDX_MULHI24 : IDX_FP64;
+    } else if (*mode == IDX_TOP24) {
+        *mode = find_top24((uint32_t)c_int, top, &hp) ? IDX_TOP24 : IDX_FP64;
     } else {
         *mode = IDX_FP64;
     }
@@ -853,6 +981,11 @@ void intattn_destroy(intattn_ctx *ctx)
         if (ctx->d_amax) (void)hipFree(ctx->d_amax);
         if (ctx->d_status) (void)hipFree(ctx->d_status);
         if (ctx->d_rowtab) (void)hipFree(ctx->d_rowtab);
+        for (Staging &sg : ctx->stage) {
+            if (sg.pending) (void)hipEventSynchronize(sg.done);
+            if (sg.done) (void)hipEventDestroy(sg.done);
+            if (sg.host) (void)hipHostFree(sg.host);
+        }
     }
     delete ctx;
 }

@@ -3,7 +3,8 @@
 // reading anything back:
 //   c_int = round(c * sqrt(d) / (s_Q s_K))                    (Sec. 3.1, Eq. clipping_thr)
 //   (M, sh) with M * 2^-sh ~ s_V / (255 s_O), M in [2^30, 2^31)   (output requantization)
-//   constants of an exact index map idx = round(x * top / c_int)  (Sec. 3.1, index map)
+//   constants of an exact index map idx = round(x * top / c_int)  (Sec. 3.1, index map): the 24-bit
+//   multiply-add whose top byte is the index where it exists, else the fp64 map
 // The arithmetic is the host's, operation for operation, in IEEE double: products, quotients,
 // floor, frexp and the fma are exactly rounded on the GPU as on the CPU, and sqrt(d) comes from the
 // host.  One wave per query head, one check point of the index map per lane.
@@ -38,7 +39,8 @@ __device__ __forceinline__ bool derive_scalars(float sq, float sk, float sv, flo
         if (c > 1073741824.0) c = 1073741824.0;
     }
     hp.c_int = (int32_t)c;
-    hp.rq_mult = 1 << 30;
+    // unusable scales: multiplier 0, i.e. the head's output is all zeros (and its status word is set)
+    hp.rq_mult = 0;
     hp.rq_shift = 31;
     if (ok) {
         const double r = (double)sv / (255.0 * (double)so);
@@ -97,23 +99,36 @@ __global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
     }
     const uint32_t want = exact_index(have ? x : 0u, c_int, top);
 
-    // fp32: trunc(fma(x, r, 0.5)) with r one of the three floats around top / c_int (x must be exact in fp32)
-    const uint32_t bits0 = __float_as_uint((float)((double)top / (double)c_int)) - 1u; // the float before (r > 0)
-    int found = -1;
-    if (c_int < (1u << 24)) {
+    // (x * mul + add) >> 24 with a 23-bit multiplier (the host's find_top24, candidate for candidate):
+    // lane l's check point with exact index k confines add to [k 2^24 - x mul, (k + 1) 2^24 - 1 - x mul];
+    // the first multiplier around top 2^24 / c_int whose intervals intersect is taken
+    bool found = false;
+    if (ok && c_int < (1u << 23)) {
+        const long long m0 = (long long)(((unsigned long long)top << 24) / c_int);
+        for (int cand = 0; cand < 80 && !found; ++cand) { // wave-uniform
+            const long long dm = cand >> 1, mul = (cand & 1) ? m0 - dm : m0 + 1 + dm;
+            if (mul < 1 || mul >= (1ll << 23)) continue;
+            long long lo = 0, hi = (1ll << 31) - 1 - (long long)c_int * mul;
+            if (have) {
+                const long long xm = (long long)x * mul;
+                lo = max(lo, ((long long)want << 24) - xm);
+                hi = min(hi, (((long long)want + 1) << 24) - 1 - xm);
+            }
 #pragma unroll
-        for (int step = 0; step < 3; ++step) {
-            const float r = __uint_as_float(bits0 + (uint32_t)step);
-            const bool match = !have || (uint32_t)(int)__builtin_fmaf(-(float)x, -r, 0.5f) == want;
-            if (found < 0 && __all(match)) found = step;
+            for (int off = 32; off >= 1; off >>= 1) {
+                lo = max(lo, __shfl_xor(lo, off));
+                hi = min(hi, __shfl_xor(hi, off));
+            }
+            if (lo <= hi) {
+                found = true;
+                hp.pad[0] = IDX_TOP24;
+                hp.idx_mul = (uint32_t)(-(int32_t)mul);
+                hp.idx_add = (uint32_t)(lo + (hi - lo) / 2);
+                hp.idx_shift = 24;
+            }
         }
     }
-    if (found >= 0) {
-        hp.pad[0] = IDX_FP32;
-        hp.idx_mul = (bits0 + (uint32_t)found) ^ 0x80000000u; // bits of -r
-        hp.idx_add = 0;
-        hp.idx_shift = 0;
-    } else {
+    if (!found) {
         // fp64 with r the double after top / c_int: exact for every c_int (the excess of r is under
         // two units in the last place and the fma rounds once, monotonically; values of
         // x*top/c_int + 1/2 that are not integers stay 1/(2 c_int) away from the next integer)
@@ -127,6 +142,7 @@ __global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
         hp.idx_add = (uint32_t)(neg >> 32);
         hp.idx_shift = 0;
     }
+    if (!ok) hp.rq_mult = 0; // (the fp64 check cannot fail; kept as the last line of defence)
     if (lane == 0) {
         dp.hp_table[h] = hp;
         dp.status[h] = ok ? 0 : 1;

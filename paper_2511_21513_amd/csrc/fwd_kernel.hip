@@ -63,10 +63,8 @@ int launch_colsum(const FwdParams &p, int d, int chunk, hipStream_t st)
 
 // Kernel variants (0 = automatic choice; the others are tuning knobs, all bit-identical):
 //   1  one launch, 32 query rows per wave, 64-key tiles     2  one launch, 64 rows per wave
-//   3  one launch, 32 rows per wave, 32-key tiles
 //   4  two launches: sweeps A+B (64 rows per wave), then sweep C (32 rows per wave), phase-ordered kernels
-//   5  as 4 with the software-pipelined sweep C kernel      6  as 5 with 64 rows per wave in sweep C
-//   7  software-pipelined sweeps A+B (64 rows per wave) and sweep C     8  as 7 with 32 rows per wave in A+B
+//   5  as 4 with the software-pipelined sweep C kernel
 //   9  the split-key kernels of decode_kernel.hip whenever the shape allows them, else as 0
 // Automatic choice among the tiled kernels: enough workgroups to amortise three launches -> variant 5;
 // small problems take the single launch.
@@ -76,13 +74,13 @@ int fwd_choose_variant(int variant, int B, int Hq, int L)
     const int64_t workgroups = (int64_t)B * Hq * ((L + 127) / 128);
     return workgroups >= 1024 ? 5 : 1;
 }
-bool fwd_variant_known(int variant) { return variant >= 0 && variant <= 9; }
-int fwd_rows_per_block(int variant) { return (variant == 2 || variant == 6) ? 256 : 128; }
+bool fwd_variant_known(int variant) { return variant == 0 || variant == 1 || variant == 2 || variant == 4 || variant == 5 || variant == 9; }
+int fwd_rows_per_block(int variant) { return variant == 2 ? 256 : 128; }
 
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const bool two_launches = variant >= 4 && variant <= 8;
+    const bool two_launches = variant == 4 || variant == 5;
     if (stage != 0 && !two_launches) return (int)hipErrorNotSupported;
     // all launches go to the same stream: V chunk sums first, then the sweeps
     int e = 0;
@@ -91,24 +89,21 @@ int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, 
         FwdParams ps = p;
         ps.ws_colsum = nullptr;
         if (variant == 2) return launch_shape<2, 2, 0>(ps, d, idx_mode, st);
-        if (variant == 3) return launch_shape<1, 1, 0>(ps, d, idx_mode, st);
         return launch_shape<1, 2, 0>(ps, d, idx_mode, st);
     }
     if (stage != 2) e = launch_colsum(p, d, fwd_rows_per_block(variant), st);
     if (e != 0) return e;
     if (variant == 2) return launch_shape<2, 2, 0>(p, d, idx_mode, st);
-    if (variant == 3) return launch_shape<1, 1, 0>(p, d, idx_mode, st);
     if (two_launches) {
         // sweeps A+B leave row max and row sum in the workspace for sweep C
         if (stage != 2) {
             FwdParams pab = p;
-            if (variant != 8) pab.n_qtiles = fwd_row_tiles(p.row_lo, p.L, 256); // 64 query rows per wave in the first launch
-            e = variant <= 6 ? launch_shape<2, 2, 1>(pab, d, idx_mode, st)
-                             : launch_sweep_ab(pab, d, idx_mode, variant == 7 ? 64 : 32, stream);
+            pab.n_qtiles = fwd_row_tiles(p.row_lo, p.L, 256); // 64 query rows per wave in the first launch
+            e = launch_shape<2, 2, 1>(pab, d, idx_mode, st);
             if (e != 0 || stage == 1) return e;
         }
         if (variant == 4) return launch_shape<1, 2, 2>(p, d, idx_mode, st);
-        return launch_sweep_c(p, d, idx_mode, variant == 6 ? 64 : 32, stream);
+        return launch_sweep_c(p, d, idx_mode, stream);
     }
     return launch_shape<1, 2, 0>(p, d, idx_mode, st);
 }

@@ -83,7 +83,9 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     const int b = wi.b, hq = wi.hq, kvh = wi.kvh, qt = wi.qt + p.row_lo / BQ;
     const int bh = b * p.Hq + hq;
     const HeadParams hp = p.hp_table ? p.hp_table[hq] : p.hp0;
-    if (p.filter && hp.pad[0] != MODE) return; // another launch of this pair serves the head (uniform for the workgroup)
+    // device-derived parameters: another launch of this pair serves the head when its scheme is not this
+    // kernel's (uniform for the workgroup); the top-byte scheme runs in the multiply-add code here
+    if (p.filter && (hp.pad[0] == IDX_TOP24 ? (int)IDX_MAD24 : hp.pad[0]) != MODE) return;
     const int L = p.Lk; // keys
     // query rows: [rlo, rhi) of the numbering in which row r sees keys <= r under the causal mask
     const int rlo = p.row_lo, rhi = p.row_lo + p.L, LQ = p.L;
@@ -528,11 +530,11 @@ int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
         // skipping the heads of the other
         FwdParams pf = p;
         pf.filter = 1;
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP32, PH>), grid, block, 0, st, pf);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24, PH>), grid, block, 0, st, pf);
         hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP64, PH>), grid, block, 0, st, pf);
         return (int)hipGetLastError();
     }
-    if (idx_mode == IDX_MAD24)
+    if (idx_mode == IDX_MAD24 || idx_mode == IDX_TOP24) // TOP24 is MAD24 with the shift at 24: same code here
         hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24, PH>), grid, block, 0, st, p);
     else if (idx_mode == IDX_MULHI24)
         hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MULHI24, PH>), grid, block, 0, st, p);

@@ -5,6 +5,5 @@ namespace intattn {
 namespace fwdk {
 template int launch_shape<1, 2, 0>(const FwdParams &, int, int, hipStream_t);
 template int launch_shape<2, 2, 0>(const FwdParams &, int, int, hipStream_t);
-template int launch_shape<1, 1, 0>(const FwdParams &, int, int, hipStream_t);
 } // namespace fwdk
 } // namespace intattn

@@ -64,6 +64,8 @@ __device__ __forceinline__ uint32_t index_map(int t, const HeadParams &hp, uint3
     if (MODE == IDX_MAD24) {
         // (-t) * mul + add, 24-bit signed operands (idx_mul holds -mul)
         return (uint32_t)(__mul24(t, (int)hp.idx_mul) + (int)hp.idx_add) >> hp.idx_shift;
+    } else if (MODE == IDX_TOP24) {
+        return (uint32_t)(__mul24(t, (int)hp.idx_mul) + (int)hp.idx_add) >> 24;
     } else if (MODE == IDX_MULHI24) {
         // high word of ((t << pre) - off) * (-mul): both factors negative 24-bit values
         const int x = (int)(((uint32_t)t << hp.idx_shift) + hp.idx_add); // idx_add holds -off
@@ -88,6 +90,7 @@ __device__ __forceinline__ uint32_t index_any(const HeadParams &hp, int t, uint3
 {
     switch (hp.pad[0]) {
     case IDX_MAD24: return index_map<IDX_MAD24>(t, hp, top);
+    case IDX_TOP24: return index_map<IDX_TOP24>(t, hp, top);
     case IDX_MULHI24: return index_map<IDX_MULHI24>(t, hp, top);
     case IDX_FP32: return index_map<IDX_FP32>(t, hp, top);
     default: return index_map<IDX_FP64>(t, hp, top);
@@ -116,8 +119,19 @@ template <int MODE> struct RowIndex {
         negr = (MODE == IDX_FP64 || MODE == IDX_ROW64) ? idx_fp64_factor(hp) : 0.0;
         (void)top_;
         if (MODE == IDX_MULHI24) addc = hp.idx_add - ((uint32_t)row_max << hp.idx_shift);
-        else if (MODE == IDX_MAD24) addc = hp.idx_add - (uint32_t)__mul24(row_max, (int)hp.idx_mul);
+        else if (MODE == IDX_MAD24 || MODE == IDX_TOP24) addc = hp.idx_add - (uint32_t)__mul24(row_max, (int)hp.idx_mul);
         else addc = 0;
+    }
+    // Delta' * mul + add of the clipped score sc (IDX_TOP24: the index is its top byte)
+    __device__ __forceinline__ uint32_t scaled(int sc) const { return (uint32_t)__mul24(sc, mul) + addc; }
+    // Address of the score's entry in a table whose rows (one per index) are 256 bytes apart.  lane_base =
+    // the table's address, which must be a multiple of 65536, plus the lane's offset (< 256) inside a
+    // row.  IDX_TOP24: one byte permute puts the top byte of the scaled score into byte 1 of lane_base;
+    // the other schemes shift the index up and add.
+    __device__ __forceinline__ uint32_t row_addr(int sc, uint32_t lane_base) const
+    {
+        if (MODE == IDX_TOP24) return __builtin_amdgcn_perm(scaled(sc), lane_base, 0x03020700u);
+        return ((*this)(sc) << 8) + lane_base;
     }
     __device__ __forceinline__ uint32_t operator()(int sc) const
     {
@@ -128,6 +142,8 @@ template <int MODE> struct RowIndex {
             return (uint32_t)r;
         } else if (MODE == IDX_MAD24) {
             return ((uint32_t)__mul24(sc, mul) + addc) >> shift;
+        } else if (MODE == IDX_TOP24) {
+            return scaled(sc) >> 24;
         } else if (MODE == IDX_FP32) {
             return (uint32_t)(int)__builtin_fmaf((float)(sc - mx), __uint_as_float((uint32_t)mul), 0.5f);
         } else {

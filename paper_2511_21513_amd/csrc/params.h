@@ -14,8 +14,10 @@ enum IdxMode : int32_t {
     IDX_MULHI24 = 2,// high 32 bits of the 48-bit product ((Delta' << pre) + add) * mul
     IDX_FP32 = 3,   // trunc(fma(Delta', top/c_int, 0.5)) in IEEE fp32 (idx_mul holds the bits of -top/c_int)
     IDX_DEVICE = 4, // launchers only: each head's scheme (FP32 or FP64) is in its HeadParams, written on the device
-    IDX_ROW64 = 5   // the fp64 scheme with parameters per block of query rows (FwdParams::row_table): finer
+    IDX_ROW64 = 5,  // the fp64 scheme with parameters per block of query rows (FwdParams::row_table): finer
                     // quantization groups over the query rows, Sec. 3.3
+    IDX_TOP24 = 6   // MAD24 with shift 24: the index is the top byte of Delta' * mul + add, which one byte
+                    // permute turns into the address of a table row 256 bytes apart (sweep C)
 };
 
 // Per query head: everything the kernel needs that depends on the scales.
@@ -110,8 +112,7 @@ struct DeriveParams {
 // Launchers implemented in the .hip files.  Return a hipError_t cast to int.
 // stage 0: everything; 1: V column sums + sweeps A+B; 2: sweep C (two-launch variants only; else hipErrorNotSupported)
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, void *stream);
-int launch_sweep_ab(const FwdParams &p, int d, int idx_mode, int rows_per_wave, void *stream);
-int launch_sweep_c(const FwdParams &p, int d, int idx_mode, int rows_per_wave, void *stream);
+int launch_sweep_c(const FwdParams &p, int d, int idx_mode, void *stream);
 int fwd_choose_variant(int variant, int B, int Hq, int L); // resolves 0 (automatic) to a concrete variant
 int fwd_rows_per_block(int variant);
 // tiles of `rows_per_tile` rows, aligned to multiples of it, that rows [row_lo, row_lo + n_rows) touch

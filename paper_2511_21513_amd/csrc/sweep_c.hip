@@ -20,6 +20,26 @@
 // has half a step or more to arrive, and nothing waits on what it has just issued.  Scheduling
 // barriers pin that order.
 //
+// Table lookups without LDS.  P_hat = round(255 E_hat / S) is 0 for every table index k with
+// 510 LUT_hat[k] < S (Eq. uint8-prob), so a row whose sum S exceeds 510 LUT_hat[8 n] can only give a
+// nonzero probability at its first 8 n table entries, and once S > 510 every probability fits a
+// signed byte.  Such a row keeps those entries in 2 n registers (n = 1, 2, 3), the kernel clips the
+// distance at the first value whose index is 8 n instead of at c_int (the index map below that is
+// unchanged), packs four index bytes into a register and looks four probabilities up with n byte
+// permutes: a permute selects among the 8 bytes of a register pair, returns 0xff for selectors from 13
+// up and 0 for selector 12 or a sign selector of a byte below 128, so with selectors rewritten per
+// pair (in range: 0..7; out of range: >= 16) the AND of the n results is the entry, and the clipped
+// index lands on a selector that yields 0.  No table in LDS, no lookup latency to hide, no offset of
+// 128, no column-sum correction.  The LDS pipe is shared by the four SIMDs of a compute unit and a
+// wave-wide byte lookup costs it three cycles -- sixteen of them per 32 x 32 block were the largest
+// single cost of this kernel.  The path is chosen per wave: the largest n among its 32 rows, and the
+// general path with the tables in LDS when a row has S <= 510 or more than 24 live entries.  The four
+// waves of a workgroup meet at a barrier per tile, so a workgroup runs at the pace of its slowest wave:
+// rows with similar sums (flat logits, encoder-style attention over many keys) gain up to a quarter,
+// workloads whose row sums vary widely inside every tile (heavy-tailed logits) stay at the general
+// path's speed.  (Sorting the rows of a tile by n to make its waves homogeneous was measured and
+// dropped: the slowest wave still sets the pace.)
+//
 // Tiles are NSUB sub-tiles (64 or 128 keys), double buffered per operand; one barrier per tile.
 // The K fragments are read two sub-tiles ahead of the V^T fragments.  K tiles are cut NSUB - 2
 // sub-tiles earlier than V tiles (K tile t covers sub-tiles [NSUB (t-1) + 2, NSUB t + 2)), so that
@@ -65,7 +85,13 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     __shared__ __attribute__((aligned(1024))) int8_t Ks1[TILE];
     __shared__ __attribute__((aligned(1024))) int8_t Vs0[TILE];
     __shared__ __attribute__((aligned(1024))) int8_t Vs1[TILE];
-    __shared__ uint16_t PT[WAVES][RB][32 * 32]; // [idx][row] per wave and row block (16-bit entries: half the LDS, few bank conflicts)
+    // per-row probability tables of the workgroup as bytes [idx][lane][wave]: a table row (one index) is 256
+    // bytes, lane l of wave w owns byte 4 l + w of every row -- its own bank, so lookups never conflict --
+    // and the address of an entry is (idx << 8) + 4 l + w, which the IDX_TOP24 scheme forms with one byte
+    // permute.  The two lanes that share a query row (l and l + 32) each hold a copy of its table.
+    static_assert(RB == 1 && WAVES == 4, "table layout: 64 lanes x 4 waves = one 256-byte row per index");
+    // (aligned to 64 KiB: the table's address then has a zero byte 1 for the index to go into)
+    __shared__ __attribute__((aligned(65536))) uint8_t PT[32 * 256];
     __shared__ uint32_t lut_lds[8];
     __shared__ int32_t colsum[D];
 
@@ -86,24 +112,12 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     };
     const uint32_t top = (uint32_t)p.top;
 
-    const int q0 = qt * BQ, qw0 = q0 + wave * (RB * 32);
+    const int q0 = qt * BQ;
     const int8_t *Qp = p.q + (int64_t)b * p.qs[0] + (int64_t)hq * p.qs[1];
     const int8_t *Kp = p.k + (int64_t)b * p.ks[0] + (int64_t)kvh * p.ks[1];
     const int8_t *Vp = p.v + (int64_t)b * p.vs[0] + (int64_t)kvh * p.vs[1];
 
     if (tid < 8) lut_lds[tid] = p.lut[tid];
-
-    // Q fragments: row block rb, row qw0 + 32 rb + n, bytes [32 kb + 16 h, +16)
-    v4i qf[RB][KB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int row = qw0 + 32 * rb + n;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            qf[rb][kb] = v4i{0, 0, 0, 0};
-            if (row >= rlo && row < rhi) qf[rb][kb] = *(const v4i *)(Qp + (int64_t)(row - rlo) * p.qs[2] + kb * 32 + h * 16);
-        }
-    }
 
     const int kmax = CAUSAL ? min(L, q0 + BQ) : L;
     const int ntiles = (kmax + BK - 1) / BK; // iterations = V tiles; K tiles 0..ntiles are touched
@@ -150,18 +164,69 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     dma_v(0, Vs0);
     dma_k(1, Ks1);
 
-    // ---- per-row state from the first launch, probability tables, column sums of V
+    // ---- class of every row
+    // class n = 1, 2, 3: S > max(510 LUT_hat[8 n], 510), the row needs n register pairs; 4: the general path.
+    auto lut_at = [&](int k) { return (uint32_t)k <= top ? (p.lut[k / 4] >> (8 * (k % 4))) & 0xffu : 0u; };
+    auto row_class = [&](uint32_t s_row, const HeadParams &hr) {
+        int c = 4;
+#pragma unroll
+        for (int nn = 3; nn >= 1; --nn) {
+            // first clipped distance whose index is 8 nn; its own index is the "probability 0" selector and
+            // must be exactly 8 nn (thresholds below two per index step can jump past it)
+            const int64_t cap = 8 * nn > (int)top ? hr.c_int : ((int64_t)(16 * nn - 1) * hr.c_int + 2 * (int64_t)top - 1) / (2 * (int64_t)top);
+            const bool exact = 8 * nn > (int)top || (cap <= hr.c_int && (2 * (int64_t)top * cap + hr.c_int) / (2 * (int64_t)hr.c_int) == 8 * nn);
+            if (exact && s_row > max(510u * lut_at(8 * nn), 510u)) c = nn;
+        }
+        return c;
+    };
+    const int qw0 = q0 + 32 * wave;
+    const int row = qw0 + n; // this lane's query row
+    const bool valid = row >= rlo && row < rhi;
+    // the wave's path: the largest class among its rows (0: general path); rows outside [rlo, rhi) are inert
+    const int my_cls = valid ? row_class((uint32_t)p.ws_row_sum[(int64_t)bh * LQ + (row - rlo)], MODE == IDX_ROW64 ? row_hp(row) : hp) : 1;
+    const int path = __any(my_cls == 4) ? 0 : __any(my_cls == 3) ? 3 : __any(my_cls == 2) ? 2 : 1;
+
+    // Q fragments: row `row`, bytes [32 kb + 16 h, +16)
+    v4i qf[RB][KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+        qf[0][kb] = v4i{0, 0, 0, 0};
+        if (valid) qf[0][kb] = *(const v4i *)(Qp + (int64_t)(row - rlo) * p.qs[2] + kb * 32 + h * 16);
+    }
+
+    // ---- per-row state from the first launch
     RowIndex<MODE> ri[RB];
     uint32_t sum[RB];
+    const HeadParams hrow = MODE == IDX_ROW64 ? row_hp(row) : hp;
+    {
+        const int mx = valid ? p.ws_row_max[(int64_t)bh * LQ + (row - rlo)] : 0;
+        sum[0] = valid ? (uint32_t)p.ws_row_sum[(int64_t)bh * LQ + (row - rlo)] : 0u;
+        if (sum[0] == 0) sum[0] = 1; // only rows outside [rlo, rhi); never stored
+        ri[0].init(hrow, mx, top);
+        if (p.dbg_row_max && h == 0 && valid) p.dbg_row_max[(int64_t)bh * LQ + (row - rlo)] = mx;
+        if (p.dbg_row_sum && h == 0 && valid) p.dbg_row_sum[(int64_t)bh * LQ + (row - rlo)] = (int32_t)sum[0];
+    }
+
+    // ---- register tables of the permute paths: tab[2 k], tab[2 k + 1] hold entries 8 k .. 8 k + 7 of
+    // P_hat[idx] = round(255 LUT_hat[idx] / S); the clip of path n at the first distance of index 8 n
+    RowIndex<MODE> rif[RB];
+    uint32_t tab[6] = {0u, 0u, 0u, 0u, 0u, 0u};
+    rif[0] = ri[0];
+    if (path != 0) {
+        const int64_t cap = 8 * path > (int)top ? hrow.c_int : ((int64_t)(16 * path - 1) * hrow.c_int + 2 * (int64_t)top - 1) / (2 * (int64_t)top);
+        rif[0].bound = ri[0].mx - (int)cap;
+        // quotients below 128 of numerators below 2^26: a single-precision estimate, corrected by at most one
+        const float rs = 1.0f / (float)(2u * sum[0]);
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int row = qw0 + 32 * rb + n;
-        const int mx = (row >= rlo && row < rhi) ? p.ws_row_max[(int64_t)bh * LQ + (row - rlo)] : 0;
-        sum[rb] = (row >= rlo && row < rhi) ? (uint32_t)p.ws_row_sum[(int64_t)bh * LQ + (row - rlo)] : 0u;
-        if (sum[rb] == 0) sum[rb] = 1; // only rows outside [rlo, rhi); never stored
-        ri[rb].init(MODE == IDX_ROW64 ? row_hp(row) : hp, mx, top);
-        if (p.dbg_row_max && h == 0 && row >= rlo && row < rhi) p.dbg_row_max[(int64_t)bh * LQ + (row - rlo)] = mx;
-        if (p.dbg_row_sum && h == 0 && row >= rlo && row < rhi) p.dbg_row_sum[(int64_t)bh * LQ + (row - rlo)] = (int32_t)sum[rb];
+        for (int k = 0; k < 24; ++k) {
+            if (k < 8 * path) { // wave-uniform
+                const uint32_t num = 510u * lut_at(k) + sum[0], den = 2u * sum[0];
+                uint32_t q = (uint32_t)((float)num * rs);
+                if (q * den > num) --q;
+                if ((q + 1u) * den <= num) ++q;
+                tab[k / 4] |= (valid ? q : 0u) << (8 * (k % 4));
+            }
+        }
     }
 
     // Column sums of V over every key the steps below cover (keys up to the end of this query tile
@@ -177,22 +242,22 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     }
     __syncthreads(); // LUT_hat, K tiles 0 and 1, V tile 0 are in LDS
 
-    // per-row probability table: PT[idx] = round(255 * LUT_hat[idx] / sum) - 128 as a byte
-    {
+    // per-row probability table of the general path: PT[idx] = round(255 * LUT_hat[idx] / sum) - 128 as a
+    // byte; each lane of a row's pair computes half of the entries and stores them into both lanes' columns
+    const uint32_t lane_off = (uint32_t)(4 * lane + wave);
+    const uint32_t lane_base = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) uint8_t *)PT + lane_off;
+    if (path == 0) {
         const uint8_t *lut_b = (const uint8_t *)lut_lds;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            uint16_t *ptw = PT[wave][rb];
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int kidx = 16 * h + j;
-                const uint32_t e = lut_b[kidx];
-                const uint32_t pr = (510u * e + sum[rb]) / (2u * sum[rb]);
-                ptw[kidx * 32 + n] = (uint16_t)((pr ^ 0x80u) & 0xffu);
-            }
+        for (int j = 0; j < 16; ++j) {
+            const int kidx = 16 * h + j;
+            const uint32_t e = lut_b[kidx];
+            const uint32_t pr = (510u * e + sum[0]) / (2u * sum[0]);
+            const uint8_t byte = (uint8_t)((pr ^ 0x80u) & 0xffu);
+            PT[kidx * 256 + 4 * n + wave] = byte;
+            PT[kidx * 256 + 4 * (n + 32) + wave] = byte;
         }
     }
-    const uint16_t *pt = PT[wave][0] + n; // row block rb: + 1024 rb
 
     // ---- LDS read addresses (lane constants; sub-tile and buffer go into immediate offsets)
     int kf_off[KB], vf_off[CB];
@@ -219,7 +284,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
             vf[cb] = v4i{x0[0], x0[1], x1[0], x1[1]};
         }
     };
-    auto visible = [&](int key, int rb) { return key < L && (!CAUSAL || key <= qw0 + 32 * rb + n); };
+    auto visible = [&](int key, int) { return key < L && (!CAUSAL || key <= row); };
 
     // ---- pipeline state
     v16i o[RB][CB];
@@ -244,11 +309,13 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
             bt[r] = l[w0 + r];
             if (MASKED) bt[r] = visible(32 * jp + acc_key(e0 + r, h), rb) ? bt[r] : 0x80u;
         }
+        // byte permutes: two looked-up bytes into a pair, two pairs into the operand register
+        const uint32_t pair = __builtin_amdgcn_perm(bt[1], bt[0], 0x0c0c0400u);
         if (EPS == 4) {
-            pf[rb][g] = (int)(((bt[1] << 8) | bt[0]) | (((bt[3 % EPS] << 8) | bt[2 % EPS]) << 16));
+            const uint32_t pair2 = __builtin_amdgcn_perm(bt[3 % EPS], bt[2 % EPS], 0x0c0c0400u);
+            pf[rb][g] = (int)__builtin_amdgcn_perm(pair2, pair, 0x05040100u);
         } else {
-            const uint32_t pair = (bt[1] << 8) | bt[0];
-            pf[rb][g] = (e0 % 4 == 0) ? (int)pair : (int)((uint32_t)pf[rb][g] | (pair << 16));
+            pf[rb][g] = (e0 % 4 == 0) ? (int)pair : (int)__builtin_amdgcn_perm(pair, (uint32_t)pf[rb][g], 0x05040100u);
         }
     };
 
@@ -257,9 +324,29 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     // A score looked up after MFMA slot s is packed HALF slots later, so only half a step's lookups
     // are in flight and the packing never waits for what was just issued.  On entry kf holds the K
     // fragments of sub-tile j+1 and vf the V^T fragments of sub-tile j-1.
-    auto step = [&](auto masked_tag, int j, const int8_t *Knext, const int8_t *Vcur, const v16i (&sc)[RB], v16i (&sn)[RB],
+    uint32_t selw[RB]; // permute paths: index bytes of the operand register being assembled
+    // Four probabilities from four packed index bytes s4 (each 0 .. 8 NP, where 8 NP is the clipped index)
+    // and the row's NP register pairs.  lift(x) = x | ((x & 8) << 1) keeps 0..7 and turns 8..15 into
+    // 24..31, so a lifted selector is 0..7 inside its pair and >= 16 (permute result 0xff) outside; the
+    // last pair's selector is left so that the clipped index becomes 8, the sign of a byte below 128: 0.
+    //   NP = 2:  A = lift(s): 0..7 | 24..31 | 16;    A ^ 24: 24..31 | 0..7 | 8
+    //   NP = 3:  lift(s): 0..7 | 24..31 | 16..23 | 24;   lift(s ^ 8): 24..31 | 0..7 | 24..31 | 16;
+    //            s ^ 16: 16..23 | 24..31 | 0..7 | 8
+    auto lookup = [&](auto np_tag, uint32_t s4) __attribute__((always_inline)) {
+        constexpr int NP = decltype(np_tag)::value;
+        auto lift = [](uint32_t x) { const uint32_t t = x & 0x08080808u; return x | (t + t); };
+        if (NP == 1) return __builtin_amdgcn_perm(tab[1], tab[0], s4);
+        if (NP == 2) {
+            const uint32_t sa = lift(s4);
+            return __builtin_amdgcn_perm(tab[1], tab[0], sa) & __builtin_amdgcn_perm(tab[3], tab[2], sa ^ 0x18181818u);
+        }
+        return __builtin_amdgcn_perm(tab[1], tab[0], lift(s4)) & __builtin_amdgcn_perm(tab[3], tab[2], lift(s4 ^ 0x08080808u)) &
+               __builtin_amdgcn_perm(tab[5], tab[4], s4 ^ 0x10101010u);
+    };
+    auto step = [&](auto masked_tag, auto path_tag, int j, const int8_t *Knext, const int8_t *Vcur, const v16i (&sc)[RB], v16i (&sn)[RB],
                     const uint32_t (&lp)[NEL], uint32_t (&lc)[NEL], v4i (&pfp)[RB], v4i (&pfc)[RB]) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
+        constexpr int NP = decltype(path_tag)::value; // register pairs of the permute path; 0: tables in LDS
 #pragma unroll
         for (int sl = 0; sl < NSLOT; ++sl) {
             if (sl < HALF) {
@@ -273,14 +360,38 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
                 o[rb][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[cb], pfp[rb], o[rb][cb], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            if (sl < HALF) pack(masked_tag, j - 1, lp, (sl + HALF) * EPS, pfp);
-            else pack(masked_tag, j, lc, (sl - HALF) * EPS, pfc);
+            if (NP != 0) {
+                // index of each score (0 .. 8 NP after the short clip) as a byte: two byte permutes pair
+                // them up, a third joins the pairs, and four probabilities come out of the row's table
+                // registers.  IDX_TOP24: the index is the top byte of the scaled score and is picked up
+                // there; the other schemes deliver it in the low byte.
+                constexpr uint32_t PAIR = MODE == IDX_TOP24 ? 0x0c0c0703u : 0x0c0c0400u;
+                constexpr uint32_t CLIPPED = MODE == IDX_TOP24 ? (uint32_t)(8 * NP) << 24 : (uint32_t)(8 * NP);
+                uint32_t ivp = 0;
 #pragma unroll
-            for (int w = sl * EPS; w < (sl + 1) * EPS; ++w) {
-                const int rb = w / 16, e = w % 16;
-                // hidden keys may exceed the row max
-                const int c = MASKED ? min(max(sc[rb][e], ri[rb].bound), ri[rb].mx) : max(sc[rb][e], ri[rb].bound);
-                lc[w] = pt[rb * 1024 + ri[rb](c) * 32];
+                for (int w = sl * EPS; w < (sl + 1) * EPS; ++w) {
+                    const int rb = w / 16, e = w % 16;
+                    const int c = max(sc[rb][e], rif[rb].bound);
+                    uint32_t iv = MODE == IDX_TOP24 ? rif[rb].scaled(c) : rif[rb](c);
+                    if (MASKED) iv = visible(32 * j + acc_key(e, h), rb) ? iv : CLIPPED; // also covers hidden keys above the row max
+                    if (e % 2 == 0) {
+                        ivp = iv;
+                    } else {
+                        const uint32_t pair = __builtin_amdgcn_perm(iv, ivp, PAIR);
+                        if (e % 4 == 1) selw[rb] = pair;
+                        else pfc[rb][e / 4] = (int)lookup(path_tag, __builtin_amdgcn_perm(pair, selw[rb], 0x05040100u));
+                    }
+                }
+            } else {
+                if (sl < HALF) pack(masked_tag, j - 1, lp, (sl + HALF) * EPS, pfp);
+                else pack(masked_tag, j, lc, (sl - HALF) * EPS, pfc);
+#pragma unroll
+                for (int w = sl * EPS; w < (sl + 1) * EPS; ++w) {
+                    const int rb = w / 16, e = w % 16;
+                    // hidden keys may exceed the row max
+                    const int c = MASKED ? min(max(sc[rb][e], ri[rb].bound), ri[rb].mx) : max(sc[rb][e], ri[rb].bound);
+                    lc[w] = *(const __attribute__((address_space(3))) uint8_t *)(uintptr_t)ri[rb].row_addr(c, lane_base);
+                }
             }
             if (sl == HALF - 1) read_kf(Knext, kf); // the scores' MFMAs have all issued
             if (sl == NSLOT - 1) read_vf(Vcur, vf);
@@ -292,14 +403,14 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     // two further on (K tile T+1).  With PAR = T & 1: K tile T+2 replaces K tile T (read an iteration
     // ago) in Ks[PAR], V tile T+1 replaces V tile T-1 in Vs[PAR^1]; K tile T+1 is read from Ks[PAR^1]
     // and V tile T from Vs[PAR].
-    auto iteration = [&](auto masked_tag, int T, int8_t *Kdma, int8_t *Vdma, const int8_t *Krd, const int8_t *Vrd)
+    auto iteration = [&](auto masked_tag, auto path_tag, int T, int8_t *Kdma, int8_t *Vdma, const int8_t *Krd, const int8_t *Vrd)
                          __attribute__((always_inline)) {
         if (T + 2 <= ntiles) dma_k(T + 2, Kdma);
         if (T + 1 < ntiles) dma_v(T + 1, Vdma);
 #pragma unroll
         for (int u = 0; u < NSUB; u += 2) {
-            step(masked_tag, NSUB * T + u, Krd + u * SUB, Vrd + u * SUB, sA, sB, lB, lA, pfB, pfA);
-            step(masked_tag, NSUB * T + u + 1, Krd + (u + 1) * SUB, Vrd + (u + 1) * SUB, sB, sA, lA, lB, pfA, pfB);
+            step(masked_tag, path_tag, NSUB * T + u, Krd + u * SUB, Vrd + u * SUB, sA, sB, lB, lA, pfB, pfA);
+            step(masked_tag, path_tag, NSUB * T + u + 1, Krd + (u + 1) * SUB, Vrd + (u + 1) * SUB, sB, sA, lA, lB, pfA, pfB);
         }
         __syncthreads();
     };
@@ -330,35 +441,42 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     // count).  They run in pairs in a loop of their own, every buffer named statically (the compiler
     // then knows which direct-to-LDS load a fragment read depends on) and no branch inside the body;
     // the few remaining iterations take the masked code with the buffers chosen at run time.
+    // Every wave of the workgroup passes the same number of barriers whichever path it takes: one per
+    // iteration, ntiles in all.
     const int nfull_sub = CAUSAL ? min(L / 32, (qw0 + 1) / 32) : L / 32;
     const int nhot = min(nfull_sub / NSUB, ntiles);
-    int T = 0;
-    for (; T + 2 <= nhot; T += 2) {
-        iteration(std::false_type{}, T, Ks0, Vs1, Ks1, Vs0);
-        iteration(std::false_type{}, T + 1, Ks1, Vs0, Ks0, Vs1);
-    }
+    auto sweep = [&](auto path_tag) __attribute__((always_inline)) {
+        constexpr bool FAST = decltype(path_tag)::value != 0;
+        int T = 0;
+        for (; T + 2 <= nhot; T += 2) {
+            iteration(std::false_type{}, path_tag, T, Ks0, Vs1, Ks1, Vs0);
+            iteration(std::false_type{}, path_tag, T + 1, Ks1, Vs0, Ks0, Vs1);
+        }
 #pragma unroll 1
-    for (; T < ntiles; ++T) {
-        const bool odd = T & 1;
-        iteration(std::true_type{}, T, odd ? Ks1 : Ks0, odd ? Vs0 : Vs1, odd ? Ks0 : Ks1, odd ? Vs1 : Vs0);
-    }
-    // ---- drain: the second half of the last sub-tile's lookups (in lB) is packed, then its
-    // probabilities meet V (V^T fragments in vf)
+        for (; T < ntiles; ++T) {
+            const bool odd = T & 1;
+            iteration(std::true_type{}, path_tag, T, odd ? Ks1 : Ks0, odd ? Vs0 : Vs1, odd ? Ks0 : Ks1, odd ? Vs1 : Vs0);
+        }
+        // ---- drain: the last sub-tile's probabilities meet V (V^T fragments in vf); in the general path
+        // the second half of its lookups (in lB) is packed first
+        if (!FAST) {
 #pragma unroll
-    for (int sl = 0; sl < HALF; ++sl) pack(std::true_type{}, NSUB * ntiles - 1, lB, (sl + HALF) * EPS, pfB);
+            for (int sl = 0; sl < HALF; ++sl) pack(std::true_type{}, NSUB * ntiles - 1, lB, (sl + HALF) * EPS, pfB);
+        }
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
+        for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) o[rb][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[cb], pfB[rb], o[rb][cb], 0, 0, 0);
+            for (int rb = 0; rb < RB; ++rb) o[rb][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[cb], pfB[rb], o[rb][cb], 0, 0, 0);
+    };
+    if (path == 1) sweep(std::integral_constant<int, 1>{});
+    else if (path == 2) sweep(std::integral_constant<int, 2>{});
+    else if (path == 3) sweep(std::integral_constant<int, 3>{});
+    else sweep(std::integral_constant<int, 0>{});
 
     // ================================================================= epilogue (Sec. 3.2: requantization)
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int row = qw0 + 32 * rb + n;
-        if (row < rlo || row >= rhi) continue;
+    if (valid) {
         int8_t *Op = p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)(row - rlo) * p.os[2];
-        const HeadParams he = MODE == IDX_ROW64 ? row_hp(row) : hp;
-        const int64_t half = 1ll << (he.rq_shift - 1);
+        const int64_t half = 1ll << (hrow.rq_shift - 1);
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
 #pragma unroll
@@ -367,9 +485,10 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
                 uint32_t packed = 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int32_t acc = o[rb][cb][4 * g + r] + 128 * colsum[ch0 + r];
+                    // the general path fed P - 128 to the signed MFMA: add 128 times the column sums of V back
+                    const int32_t acc = o[0][cb][4 * g + r] + (path == 0 ? 128 * colsum[ch0 + r] : 0);
                     if (p.dbg_acc) p.dbg_acc[((int64_t)bh * LQ + (row - rlo)) * D + ch0 + r] = acc;
-                    int64_t v = ((int64_t)acc * he.rq_mult + half) >> he.rq_shift;
+                    int64_t v = ((int64_t)acc * hrow.rq_mult + half) >> hrow.rq_shift;
                     v = v > 127 ? 127 : (v < -127 ? -127 : v);
                     packed |= ((uint32_t)(int)v & 0xffu) << (8 * r);
                 }
@@ -388,11 +507,13 @@ int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
         // skipping the heads of the other
         FwdParams pf = p;
         pf.filter = 1;
-        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_FP32>), grid, block, 0, st, pf);
+        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_TOP24>), grid, block, 0, st, pf);
         hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_FP64>), grid, block, 0, st, pf);
         return (int)hipGetLastError();
     }
-    if (idx_mode == IDX_MAD24)
+    if (idx_mode == IDX_TOP24)
+        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_TOP24>), grid, block, 0, st, p);
+    else if (idx_mode == IDX_MAD24)
         hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_MAD24>), grid, block, 0, st, p);
     else if (idx_mode == IDX_MULHI24)
         hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_MULHI24>), grid, block, 0, st, p);
@@ -405,23 +526,15 @@ int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
     return (int)hipGetLastError();
 }
 
-template <int RB>
-int launch_rb(const FwdParams &p, int d, int idx_mode, hipStream_t st)
-{
-    if (d == 64) return p.causal ? launch_mode<64, RB, true>(p, idx_mode, st) : launch_mode<64, RB, false>(p, idx_mode, st);
-    if (d == 128) return p.causal ? launch_mode<128, RB, true>(p, idx_mode, st) : launch_mode<128, RB, false>(p, idx_mode, st);
-    return (int)hipErrorInvalidValue;
-}
-
 } // namespace
 
-// rows_per_wave is 32 or 64; p.n_qtiles must count tiles of 4 * rows_per_wave query rows, and the
-// V chunk sums in p.ws_colsum must be over chunks of as many keys; p.ws_row_max / ws_row_sum filled.
-int launch_sweep_c(const FwdParams &p, int d, int idx_mode, int rows_per_wave, void *stream)
+// 32 query rows per wave: p.n_qtiles must count tiles of 128 query rows, and the V chunk sums in
+// p.ws_colsum must be over chunks of as many keys; p.ws_row_max / ws_row_sum filled.
+int launch_sweep_c(const FwdParams &p, int d, int idx_mode, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    if (rows_per_wave == 32) return launch_rb<1>(p, d, idx_mode, st);
-    if (rows_per_wave == 64) return launch_rb<2>(p, d, idx_mode, st);
+    if (d == 64) return p.causal ? launch_mode<64, 1, true>(p, idx_mode, st) : launch_mode<64, 1, false>(p, idx_mode, st);
+    if (d == 128) return p.causal ? launch_mode<128, 1, true>(p, idx_mode, st) : launch_mode<128, 1, false>(p, idx_mode, st);
     return (int)hipErrorInvalidValue;
 }
 

@@ -20,12 +20,11 @@ def torch_mod():
     return torch
 
 
-# kernel variants: 0 = automatic choice; 1-3 = one launch (32 query rows per wave with 64-key tiles,
-# 64 rows per wave, 32 rows per wave with 32-key tiles); 4 = two launches (sweeps A+B, then sweep C)
-# with the phase-ordered kernels; 5 / 6 = software-pipelined sweep C with 32 / 64 rows per wave;
-# 7 / 8 = software-pipelined sweeps A+B with 64 / 32 rows per wave, and sweep C; 9 = the split-key
-# kernels (few query rows against many keys) wherever (Hq / Hkv) * L <= 31, else as 0
-@pytest.fixture(scope="module", params=[0, 1, 2, 3, 4, 5, 6, 7, 8, 9], ids=lambda v: f"variant{v}")
+# kernel variants: 0 = automatic choice; 1, 2 = one launch (32 / 64 query rows per wave); 4 = two
+# launches (sweeps A+B, then sweep C) with the phase-ordered kernels; 5 = the software-pipelined sweep C
+# with its short-table path; 9 = the split-key kernels (few query rows against many keys) wherever
+# (Hq / Hkv) * L <= 31, else as 0
+@pytest.fixture(scope="module", params=[0, 1, 2, 4, 5, 9], ids=lambda v: f"variant{v}")
 def ia(torch_mod, request):
     from paper_2511_21513_amd import binding
 
@@ -252,7 +251,7 @@ def test_stages_compose_to_the_forward(torch_mod, oracle):
     p = inputs.random_problem(21, 2, 4, 2, 300, 128, True)
     q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
     want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, None, causal=True)["out"]
-    for variant in (4, 5, 7):
+    for variant in (4, 5):
         ia = binding.IntAttn(device=0, variant=variant)
         out = torch.zeros_like(q)
         args, keep = ia.make_args(q, k, v, out, p.s_q, p.s_k, p.s_v, None, causal=True, per_head=False)
@@ -798,7 +797,7 @@ def _random_cases(n, seed):
         cases.append((int(rng.integers(1, 3)), g * Hkv, Hkv, lq, lk, int(rng.choice([64, 128])), causal,
                       int(rng.integers(0, 3)),           # scale mode: per tensor, per head, per block of rows
                       int(rng.choice([1, 3, 32, 50])),   # q_block (mode 2)
-                      int(rng.integers(0, 10)),          # kernel variant
+                      int(rng.choice([0, 1, 2, 4, 5, 9, 5, 0, 4, 1])),  # kernel variant
                       bool(rng.integers(0, 2)),          # with an output scale
                       float(rng.choice([1.0, 1.0, 0.05, 1e-3]))))  # multiplier on s_q: moves c_int between the schemes
     return cases
@@ -875,3 +874,46 @@ def test_parameter_cache_follows_the_scales(torch_mod, oracle):
         want = oracle.forward(p.q, p.k, p.v, s_q, sk, sv, so_, causal=True, per_head=per_head)["out"]
         assert int((got.cpu().numpy() != want).sum()) == 0
     ia.close()
+
+
+# ---------------------------------------------------------------- short-table path of the pipelined sweep C
+@pytest.mark.parametrize("case", [
+    # L, d, causal, spread, per_head: flat logits make the row sums large, so that only the first eight table
+    # entries of a row can give a nonzero probability; the thresholds reach every index-map scheme
+    (1500, 128, True, 0.6, False), (1500, 64, False, 0.6, True), (2048, 64, True, 1.0, False),
+    (900, 128, True, 0.35, False), (700, 128, False, 2.0, False),
+], ids=lambda c: "L{}d{}c{}s{}ph{}".format(c[0], c[1], int(c[2]), c[3], int(c[4])))
+def test_short_table_path_bit_exact(torch_mod, oracle, case):
+    """Rows whose sum of E_hat exceeds 510 * LUT_hat[8] (waves of such rows look probabilities up with a
+    byte permute and skip the offset of 128), rows below it, and waves and workgroups that mix both:
+    every tap and every output byte against the oracle, on diagonal (masked) and ragged tiles too."""
+    from paper_2511_21513_amd import binding
+
+    L, d, causal, spread, per_head = case
+    p = inputs.random_problem(77, 1, 4, 2, L, d, causal, per_head=per_head, spread=spread)
+    want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, None, causal=causal, per_head=per_head, taps=True, threads=8)
+    n_short = int((want["row_sum"] > 510 * 46).sum())
+    print(f"case {case}: {n_short} of {want['row_sum'].size} rows above the short-table threshold", flush=True)
+    if spread < 2.0:
+        assert n_short > want["row_sum"].size // 5  # the case does exercise the path
+    ia = binding.IntAttn(device=0, variant=5)
+    check_full(torch_mod, ia, oracle, p)
+    check_full(torch_mod, ia, oracle, p, inputs.calibrated_out_scale(p), taps=False)
+    ia.close()
+
+
+def test_short_table_path_on_the_headline_distribution(torch_mod, oracle):
+    """Four query heads of the long-context GQA workload at a ragged length: small threshold (the
+    24-bit index maps), late rows on the short-table path, early rows on the general one."""
+    from paper_2511_21513_amd import binding
+
+    p = inputs.make_problem("c4_gqa_prefill_8k", Hq=4, Hkv=1, L=5000)
+    s_o = inputs.calibrated_out_scale(p, sample_rows=16)
+    for variant in (0, 5):
+        ia = binding.IntAttn(device=0, variant=variant)
+        check_full(torch_mod, ia, oracle, p, s_o, taps=False)
+        ia.close()
+    ia = binding.IntAttn(device=0, variant=5)
+    got = check_full(torch_mod, ia, oracle, p)
+    ia.close()
+    assert int((got["row_sum"] > 510 * 46).sum()) > got["row_sum"].size // 4

@@ -36,7 +36,8 @@
  * All entry points return 0 on success or a negative INTATTN_ERR_* code; none throws or aborts.
  * A forward call enqueues its kernels and returns; it allocates device memory (hipMalloc / hipFree,
  * which wait for the device) only when the problem needs a larger workspace or table than any call
- * before it on this context did -- intattn_reserve does that ahead of time.  Small per-head tables reach the device through pinned
+ * before it on this context did -- intattn_reserve does that ahead of time, and
+ * intattn_forward_noalloc never allocates.  Small per-head tables reach the device through pinned
  * staging buffers of the context (two of them; a third upload while two are still in flight waits
  * for the oldest).  intattn_dynamic_status reads a word back and so waits for its copy.
  * A context is bound to one device and is not thread-safe; calls that share a context must be
@@ -120,7 +121,7 @@ INTATTN_API int intattn_create(intattn_ctx **out, const intattn_config *cfg);
  * the default stream) and returns without waiting for it.  The context owns a device workspace
  * (8 bytes per query row plus d int32 per 128 keys and KV head) that the first call allocates and
  * a later, larger call re-allocates (hipMalloc / hipFree wait for the device and are not for use
- * under graph capture: call intattn_reserve first); the
+ * under graph capture: call intattn_reserve first, or use intattn_forward_noalloc); the
  * kernels of a call pass intermediate results through it, so calls on ONE context must not
  * overlap in time (same stream, or ordered by the caller); use one context per concurrent stream. */
 INTATTN_API int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
@@ -130,6 +131,20 @@ INTATTN_API int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void
  * never wait for the device.  dynamic != 0: for intattn_forward_dynamic (scale pointers are not read
  * either way).  May call hipMalloc / hipFree; launches nothing. */
 INTATTN_API int intattn_reserve(intattn_ctx *ctx, const intattn_args *args, int32_t dynamic);
+
+/* intattn_forward for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments (host scales), same kernels, same
+ * bytes out, but the workspace -- row maxima and row sums between the launches, V column sums, the
+ * partial results of the split-key kernels -- and the per-head parameter table live in a static
+ * device array of INTATTN_NOALLOC_SCRATCH_BYTES that the library's image holds on every GPU it runs
+ * on.  Calls no hipMalloc / hipFree.  A problem that needs more workspace than the array holds (8
+ * bytes per query row of every (batch, head) plus 4 d bytes per 128 keys of every (batch, KV head),
+ * or more than 512 query heads with per-head scales) is rejected with INTATTN_ERR_UNSUPPORTED and a
+ * message naming both sizes.  The array is shared by every context on the GPU and keeps the last
+ * call's contents (everything a call reads it has written first): calls that overlap in time on one
+ * GPU race -- order them on one stream. */
+#define INTATTN_NOALLOC_SCRATCH_BYTES (4u << 20)
+INTATTN_API int intattn_forward_noalloc(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
 
 /* Timing hook for benchmarks, not part of the serving interface: the forward cut at the point where
  * the row maxima and row sums of IndexSoftmax (Sec. 3.1-3.2) are complete, so that the two launches of

@@ -20,6 +20,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = 0, -1, -2, -3, -4
 SYMBOLS = (
     "intattn_create",
     "intattn_forward",
+    "intattn_forward_noalloc",
     "intattn_reserve",
     "intattn_forward_stage",
     "intattn_forward_dynamic",
@@ -104,6 +105,8 @@ def load() -> ctypes.CDLL:
         lib.intattn_create.restype = i32
         lib.intattn_forward.argtypes = [vp, ctypes.POINTER(Args), vp]
         lib.intattn_forward.restype = i32
+        lib.intattn_forward_noalloc.argtypes = [vp, ctypes.POINTER(Args), vp]
+        lib.intattn_forward_noalloc.restype = i32
         lib.intattn_reserve.argtypes = [vp, ctypes.POINTER(Args), i32]
         lib.intattn_reserve.restype = i32
         lib.intattn_forward_stage.argtypes = [vp, ctypes.POINTER(Args), vp, i32]
@@ -254,6 +257,12 @@ class IntAttn:
     def forward_args(self, args: Args, stream: int = 0, quantonly: bool = False):
         fn = self._lib.intattn_forward_quantonly if quantonly else self._lib.intattn_forward
         rc = fn(self._ctx, ctypes.byref(args), ctypes.c_void_p(stream))
+        if rc != OK:
+            raise IntAttnError(rc, self.last_error())
+
+    def forward_noalloc_args(self, args: Args, stream: int = 0):
+        """intattn_forward_noalloc: the forward with its workspace in the library's static device array."""
+        rc = self._lib.intattn_forward_noalloc(self._ctx, ctypes.byref(args), ctypes.c_void_p(stream))
         if rc != OK:
             raise IntAttnError(rc, self.last_error())
 

@@ -17,6 +17,16 @@
 
 using namespace intattn;
 
+// Workspace of intattn_forward_noalloc: one array per GPU in the library's image.  The name below is
+// a host-side stand-in, not a device address: every use goes through the pointer that
+// hipGetSymbolAddress returned for the device at hand (g_scratch_ptr).
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)INTATTN_NOALLOC_SCRATCH_BYTES;
+constexpr size_t STATIC_TABLE_BYTES = 16384; // head of the scratch: per-head parameter table (512 heads)
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void *g_scratch_ptr[MAX_DEVICES] = {nullptr};
+static std::mutex g_scratch_mu;
+
 // Pinned host staging for small host-to-device uploads (per-head tables): the bytes are copied here
 // first, so the asynchronous copy never reads memory that the caller, or a returning function, owns.
 struct Staging {
@@ -465,6 +475,7 @@ struct RunMode {
     bool comparator = false; // the conventional INT8 pipeline instead of the integer one
     int stage = 0;           // 0: everything; 1 / 2: the two launches of the tiled path separately
     bool dynamic = false;    // the scale pointers of the arguments are DEVICE memory: parameters derived by a kernel
+    bool no_alloc = false;   // workspace and per-head table in the static device array; nothing is allocated
     bool reserve = false;    // allocate what the call would need and return without deriving or launching
 };
 
@@ -518,22 +529,43 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
     if (guard.status != hipSuccess) return hip_fail(ctx, guard.status, "hipSetDevice");
     hipStream_t st = (hipStream_t)stream;
 
-    // device memory of the call: the context's, allocated on demand
+    // device memory of the call: the context's (allocated on demand), or the static array of this GPU
+    unsigned char *static_base = nullptr;
+    if (rm.no_alloc) {
+        if (ctx->device >= MAX_DEVICES || !(static_base = (unsigned char *)g_scratch_ptr[ctx->device]))
+            return fail(ctx, INTATTN_ERR_HIP, "the static workspace of this device was not resolved at intattn_create");
+    }
     HeadParams *d_hp = nullptr; // per-head parameter table in use
     auto get_tables = [&](int n) -> int {
+        if (rm.no_alloc) {
+            if ((size_t)n * sizeof(HeadParams) > STATIC_TABLE_BYTES)
+                return fail(ctx, INTATTN_ERR_UNSUPPORTED, "intattn_forward_noalloc: more than 512 query heads with per-head scales");
+            d_hp = (HeadParams *)static_base;
+            return INTATTN_OK;
+        }
         const int r = ensure_tables(ctx, n);
         d_hp = ctx->d_hp;
         return r;
     };
     int32_t *d_ws = nullptr; // kernel workspace in use
     auto get_ws = [&](size_t n_int32) -> int {
+        if (rm.no_alloc) {
+            if (n_int32 * sizeof(int32_t) > STATIC_SCRATCH_BYTES - STATIC_TABLE_BYTES)
+                return fail(ctx, INTATTN_ERR_UNSUPPORTED,
+                            "intattn_forward_noalloc: the problem needs " + std::to_string(n_int32 * sizeof(int32_t)) +
+                                " bytes of workspace, the static array holds " + std::to_string(STATIC_SCRATCH_BYTES - STATIC_TABLE_BYTES));
+            d_ws = (int32_t *)(static_base + STATIC_TABLE_BYTES);
+            return INTATTN_OK;
+        }
         const int r = ensure_workspace(ctx, n_int32);
         d_ws = ctx->d_ws;
         return r;
     };
-    // the table the kernels read: uploaded only when it differs from what the context's copy holds
-    // (calls on a context are ordered by the caller)
+    // the table the kernels read: the context's copy is uploaded only when it differs from what it holds
+    // (calls on a context are ordered by the caller); the static array is shared by every context on the
+    // GPU, so its table is written on every call
     auto put_table = [&](const std::vector<HeadParams> &tab) -> int {
+        if (rm.no_alloc) return upload(ctx, d_hp, tab.data(), tab.size() * sizeof(HeadParams), st, "hipMemcpyAsync(head params)");
         const bool same = ctx->hp_host.size() == tab.size() &&
                           std::memcmp(ctx->hp_host.data(), tab.data(), tab.size() * sizeof(HeadParams)) == 0;
         if (same) return INTATTN_OK;
@@ -571,6 +603,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
     const bool decode = decode_ok && (ctx->variant == 9 || (ctx->variant == 0 && p.Lk >= 1024));
 
     if (dynamic) {
+        if (rm.no_alloc) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "intattn_forward_noalloc takes host scales");
         rc = get_tables(a->Hq);
         if (rc) return rc;
         if (a->Hq > ctx->status_cap) {
@@ -748,8 +781,17 @@ int intattn_create(intattn_ctx **out, const intattn_config *cfg)
             if (e == hipSuccess) e = hipHostMalloc((void **)&sg.host, STAGING_BYTES, hipHostMallocDefault);
             if (e == hipSuccess) e = hipEventCreateWithFlags(&sg.done, hipEventDisableTiming);
         }
+        // this GPU's copy of the static workspace of intattn_forward_noalloc
+        if (e == hipSuccess && ctx->device < MAX_DEVICES) {
+            std::lock_guard<std::mutex> lock(g_scratch_mu);
+            if (!g_scratch_ptr[ctx->device]) {
+                void *ptr = nullptr;
+                e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+                if (e == hipSuccess) g_scratch_ptr[ctx->device] = ptr;
+            }
+        }
         if (e != hipSuccess) {
-            const int rc = hip_fail(nullptr, e, "intattn_create (staging buffers)");
+            const int rc = hip_fail(nullptr, e, "intattn_create (staging buffers / static workspace)");
             intattn_destroy(ctx);
             return rc;
         }
@@ -761,6 +803,13 @@ int intattn_create(intattn_ctx **out, const intattn_config *cfg)
 int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void *hip_stream)
 {
     return run(ctx, args, hip_stream, RunMode{});
+}
+
+int intattn_forward_noalloc(intattn_ctx *ctx, const intattn_args *args, void *hip_stream)
+{
+    RunMode rm;
+    rm.no_alloc = true;
+    return run(ctx, args, hip_stream, rm);
 }
 
 int intattn_reserve(intattn_ctx *ctx, const intattn_args *args, int32_t dynamic)

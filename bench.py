@@ -27,46 +27,104 @@ if ROOT not in sys.path:
 
 INT8_MFMA_PEAK_TOPS = 5000.0  # MI355X dense int8 matrix peak, 5.0 POP/s
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the dominant kernel (sweep C) measured with rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE, each scaled by the same counter's reading for a plain 1 GiB device copy
-# (profiles/sweep_c_kernel_c4_gqa_prefill_8k.md).  Only workloads that were profiled have an entry.
-MEASURED_HBM_TRAFFIC_BYTES = {"c4_gqa_prefill_8k": 54.85e6 + 33.55e6,
-                              # --decode, all four kernels of a step (profiles/decode_kernels_c4_gqa_shape_b32_lkv8192.md)
-                              "decode:c4_gqa_prefill_8k:B32": 633e6}
+# Lane operations the vector ALUs can issue: 64 per clock and compute unit (four SIMDs, each a 64-wide wave
+# instruction over four clocks), 256 compute units, 2.4 GHz peak engine clock.
+VALU_PEAK_LANE_OPS = 64 * 256 * 2.4e9
+CSRC = os.path.join(ROOT, "paper_2511_21513_amd", "csrc")
+
+
+def kernel_source_hash():
+    """SHA-256 over the kernel sources, in name order: what a stored counter reading is valid for."""
+    import hashlib
+
+    h = hashlib.sha256()
+    for fn in sorted(os.listdir(CSRC)):
+        if fn.endswith((".hip", ".h", ".cpp")):
+            with open(os.path.join(CSRC, fn), "rb") as f:
+                h.update(fn.encode() + b"\0" + f.read())
+    return h.hexdigest()
+
+
+def stored_counters(tag):
+    """`key: number` lines of profiles/counters_<tag>.md (rocprofv3 --pmc readings that a timing run
+    cannot take itself), or {} when there is no such file or it was taken on other kernel sources."""
+    path = os.path.join(ROOT, "profiles", f"counters_{tag}.md")
+    if not os.path.exists(path):
+        return {}
+    vals = {}
+    with open(path) as f:
+        for line in f:
+            key, sep, val = line.strip().lstrip("-* ").partition(":")
+            if sep and key and " " not in key:
+                vals[key] = val.strip()
+    if vals.get("kernel_source_sha256") != kernel_source_hash():
+        return {}
+    out = {}
+    for key, val in vals.items():
+        try:
+            out[key] = float(val)
+        except ValueError:
+            out[key] = val
+    return out
+
+
+def host_cpu():
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return {"model": model, "nproc": os.cpu_count() or 1, "usable": usable}
+
 
 ALIASES = {"c1": "c1_single_head", "c2": "c2_vit_b16", "c3": "c3_llm_prefill_2k",
            "c4": "c4_gqa_prefill_8k", "c5": "c5_batched_prefill_4k"}
 
 
-def cpu_baseline(p, budget_heads):
-    """The oracle as it stands on this host's cores, over whole heads of the same workload."""
-    import oracle
-
-    threads = min(16, os.cpu_count() or 1)
-    n_heads = min(p.B * p.Hq, budget_heads)
-    # one batch entry's first n_heads query heads (with their KV heads), all rows
-    t0 = time.perf_counter()
+def cpu_baseline(p, s_o, budget_heads, gpu_out=None):
+    """The oracle as it stands on this host's cores, over whole heads of the same workload with the
+    same output scale; its bytes are compared with the timed GPU output where one is given."""
     import numpy as np
 
+    import oracle
+
+    cpu = host_cpu()
+    n_heads = min(p.B * p.Hq, budget_heads)
+    # the first batch entries' first n_heads query heads (with their KV heads), all rows
     b_cnt = (n_heads + p.Hq - 1) // p.Hq
     hq_cnt = min(n_heads, p.Hq)
     g = p.Hq // p.Hkv
     kv_cnt = (hq_cnt + g - 1) // g
+    if hq_cnt % kv_cnt != 0:  # keep the group structure intact
+        return None
+    threads = max(1, min(16, cpu["usable"], b_cnt * hq_cnt))  # the oracle fans (batch, head) pairs over threads
     q = np.ascontiguousarray(p.q[:b_cnt, :hq_cnt])
     k = np.ascontiguousarray(p.k[:b_cnt, :kv_cnt])
     v = np.ascontiguousarray(p.v[:b_cnt, :kv_cnt])
     sq = p.s_q[:hq_cnt] if p.per_head else p.s_q
     sk = p.s_k[:kv_cnt] if p.per_head else p.s_k
     sv = p.s_v[:kv_cnt] if p.per_head else p.s_v
-    if hq_cnt % kv_cnt != 0:  # keep the group structure intact
-        return None
+    so = s_o[:hq_cnt] if (p.per_head and s_o is not None) else s_o
     t0 = time.perf_counter()
-    oracle.forward(q, k, v, sq, sk, sv, None, causal=p.causal, per_head=p.per_head, threads=threads)
+    want = oracle.forward(q, k, v, sq, sk, sv, so, causal=p.causal, per_head=p.per_head, threads=threads)["out"]
     dt = time.perf_counter() - t0
     ops = 4 * p.d * p.pairs * b_cnt * hq_cnt
-    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": min(threads, b_cnt * hq_cnt), "kind": "oracle",
-            "sample": f"{b_cnt * hq_cnt} of {p.B * p.Hq} (batch, head) pairs, all rows, {dt:.1f} s",
-            "seconds": dt}
+    res = {"value": ops / dt / 1e12, "unit": "TOPS", "cores": threads, "kind": "oracle",
+           "sample": f"{b_cnt * hq_cnt} of {p.B * p.Hq} (batch, head) pairs, all rows, {dt:.1f} s",
+           "seconds": dt, "host_cpu": cpu["model"], "host_nproc": cpu["nproc"], "host_usable_cores": cpu["usable"]}
+    if gpu_out is not None:
+        got = gpu_out[:b_cnt, :hq_cnt].cpu().numpy()
+        res["bytes_compared_with_timed_output"] = int(want.size)
+        res["parity_mismatching_bytes"] = int((got != want).sum())
+    return res
 
 
 def quantizer_bench(a, name, dev):
@@ -256,7 +314,9 @@ def decode_bench(a, name, dev):
     bs = sorted(set([0, B - 1] + list(range(0, B, max(1, B // 6)))))
     qs, ks, vs = (x[bs].cpu().numpy() for x in (q, k, v))
     t0 = time.perf_counter()
-    want = oracle.forward(qs, ks, vs, s_q, s_k, s_v, None, causal=True, per_head=True, threads=min(16, os.cpu_count() or 1))["out"]
+    cpu = host_cpu()
+    threads = max(1, min(16, cpu["usable"], len(bs) * Hq))
+    want = oracle.forward(qs, ks, vs, s_q, s_k, s_v, None, causal=True, per_head=True, threads=threads)["out"]
     cpu_s = time.perf_counter() - t0
     mism = int((out[bs].cpu().numpy() != want).sum())
     res = {"metric": "decode attention (one token per sequence), algorithmic GB/s", "value": gbps, "unit": "GB/s",
@@ -267,11 +327,11 @@ def decode_bench(a, name, dev):
            "tokens_per_s": B / (ms * 1e-3),
            "parity_mismatching_bytes": mism,
            "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBS,
-                        "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(f"decode:{name}:B{B}"),
+                        "traffic": stored_counters(f"decode_{name}_b{B}").get("step_hbm_bytes"),
                         "kernel": "decode_scores_kernel + decode_lookup_kernel + decode_pv_kernel + decode_finish_kernel",
                         "algorithmic_bytes_per_step": alg_bytes},
            "cpu_baseline": {"value": (ks.nbytes + vs.nbytes + 2 * qs.nbytes) / cpu_s / 1e9, "unit": "GB/s",
-                            "cores": min(16, os.cpu_count() or 1, len(bs) * Hq), "kind": "oracle",
+                            "cores": threads, "kind": "oracle", "host_cpu": cpu["model"], "host_nproc": cpu["nproc"],
                             "sample": f"{len(bs)} of {B} sequences, all heads, {cpu_s:.2f} s"}}
     ia.close()
     print(json.dumps(res))
@@ -280,8 +340,8 @@ def decode_bench(a, name, dev):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -344,29 +404,34 @@ def main():
     stream = torch.cuda.current_stream(dev).cuda_stream
 
     def timed(fn, steps, warmup):
+        """`steps` back-to-back calls between two synchronizations, an event before each and one after
+        the last: (mean ms per step over the whole bracket, wall-clock ms per step, median ms of a step)."""
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         t0 = time.perf_counter()
-        ev0.record()
-        for _ in range(steps):
+        for i in range(steps):
+            evs[i].record()
             fn()
-        ev1.record()
+        evs[steps].record()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-        return ev0.elapsed_time(ev1) / steps, wall_ms
+        each = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(steps))
+        median = each[steps // 2] if steps % 2 else 0.5 * (each[steps // 2 - 1] + each[steps // 2])
+        return evs[0].elapsed_time(evs[steps]) / steps, wall_ms, median
 
-    ms, wall_ms = timed(lambda: ia.forward_args(args, stream), a.steps, a.warmup)
+    ms, wall_ms, median_ms = timed(lambda: ia.forward_args(args, stream), a.steps, a.warmup)
     tops = p.ops / (ms * 1e-3) / 1e12
+    out_timed = out.clone()  # later calls (stages, comparator) write `out` again
 
     # The step is up to three kernels on one stream: V column sums, sweeps A+B, sweep C.  Sweep C is
     # the dominant one and executes every counted operation (it recomputes Q.K^T and does P.V), so
     # the roofline object is its: timed alone through the staged entry point, same HIP events.
     try:
         ia.forward_stage(args, 1, stream)
-        ab_ms, _ = timed(lambda: ia.forward_stage(args, 1, stream), a.steps, 1)
-        c_ms, _ = timed(lambda: ia.forward_stage(args, 2, stream), a.steps, 1)
+        ab_ms = timed(lambda: ia.forward_stage(args, 1, stream), a.steps, 1)[0]
+        c_ms = timed(lambda: ia.forward_stage(args, 2, stream), a.steps, 1)[0]
         kernels = {"colsum_kernel+sweeps_a_b": ab_ms, "sweep_c_kernel": c_ms}
         dom_name, dom_ms = "sweep_c_kernel", c_ms
     except binding.IntAttnError:
@@ -380,7 +445,26 @@ def main():
     rows = np.asarray([0, 1, p.L // 2, p.L - 1], dtype=np.int32)
     want = oracle.rows(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, s_o, b=p.B - 1, hq=p.Hq - 1, rows=rows, causal=p.causal,
                        per_head=p.per_head)["out"]
-    mism = int((out[p.B - 1, p.Hq - 1].cpu().numpy()[rows] != want).sum())
+    mism = int((out_timed[p.B - 1, p.Hq - 1].cpu().numpy()[rows] != want).sum())
+
+    # Readings a timing run cannot take itself (rocprofv3 --pmc), stored with the hash of the kernel
+    # sources they were taken on; absent or stale -> null.
+    ctr = stored_counters(name) if (a.variant == 0 and not a.batch) else {}
+    traffic = None
+    if "sweep_c_fetch_bytes_per_launch" in ctr and dom_name == "sweep_c_kernel":
+        traffic = ctr["sweep_c_fetch_bytes_per_launch"] + ctr["sweep_c_write_bytes_per_launch"]
+    # The IndexSoftmax stage is element-wise integer work on the vector ALUs: its roofline is the lane
+    # operations per second the chip can issue.  Lane operations = 64 x vector instructions issued
+    # (SQ_INSTS_VALU, matrix instructions excluded), per score element of the causal triangle.
+    score_elems = p.pairs * p.B * p.Hq
+    valu = {"bound": "alu", "peak": VALU_PEAK_LANE_OPS / 1e12, "unit": "T lane-op/s", "score_elements_per_step": score_elems,
+            "lane_ops_per_score": None, "achieved": None, "frac": None}
+    if "step_valu_insts" in ctr:
+        lane_ops = 64.0 * ctr["step_valu_insts"]
+        valu.update({"lane_ops_per_score": lane_ops / score_elems,
+                     "lane_ops_per_score_by_kernel": {k[:-len("_valu_insts")]: 64.0 * v / score_elems for k, v in ctr.items()
+                                                      if k.endswith("_valu_insts") and k != "step_valu_insts"},
+                     "achieved": lane_ops / (ms * 1e-3) / 1e12, "frac": lane_ops / (ms * 1e-3) / VALU_PEAK_LANE_OPS})
 
     res = {
         "metric": "int8 attention TOPS (QK^T+PV) + % of int8 MFMA peak at L=8192",
@@ -392,31 +476,37 @@ def main():
                    "lut_bits": 5, "clip": 6.6, "variant": a.variant},
         "pct_of_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
         "wall_ms_per_step": wall_ms,
+        "median_ms_per_step": median_ms, "value_at_median": p.ops / (median_ms * 1e-3) / 1e12,
         "sampled_parity_mismatching_bytes": mism,
         "roofline": {"bound": "mfma", "achieved": dom_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": dom_tops / INT8_MFMA_PEAK_TOPS, "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(name),
+                     "frac": dom_tops / INT8_MFMA_PEAK_TOPS, "traffic": traffic,
                      "kernel": dom_name, "kernel_ms_per_launch": dom_ms, "counted_ops_per_launch": p.ops,
                      "whole_step_frac": tops / INT8_MFMA_PEAK_TOPS, "kernels_ms": kernels,
                      "hbm_algorithmic_bytes_per_launch": p.algorithmic_bytes,
-                     "hbm_algorithmic_GBps": p.algorithmic_bytes / (ms * 1e-3) / 1e9},
+                     "hbm_algorithmic_GBps": p.algorithmic_bytes / (ms * 1e-3) / 1e9,
+                     "counters_from": ctr.get("source")},
+        "valu_roofline": valu,
     }
     # the same step with the scales in device memory (parameters derived by a kernel, no host read)
     dscales = [torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(dev) for x in (p.s_q, p.s_k, p.s_v, s_o)]
     out_d = torch.empty_like(q)
     dargs, dkeep = ia.make_args(q, k, v, out_d, *dscales, causal=p.causal, per_head=p.per_head, device_scales=True)
-    dms, _ = timed(lambda: ia.forward_dynamic_args(dargs, stream), a.steps, 2)
+    dms = timed(lambda: ia.forward_dynamic_args(dargs, stream), a.steps, 2)[0]
     res["device_scales"] = {"entry": "intattn_forward_dynamic", "ms_per_step": dms, "TOPS": p.ops / (dms * 1e-3) / 1e12,
-                            "bytes_differing_from_host_scale_output": int((out_d != out).sum().item()),
+                            "bytes_differing_from_host_scale_output": int((out_d != out_timed).sum().item()),
                             "status": ia.dynamic_status()}
     if not a.no_comparator:
         try:
-            cms, _ = timed(lambda: ia.forward_args(args, stream, quantonly=True), max(3, a.steps // 3), 2)
+            cms = timed(lambda: ia.forward_args(args, stream, quantonly=True), max(3, a.steps // 3), 2)[0]
             res["comparator"] = {"kind": "fused conventional INT8 pipeline (dequant -> fp32 softmax -> requant)",
                                  "ms_per_step": cms, "speedup_of_intattention": cms / ms}
         except binding.IntAttnError as e:
             res["comparator"] = {"error": str(e)}
     if not a.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(p, a.cpu_heads)
+        res["cpu_baseline"] = cpu_baseline(p, s_o, a.cpu_heads, gpu_out=out_timed)
+        if res["cpu_baseline"] and "parity_mismatching_bytes" in res["cpu_baseline"]:
+            res["parity_mismatching_bytes"] = res["cpu_baseline"]["parity_mismatching_bytes"]
+            res["parity_bytes_compared"] = res["cpu_baseline"]["bytes_compared_with_timed_output"]
     ia.close()
     print(json.dumps(res))
 

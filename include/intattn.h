@@ -65,7 +65,7 @@ typedef struct intattn_ctx intattn_ctx; /* opaque; owned by the library */
 typedef struct {
     int32_t device;   /* HIP device ordinal the context is bound to; -1 = host-only context
                          (parameter derivation and LUT only; forward calls are rejected)     */
-    int32_t lut_bits; /* b of Sec. 3.1: the table has 2^b entries; 1..5; paper default 5     */
+    int32_t lut_bits; /* b of Sec. 3.1: the table has 2^b entries; 1..6; paper default 5     */
     double clip;      /* c of Sec. 3.1: clip threshold in logit units; > 0; paper default 6.6 */
     int32_t variant;  /* kernel variant: 0 = automatic choice.  Tuning knobs, all bit-identical: 1, 2 = one
                          launch with 32 / 64 query rows per wave; 4, 5 = two launches (row max and row

@@ -174,8 +174,8 @@ class IntAttn:
         return (self._lib.intattn_last_error(self._ctx) or b"").decode()
 
     def lut(self) -> np.ndarray:
-        buf = np.zeros(32, dtype=np.uint8)
-        n = self._lib.intattn_get_lut(self._ctx, buf.ctypes.data_as(ctypes.c_void_p), 32)
+        buf = np.zeros(64, dtype=np.uint8)
+        n = self._lib.intattn_get_lut(self._ctx, buf.ctypes.data_as(ctypes.c_void_p), 64)
         if n < 0:
             raise IntAttnError(n, "intattn_get_lut")
         return buf[:n].copy()

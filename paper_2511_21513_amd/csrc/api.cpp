@@ -41,7 +41,7 @@ struct intattn_ctx {
     int lut_bits = 5;
     double clip = 6.6;
     int variant = 0;
-    uint8_t lut[32] = {0};
+    uint8_t lut[64] = {0};
     // device-side per-head tables (allocated on first per-head call, grown on demand)
     HeadParams *d_hp = nullptr;
     float *d_alpha = nullptr, *d_svso = nullptr;
@@ -589,11 +589,12 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
     p.causal = a->causal;
     p.group = a->Hq / a->Hkv;
     p.top = (1 << ctx->lut_bits) - 1;
-    const int variant = fwd_choose_variant(ctx->variant, a->B, a->Hq, a->L);
+    int variant = fwd_choose_variant(ctx->variant, a->B, a->Hq, a->L);
+    if (variant == 5 && ctx->lut_bits > 5) variant = 4; // the pipelined sweep C holds 32-entry tables; same tiling otherwise
     const int rows_per_block = comparator ? 128 : fwd_rows_per_block(variant);
     p.n_qtiles = fwd_row_tiles(p.row_lo, p.L, rows_per_block);
     p.n_chunks = (p.Lk + rows_per_block - 1) / rows_per_block;
-    std::memcpy(p.lut, ctx->lut, 32);
+    std::memcpy(p.lut, ctx->lut, 64);
     p.dbg_row_max = a->dbg_row_max; p.dbg_row_sum = a->dbg_row_sum; p.dbg_acc = a->dbg_acc;
 
     // Few query rows against many keys: the split-key kernels (all query heads of a KV head, times
@@ -751,7 +752,7 @@ int intattn_create(intattn_ctx **out, const intattn_config *cfg)
 {
     if (!out || !cfg) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "out and cfg must be non-NULL");
     *out = nullptr;
-    if (cfg->lut_bits < 1 || cfg->lut_bits > 5) return fail(nullptr, INTATTN_ERR_UNSUPPORTED, "lut_bits must be in 1..5");
+    if (cfg->lut_bits < 1 || cfg->lut_bits > 6) return fail(nullptr, INTATTN_ERR_UNSUPPORTED, "lut_bits must be in 1..6");
     if (!(cfg->clip > 0.0) || !std::isfinite(cfg->clip)) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "clip must be finite and > 0");
     if (!fwd_variant_known(cfg->variant)) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "unknown kernel variant");
     if (cfg->reserved != 0) return fail(nullptr, INTATTN_ERR_INVALID_ARG, "reserved must be 0");
@@ -880,7 +881,7 @@ int intattn_index_softmax(intattn_ctx *ctx, const intattn_softmax_args *a, void 
     p.rows_per_matrix = a->causal ? a->rows_per_matrix : 1;
     p.causal = a->causal;
     p.top = (1 << ctx->lut_bits) - 1;
-    std::memcpy(p.lut, ctx->lut, 32);
+    std::memcpy(p.lut, ctx->lut, 64);
     // the cheapest exact index map for this threshold
     p.hp.c_int = a->c_int;
     typedef bool (*finder)(uint32_t, uint32_t, HeadParams *);

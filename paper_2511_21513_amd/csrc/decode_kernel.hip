@@ -159,12 +159,12 @@ __global__ __launch_bounds__(NT) void decode_lookup_kernel(const FwdParams p)
     __shared__ int32_t row_i[32];        // query row of packed row r
     __shared__ HeadParams row_hp[32];    // its head's parameters
     __shared__ uint32_t sums[32];
-    __shared__ uint32_t lut_lds[8];
+    __shared__ uint32_t lut_lds[16];
     const int tid = threadIdx.x;
     const int chunk = blockIdx.x, grp = blockIdx.y, b = grp / p.Hkv, kvh = grp % p.Hkv;
     const int R = p.dec_rows, nt32 = p.dec_nt32, nt = nt32 / 4;
     const int t0 = chunk * p.dec_tpw, t1 = min(t0 + p.dec_tpw, nt);
-    if (tid < 8) lut_lds[tid] = p.lut[tid];
+    if (tid < 16) lut_lds[tid] = p.lut[tid];
     if (tid < R) {
         const RowOf ro = row_of(p, kvh, tid);
         row_i[tid] = ro.i;
@@ -189,7 +189,7 @@ __global__ __launch_bounds__(NT) void decode_lookup_kernel(const FwdParams p)
         uint32_t w = 0, sum = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            uint32_t idx = 32u; // hidden key: probability 0
+            uint32_t idx = 64u; // hidden key: probability 0 (one past the largest table, 2^6 entries)
             if (key_visible(p, key0 + acc_key(4 * g + j, h), ri)) {
                 // Delta = max - score (Sec. 3.1), clipped at c_int (Eq. int_clipping), index map, Eq. gather16
                 const int64_t delta = (int64_t)mx - (int64_t)sc[j];
@@ -214,15 +214,15 @@ __global__ __launch_bounds__(NT) void decode_pv_kernel(const FwdParams p)
     __shared__ __attribute__((aligned(1024))) int8_t Vs0[BK * D];
     __shared__ __attribute__((aligned(1024))) int8_t Vs1[BK * D];
     __shared__ int32_t row_sum[32];
-    __shared__ uint32_t lut_lds[8];
-    __shared__ uint8_t PT[31][36]; // per packed row: byte P - 128 of table index 0..32 (32 = hidden key, P = 0)
+    __shared__ uint32_t lut_lds[16];
+    __shared__ uint8_t PT[31][68]; // per packed row: byte P - 128 of table index 0..64 (64 = hidden key, P = 0)
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 31, h = lane >> 5;
     const int chunk = blockIdx.x, grp = blockIdx.y, b = grp / p.Hkv, kvh = grp % p.Hkv;
     const int R = p.dec_rows, nt32 = p.dec_nt32, nt = nt32 / 4;
     const int t0 = chunk * p.dec_tpw, t1 = min(t0 + p.dec_tpw, nt);
     const int8_t *Vp = p.v + (int64_t)b * p.vs[0] + (int64_t)kvh * p.vs[1];
     stage_tile<D, true>(Vp, p.vs[2], p.Lk, t0, Vs0, wave, lane);
-    if (tid < 8) lut_lds[tid] = p.lut[tid];
+    if (tid < 16) lut_lds[tid] = p.lut[tid];
     reduce_partials<false>(p.dec_psum + (int64_t)grp * p.dec_np * R, p.dec_np, R, row_sum, tid); // its barriers also cover Vs0 and lut_lds
 
     if (p.dbg_row_sum && chunk == 0 && tid < R) {
@@ -230,10 +230,10 @@ __global__ __launch_bounds__(NT) void decode_pv_kernel(const FwdParams p)
         p.dbg_row_sum[(int64_t)(b * p.Hq + ro.hq) * p.L + ro.i] = row_sum[tid];
     }
     // Eq. uint8-prob once per row and table entry: P = round(255 LUT_hat[idx] / S), exact
-    for (int e = tid; e < R * 33; e += NT) {
-        const int r = e / 33, idx = e % 33;
+    for (int e = tid; e < R * 65; e += NT) {
+        const int r = e / 65, idx = e % 65;
         const uint32_t S = (uint32_t)row_sum[r]; // >= 255: the key of the row maximum is visible
-        const uint32_t ev = idx < 32 ? ((const uint8_t *)lut_lds)[idx] : 0u;
+        const uint32_t ev = idx < 64 ? ((const uint8_t *)lut_lds)[idx] : 0u;
         PT[r][idx] = (uint8_t)((((510u * ev + S) / (2u * S)) ^ 0x80u) & 0xffu);
     }
     __syncthreads();

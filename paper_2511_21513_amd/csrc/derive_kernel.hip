@@ -73,9 +73,9 @@ __device__ __forceinline__ uint64_t set_fp64_factor(HeadParams &hp, uint32_t top
     return bits;
 }
 
-// One wave per query head; lane l holds one check point x of the index map: x = 0, x = c_int, and
-// both sides of each of the (at most 31) steps of the exact map.  Every map in question is a
-// monotone step function, so agreement at these points is agreement on all of [0, c_int].
+// One wave per query head; lane l holds two check points x of the index map (numbers l and l + 64):
+// x = 0, x = c_int, and both sides of each of the (at most 63) steps of the exact map.  Every map in
+// question is a monotone step function, so agreement at these points is agreement on all of [0, c_int].
 __global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
 {
     const int h = blockIdx.x, lane = threadIdx.x;
@@ -86,21 +86,28 @@ __global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
     HeadParams hp;
     bool ok = derive_scalars(sq, sk, sv, so, dp.clip, dp.sqrt_d, hp);
 
-    // this lane's check point
+    // this lane's check points
     const uint32_t c_int = (uint32_t)hp.c_int, top = (uint32_t)dp.top;
-    uint32_t x = lane == 0 ? 0u : c_int;
-    bool have = lane < 2;
-    if (lane >= 2) {
-        const uint64_t k = (uint64_t)((lane - 2) >> 1) + 1;
-        const uint64_t t = ((2 * k - 1) * (uint64_t)c_int + 2ull * top - 1) / (2ull * top); // first x whose index is >= k
-        const uint32_t below = (uint32_t)(lane & 1);
-        have = k <= top && t <= c_int && t >= below;
-        x = (uint32_t)t - below;
+    uint32_t x[2], want[2];
+    bool have[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int id = lane + 64 * q;
+        x[q] = id == 0 ? 0u : c_int;
+        have[q] = id < 2;
+        if (id >= 2) {
+            const uint64_t k = (uint64_t)((id - 2) >> 1) + 1;
+            const uint64_t t = ((2 * k - 1) * (uint64_t)c_int + 2ull * top - 1) / (2ull * top); // first x whose index is >= k
+            const uint32_t below = (uint32_t)(id & 1);
+            have[q] = k <= top && t <= c_int && t >= below;
+            x[q] = (uint32_t)t - below;
+        }
+        if (!have[q]) x[q] = 0u;
+        want[q] = exact_index(x[q], c_int, top);
     }
-    const uint32_t want = exact_index(have ? x : 0u, c_int, top);
 
     // (x * mul + add) >> 24 with a 23-bit multiplier (the host's find_top24, candidate for candidate):
-    // lane l's check point with exact index k confines add to [k 2^24 - x mul, (k + 1) 2^24 - 1 - x mul];
+    // a check point with exact index k confines add to [k 2^24 - x mul, (k + 1) 2^24 - 1 - x mul];
     // the first multiplier around top 2^24 / c_int whose intervals intersect is taken
     bool found = false;
     if (ok && c_int < (1u << 23)) {
@@ -109,10 +116,12 @@ __global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
             const long long dm = cand >> 1, mul = (cand & 1) ? m0 - dm : m0 + 1 + dm;
             if (mul < 1 || mul >= (1ll << 23)) continue;
             long long lo = 0, hi = (1ll << 31) - 1 - (long long)c_int * mul;
-            if (have) {
-                const long long xm = (long long)x * mul;
-                lo = max(lo, ((long long)want << 24) - xm);
-                hi = min(hi, (((long long)want + 1) << 24) - 1 - xm);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                if (!have[q]) continue;
+                const long long xm = (long long)x[q] * mul;
+                lo = max(lo, ((long long)want[q] << 24) - xm);
+                hi = min(hi, (((long long)want[q] + 1) << 24) - 1 - xm);
             }
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) {
@@ -134,7 +143,10 @@ __global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
         // x*top/c_int + 1/2 that are not integers stay 1/(2 c_int) away from the next integer)
         const uint64_t bits = (uint64_t)__double_as_longlong((double)top / (double)c_int) + 1ull;
         const double r = __longlong_as_double((long long)bits);
-        const bool match = !have || (uint32_t)(int)__builtin_fma(-(double)x, -r, 0.5) == want;
+        bool match = true;
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+            if (have[q] && (uint32_t)(int)__builtin_fma(-(double)x[q], -r, 0.5) != want[q]) match = false;
         if (!__all(match)) ok = false;
         const uint64_t neg = bits ^ 0x8000000000000000ull;
         hp.pad[0] = IDX_FP64;

@@ -72,8 +72,10 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     __shared__ __attribute__((aligned(1024))) int8_t Ks1[TILE];
     __shared__ __attribute__((aligned(1024))) int8_t Vs0[PH == 1 ? 16 : TILE];
     __shared__ __attribute__((aligned(1024))) int8_t Vs1[PH == 1 ? 16 : TILE];
-    __shared__ uint32_t PT[WAVES][RB][32 * 32]; // [idx][row] per wave and row block
-    __shared__ uint32_t lut_lds[8];
+    // per-row probability tables, [wave][row block][idx][row]: dynamic shared memory of WAVES * RB * NIDX * 32
+    // words, NIDX = 32 or 64 table entries (none for sweeps A+B alone)
+    extern __shared__ uint32_t PT[];
+    __shared__ uint32_t lut_lds[16];
     __shared__ int32_t colsum[D];
     __shared__ int32_t cs4[PH == 0 ? WAVES : 1][D]; // in-kernel column sums of V (short sequences, single launch)
 
@@ -90,13 +92,14 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     // query rows: [rlo, rhi) of the numbering in which row r sees keys <= r under the causal mask
     const int rlo = p.row_lo, rhi = p.row_lo + p.L, LQ = p.L;
     const uint32_t top = (uint32_t)p.top;
+    const int NIDX = top < 32 ? 32 : 64; // table entries allocated per row
 
     const int q0 = qt * BQ, qw0 = q0 + wave * (RB * 32);
     const int8_t *Qp = p.q + (int64_t)b * p.qs[0] + (int64_t)hq * p.qs[1];
     const int8_t *Kp = p.k + (int64_t)b * p.ks[0] + (int64_t)kvh * p.ks[1];
     const int8_t *Vp = p.v + (int64_t)b * p.vs[0] + (int64_t)kvh * p.vs[1];
 
-    if (tid < 8) lut_lds[tid] = p.lut[tid];
+    if (tid < 16) lut_lds[tid] = p.lut[tid];
 
     // Q fragments: row block rb, row qw0 + 32 rb + n, bytes [32 kb + 16 h, +16).
     v4i qf[RB][KB];
@@ -394,10 +397,9 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     for (int rb = 0; rb < RB; ++rb) {
         if (sum[rb] == 0) sum[rb] = 1; // only rows outside [rlo, rhi); never stored
         // per-row probability table: PT[idx] = round(255 * LUT_hat[idx] / sum) - 128 as a byte
-        uint32_t *pt = PT[wave][rb];
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int kidx = 16 * h + j;
+        uint32_t *pt = PT + (wave * RB + rb) * NIDX * 32;
+        for (int j = 0; j < NIDX / 2; ++j) {
+            const int kidx = (NIDX / 2) * h + j;
             const uint32_t e = lut_b[kidx];
             const uint32_t pr = (510u * e + sum[rb]) / (2u * sum[rb]);
             pt[kidx * 32 + n] = (pr ^ 0x80u) & 0xffu;
@@ -435,7 +437,7 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
         for (int st = 0; st < KS; ++st) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                const uint32_t *pt = PT[wave][rb] + n;
+                const uint32_t *pt = PT + (wave * RB + rb) * NIDX * 32 + n;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int sc = MASKED ? min(max(s[st][rb][i], ri[rb].bound), ri[rb].mx) : max(s[st][rb][i], ri[rb].bound);
@@ -525,25 +527,27 @@ template <int D, int RB, int KT, bool CAUSAL, int PH>
 int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
 {
     const dim3 grid((unsigned)fwd_grid_size(p.B, p.Hq, p.Hkv, p.n_qtiles)), block(NT);
+    // dynamic shared memory: the per-row probability tables (32 or 64 entries of a word per query row)
+    const unsigned sh = PH == 1 ? 0u : (unsigned)(WAVES * RB * (p.top < 32 ? 32 : 64) * 32 * sizeof(uint32_t));
     if (idx_mode == IDX_DEVICE) {
         // the scheme of each head is known on the device only: one launch per scheme, each
         // skipping the heads of the other
         FwdParams pf = p;
         pf.filter = 1;
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24, PH>), grid, block, 0, st, pf);
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP64, PH>), grid, block, 0, st, pf);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24, PH>), grid, block, sh, st, pf);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP64, PH>), grid, block, sh, st, pf);
         return (int)hipGetLastError();
     }
     if (idx_mode == IDX_MAD24 || idx_mode == IDX_TOP24) // TOP24 is MAD24 with the shift at 24: same code here
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24, PH>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24, PH>), grid, block, sh, st, p);
     else if (idx_mode == IDX_MULHI24)
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MULHI24, PH>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MULHI24, PH>), grid, block, sh, st, p);
     else if (idx_mode == IDX_FP32)
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP32, PH>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP32, PH>), grid, block, sh, st, p);
     else if (idx_mode == IDX_ROW64)
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_ROW64, PH>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_ROW64, PH>), grid, block, sh, st, p);
     else
-        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP64, PH>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP64, PH>), grid, block, sh, st, p);
     return (int)hipGetLastError();
 }
 

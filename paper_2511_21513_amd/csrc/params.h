@@ -50,7 +50,7 @@ struct FwdParams {
     int32_t q_block, n_rowblk;
     int32_t filter;             // 1: a workgroup whose head's HeadParams name another scheme than the kernel's returns at once
     HeadParams hp0;             // the single parameter set when hp_table == nullptr
-    uint32_t lut[8];            // LUT_hat, 32 bytes packed little-endian (unused tail is 0)
+    uint32_t lut[16];           // LUT_hat, up to 64 bytes packed little-endian (unused tail is 0)
     int32_t *dbg_row_max, *dbg_row_sum, *dbg_acc;
     // workspace: [B*Hq*L] row max and [B*Hq*L] row sum (handed from the first to the second launch
     // of the two-launch variants), [B*Hkv*n_chunks*d] sums of V over each chunk of keys
@@ -92,7 +92,7 @@ struct SoftmaxParams {
     int32_t top;           // 2^b - 1
     int32_t vec_in, vec_out; // rows start 16-byte (logits) / 4-byte (prob) aligned: wide loads / stores
     HeadParams hp;         // c_int and the index-map constants, scheme in pad[0]
-    uint32_t lut[8];
+    uint32_t lut[16];
 };
 
 // Arguments of the derivation of HeadParams from device-resident scales.

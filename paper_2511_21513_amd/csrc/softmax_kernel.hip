@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void index_softmax_kernel(const SoftmaxParams 
     uint8_t *dst = p.prob + row * p.ps;
     const HeadParams hp = p.hp;
     const uint32_t c_int = (uint32_t)hp.c_int, top = (uint32_t)p.top;
-    const uint32_t lutv = lane < 32 ? (p.lut[lane >> 2] >> (8 * (lane & 3))) & 0xffu : 0u; // LUT_hat[lane]; 0 for a hidden key
+    const uint32_t lutv = (p.lut[lane >> 2] >> (8 * (lane & 3))) & 0xffu; // LUT_hat[lane] (0 beyond the table; up to 64 entries)
 
     auto load4 = [&](int c, int32_t (&x)[4]) __attribute__((always_inline)) {
         if (p.vec_in && c + 3 < cols) {
@@ -69,10 +69,10 @@ __global__ __launch_bounds__(256) void index_softmax_kernel(const SoftmaxParams 
         __syncthreads();
         return (uint32_t)red[1][0] + (uint32_t)red[1][1] + (uint32_t)red[1][2] + (uint32_t)red[1][3];
     };
-    // table index of one logit (32 for a hidden column) -- Delta = max - A needs 33 bits; as an
-    // unsigned difference it is exact, and the clip brings it below 2^30
+    // table index of one logit (a hidden column takes the last entry, which is 0 by Eq. lut16) -- Delta =
+    // max - A needs 33 bits; as an unsigned difference it is exact, and the clip brings it below 2^30
     auto index_of = [&](int32_t x, int32_t m, int col) __attribute__((always_inline)) {
-        if (col >= n_vis) return 32u;
+        if (col >= n_vis) return top;
         const uint32_t delta = (uint32_t)m - (uint32_t)x;
         const uint32_t dclip = delta < c_int ? delta : c_int;
         return index_any(hp, -(int)dclip, top);

@@ -72,7 +72,7 @@ def test_struct_layout_matches_header(lib):
 def test_create_rejects_bad_config(lib):
     ctx = ctypes.c_void_p()
     assert lib.intattn_create(None, None) == binding.ERR_INVALID_ARG
-    for cfg in (binding.Config(-1, 0, 6.6, 0, 0), binding.Config(-1, 6, 6.6, 0, 0)):
+    for cfg in (binding.Config(-1, 0, 6.6, 0, 0), binding.Config(-1, 7, 6.6, 0, 0)):
         assert lib.intattn_create(ctypes.byref(ctx), ctypes.byref(cfg)) == binding.ERR_UNSUPPORTED
     for cfg in (binding.Config(-1, 5, 0.0, 0, 0), binding.Config(-1, 5, float("nan"), 0, 0),
                 binding.Config(-1, 5, 6.6, 0, 7), binding.Config(-5, 5, 6.6, 0, 0),
@@ -101,16 +101,24 @@ def test_host_only_context_lut_and_params_agree_with_oracle(host_ctx, oracle):
         assert (m, sh) == oracle.requant_params(sv, so)
 
 
-@pytest.mark.parametrize("bits", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 5, 6])
 def test_other_table_sizes_agree_with_oracle(lib, oracle, bits):
-    ia = binding.IntAttn(device=-1, lut_bits=bits, clip=5.5)
-    np.testing.assert_array_equal(ia.lut(), oracle.lut(bits, 5.5))
-    ia.close()
+    for clip in (5.5, 6.6, 7.7):
+        ia = binding.IntAttn(device=-1, lut_bits=bits, clip=clip)
+        assert ia.lut().size == 1 << bits
+        np.testing.assert_array_equal(ia.lut(), oracle.lut(bits, clip))
+        ia.close()
+
+
+def test_table_sizes_beyond_six_bits_are_rejected(lib):
+    for bits in (0, 7, 8):
+        with pytest.raises(binding.IntAttnError):
+            binding.IntAttn(device=-1, lut_bits=bits)
 
 
 def apply_index_map(mode, mul, add, sh, x):
     x = x.astype(np.uint64)
-    if mode == 1:
+    if mode in (1, 6):
         return (x * np.uint64(mul) + np.uint64(add)) >> np.uint64(sh)
     if mode == 3:
         r = np.array([mul], dtype=np.uint32).view(np.float32)[0]
@@ -154,6 +162,35 @@ def test_index_map_constants_are_exact(host_ctx, oracle, mode):
         if got_mode:
             x = np.unique(np.concatenate([np.arange(0, 70001), rng.integers(0, c + 1, 50000)])).astype(np.uint64)
             np.testing.assert_array_equal(apply_index_map(got_mode, mul, add, sh, x), (2 * 31 * x + c) // (2 * c))
+
+
+@pytest.mark.parametrize("bits", [2, 5, 6])
+def test_top_byte_index_map_and_wider_tables(lib, oracle, bits):
+    """Scheme 6 (the index is the top byte of a 24-bit multiply-add) for 2^bits-entry tables, and
+    schemes 1 and 2 for the 64-entry table: exhaustively equal to the exact rounded quotient over
+    [0, c_int] wherever the library reports constants, and within the 24-bit operand range."""
+    ia = binding.IntAttn(device=-1, lut_bits=bits)
+    top = (1 << bits) - 1
+    rng = np.random.default_rng(bits)
+    cs = [1, 2, 3, 2 * top - 1, 2 * top, 2 * top + 1, 126, 127, 128, 445, 1462, 5203, 6274, 8191, 8192, 28794, 55064]
+    cs += [int(x) for x in rng.integers(1, 9000, 30)] + [int(x) for x in rng.integers(9000, 130000, 10)]
+    found = {1: 0, 2: 0, 6: 0}
+    for mode in (6, 1, 2):
+        for c in cs:
+            got_mode, mul, add, sh = ia.derive_index_map(c, mode)
+            if got_mode == 0:
+                continue
+            assert got_mode == mode
+            found[mode] += 1
+            if mode == 6:
+                assert sh == 24 and 0 < mul < 2**23 and c * mul + add < 2**31
+            x = np.arange(c + 1, dtype=np.uint64)
+            want = (2 * top * x + c) // (2 * c)
+            np.testing.assert_array_equal(apply_index_map(mode, mul, add, sh, x), want)
+            for xi in (0, c // 3, c):
+                assert int(want[xi]) == oracle.index_map(int(xi), c, bits)
+    assert found[6] >= 30 and found[1] >= 30, found
+    ia.close()
 
 
 def test_fp64_index_map_is_exact_for_every_threshold(host_ctx):

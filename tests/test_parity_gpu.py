@@ -438,6 +438,7 @@ def test_dynamic_forward_reports_unusable_scales(torch_mod, oracle):
         want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, None, causal=False, per_head=True)["out"]
         keep = [0, 1, 3]
         assert int((got[:, keep] != want[:, keep]).sum()) == 0
+        assert not got[:, 2].any()  # defined output for the head with the unusable scale: all zeros
     p.s_q = good
     got, status = dynamic_forward(torch_mod, ia, p)
     assert status == 0 and int((got != want).sum()) == 0
@@ -650,7 +651,8 @@ def test_index_softmax_operator_bit_exact(torch_mod, oracle, shape):
 
 # ---------------------------------------------------------------- other table resolutions b and clip bounds c
 
-@pytest.mark.parametrize("bc", [(1, 6.6), (2, 5.5), (3, 6.0), (4, 7.7), (5, 5.5), (5, 7.7)], ids=lambda t: f"b{t[0]}c{t[1]}")
+@pytest.mark.parametrize("bc", [(1, 6.6), (2, 5.5), (3, 6.0), (4, 7.7), (5, 5.5), (5, 7.7), (6, 5.5), (6, 6.6), (6, 7.7)],
+                         ids=lambda t: f"b{t[0]}c{t[1]}")
 def test_other_lut_bits_and_clip(torch_mod, oracle, bc):
     """The (b, c) settings of the paper's sweep (Sec. 4, table resolution and clip bound): tiled
     kernels in one and in three launches, the split-key kernels, and the operator, against the
@@ -663,12 +665,18 @@ def test_other_lut_bits_and_clip(torch_mod, oracle, bc):
     p = inputs.random_problem(600 + b, 1, 4, 2, 300, 64, True, per_head=True, spread=1.5)
     want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, None, causal=True, per_head=True, lut_bits=b, clip=c, taps=True)
     q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
-    for variant in (1, 5):
+    for variant in (1, 2, 4, 5):
         ia = binding.IntAttn(device=0, lut_bits=b, clip=c, variant=variant)
         got = ia.forward(q, k, v, p.s_q, p.s_k, p.s_v, None, causal=True, per_head=True, taps=True)
         torch.cuda.synchronize()
         for key in ("row_sum", "acc", "out"):
             assert int((got[key].cpu().numpy() != want[key]).sum()) == 0, (variant, key)
+        ia.close()
+    # scales in device memory: the parameter kernel's search at this table size
+    for variant in (1, 5):
+        ia = binding.IntAttn(device=0, lut_bits=b, clip=c, variant=variant)
+        got, status = dynamic_forward(torch, ia, p)
+        assert status == 0 and int((got != want["out"]).sum()) == 0, ("device scales", variant)
         ia.close()
     # one decoded token: the split-key kernels
     ia = binding.IntAttn(device=0, lut_bits=b, clip=c, variant=9)

@@ -7,6 +7,7 @@ from .oracle import (  # noqa: F401
     build,
     c_int,
     forward,
+    forward_groups,
     forward_row_groups,
     index_map,
     index_softmax,

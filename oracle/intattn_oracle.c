@@ -323,6 +323,131 @@ int intattn_oracle_rows(int B, int Hq, int Hkv, int L, int Lk, int d, int causal
     return rc;
 }
 
+/* ------------------------------------------------------------------ groups over the key axis (Sec. 3.3) */
+
+/*
+ * Finer quantization groups over BOTH axes of the logit matrix (Sec. 3.3, "Quantization Scope and
+ * Compatibility"): Q is quantized per block of q_block consecutive query rows, K per block of
+ * k_block consecutive keys (k_block = 1: one scale per key, i.e. per output channel of Q.K^T --
+ * "per-channel"; larger: "per-block"), V per KV head.  Every logit A_hat[i, j] then has the scale
+ * of its (row block, key block) pair,
+ *     alpha^(g) = s_Q^(g) s_K^(g) / sqrt(d),      c_int^(g) = round(c / alpha^(g))       (Sec. 3.3),
+ * clipping, index map and table lookup are the per-tensor formulas with c_int^(g), and the row is
+ * normalized once over all its keys ("summing contributions within each row").
+ *
+ * READING (the paper does not say how Delta_hat^(g) is formed when the groups of one row have
+ * different scales; integer logits of different groups are not comparable): the row maximum is
+ * taken over the DEQUANTIZED logits,
+ *     M = max_j alpha^(g(j)) * A_hat[i, j]                 (one fp64 product per logit),
+ * and each group measures its distances from the image of M in its own integer units,
+ *     m^(g) = round(M / alpha^(g)),    Delta_hat^(g)[j] = max(m^(g) - A_hat[i, j], 0).
+ * With equal scales this is m = rowMax(A_hat) and the per-tensor pipeline, bit for bit.
+ * c_int^(g) above 2^30 is capped at 2^30 (a range limit of this build; it needs
+ * s_Q s_K < 6.2e-9 sqrt(d)).  Scales must be finite and > 0.
+ * PARITY UNPINNED by the paper for this reading; pinned to the per-tensor pipeline (equal scales),
+ * to fp64 softmax of the dequantized logits, and to an exact-rational restatement.
+ *
+ * q [B,Hq,L,d]; k, v [B,Hkv,Lk,d]; sq, so [B,Hq,ceil(L/q_block)] (so may be NULL: s_O = s_V);
+ * sk [B,Hkv,ceil(Lk/k_block)]; sv [Hkv].  Taps (NULL to skip): row_max_real [B,Hq,L] (M, fp64),
+ * row_sum [B,Hq,L], acc [B,Hq,L,d], prob [B,Hq,L,Lk].
+ */
+int intattn_oracle_forward_groups(int B, int Hq, int Hkv, int L, int Lk, int d, int causal, const int8_t *q,
+                                  const int8_t *k, const int8_t *v, int q_block, int k_block,
+                                  const float *sq, const float *sk, const float *sv, const float *so,
+                                  int lut_bits, double clip, int8_t *out, double *row_max_real,
+                                  int32_t *row_sum, int32_t *acc, uint8_t *prob)
+{
+    int rc = check_problem(B, Hq, Hkv, L, Lk, causal, d, lut_bits, clip, q, k, v, sq, sk, sv);
+    if (rc) return rc;
+    if (!out || q_block < 1 || k_block < 1) return ORACLE_BAD_ARG;
+    const int nqb = (L + q_block - 1) / q_block, nkb = (Lk + k_block - 1) / k_block;
+    const int64_t top = ((int64_t)1 << lut_bits) - 1;
+    const int64_t C_INT_CAP = (int64_t)1 << 30;
+    uint8_t lut[256];
+    rc = intattn_oracle_lut(lut_bits, clip, lut);
+    if (rc) return rc;
+    for (int64_t e = 0; e < (int64_t)B * Hq * nqb; ++e)
+        if (!(sq[e] > 0.0f) || isinf(sq[e]) || (so && (!(so[e] > 0.0f) || isinf(so[e])))) return ORACLE_BAD_ARG;
+    for (int64_t e = 0; e < (int64_t)B * Hkv * nkb; ++e)
+        if (!(sk[e] > 0.0f) || isinf(sk[e])) return ORACLE_BAD_ARG;
+
+    int64_t *a = (int64_t *)malloc(sizeof(int64_t) * (size_t)Lk);
+    int64_t *ev = (int64_t *)malloc(sizeof(int64_t) * (size_t)Lk);
+    int64_t *pv = (int64_t *)malloc(sizeof(int64_t) * (size_t)Lk);
+    double *alpha = (double *)malloc(sizeof(double) * (size_t)Lk);
+    if (!a || !ev || !pv || !alpha) {
+        free(a); free(ev); free(pv); free(alpha);
+        return ORACLE_NO_MEM;
+    }
+    const int grp = Hq / Hkv;
+    for (int bh = 0; bh < B * Hq && rc == ORACLE_OK; ++bh) {
+        const int b = bh / Hq, hq = bh % Hq, kv = hq / grp;
+        const int8_t *qh = q + (size_t)bh * L * d;
+        const int8_t *kh = k + ((size_t)b * Hkv + kv) * (size_t)Lk * d;
+        const int8_t *vh = v + ((size_t)b * Hkv + kv) * (size_t)Lk * d;
+        const float *skh = sk + ((size_t)b * Hkv + kv) * nkb;
+        for (int i = 0; i < L && rc == ORACLE_OK; ++i) {
+            const size_t row = (size_t)bh * L + i;
+            const float s_q = sq[(size_t)bh * nqb + i / q_block];
+            const float s_v = sv[kv];
+            const float s_o = so ? so[(size_t)bh * nqb + i / q_block] : s_v;
+            int64_t rq_mult;
+            int32_t rq_shift;
+            rc = intattn_oracle_requant_params(s_v, s_o, &rq_mult, &rq_shift);
+            if (rc) break;
+            const int n_vis = causal ? (i + (Lk - L) + 1) : Lk;
+
+            /* Eq. logit-scale, and the scale of every logit (Sec. 3.3) */
+            for (int j = 0; j < n_vis; ++j) {
+                int64_t s = 0;
+                for (int c = 0; c < d; ++c) s += (int64_t)qh[(size_t)i * d + c] * (int64_t)kh[(size_t)j * d + c];
+                a[j] = s;
+                alpha[j] = ((double)s_q * (double)skh[j / k_block]) / sqrt((double)d);
+            }
+            /* row maximum of the dequantized logits */
+            double M = alpha[0] * (double)a[0];
+            for (int j = 1; j < n_vis; ++j) {
+                const double x = alpha[j] * (double)a[j];
+                if (x > M) M = x;
+            }
+            /* group-wise distance, clipping (Sec. 3.3), index map, Eq. gather16, rowSum */
+            int64_t S = 0;
+            for (int j = 0; j < n_vis; ++j) {
+                double cd = floor(clip / alpha[j] + 0.5);
+                int64_t c_int = !(cd >= 1.0) ? 1 : (cd > (double)C_INT_CAP ? C_INT_CAP : (int64_t)cd);
+                double md = floor(M / alpha[j] + 0.5); /* image of the row maximum in this group's units */
+                if (md > 4.0e18) md = 4.0e18;
+                if (md < -4.0e18) md = -4.0e18;
+                int64_t delta = (int64_t)md - a[j];
+                if (delta < 0) delta = 0;
+                const int64_t dclip = delta < c_int ? delta : c_int;
+                const int64_t idx = round_div(dclip * top, c_int);
+                ev[j] = (int64_t)lut[idx];
+                S += ev[j];
+            }
+            /* Eq. uint8-prob over the whole row */
+            for (int j = 0; j < n_vis; ++j) pv[j] = intattn_oracle_prob(ev[j], S);
+            if (prob)
+                for (int j = 0; j < Lk; ++j) prob[row * Lk + j] = (j < n_vis) ? (uint8_t)pv[j] : 0;
+            if (row_max_real) row_max_real[row] = M;
+            if (row_sum) row_sum[row] = (int32_t)S;
+            /* P_hat * V_hat, requantization */
+            const int64_t half = (int64_t)1 << (rq_shift - 1), den = (int64_t)1 << rq_shift;
+            for (int c = 0; c < d; ++c) {
+                int64_t s = 0;
+                for (int j = 0; j < n_vis; ++j) s += pv[j] * (int64_t)vh[(size_t)j * d + c];
+                if (acc) acc[row * d + c] = (int32_t)s;
+                int64_t o = floor_div(s * rq_mult + half, den);
+                if (o > 127) o = 127;
+                if (o < -127) o = -127;
+                out[row * d + c] = (int8_t)o;
+            }
+        }
+    }
+    free(a); free(ev); free(pv); free(alpha);
+    return rc;
+}
+
 /* ------------------------------------------------------------------ IndexSoftmax as an operator */
 
 /*

@@ -56,6 +56,8 @@ def _load():
             lib.intattn_oracle_rows.restype = i32
             lib.intattn_oracle_index_softmax.argtypes = [i64, i64, vp, i64, i32, dbl, i64, i32, vp]
             lib.intattn_oracle_index_softmax.restype = i32
+            lib.intattn_oracle_forward_groups.argtypes = [i32] * 7 + [vp] * 3 + [i32, i32] + [vp] * 4 + [i32, dbl] + [vp] * 5
+            lib.intattn_oracle_forward_groups.restype = i32
             lib.intattn_oracle_quantize.argtypes = [i32] * 4 + [vp, i32, vp, vp]
             lib.intattn_oracle_quantize.restype = i32
             _lib = lib
@@ -207,6 +209,40 @@ def forward_row_groups(q, k, v, s_q, s_k, s_v, s_o=None, *, q_block, causal=Fals
                             causal=causal, per_head=False, lut_bits=lut_bits, clip=clip)
                 for key in res:
                     res[key][b, h, r0:r1] = part[key]
+    return res
+
+
+def forward_groups(q, k, v, s_q, s_k, s_v, s_o=None, *, q_block, k_block, causal=False, lut_bits=5, clip=6.6,
+                   taps=False, want_prob=False):
+    """Finer quantization groups over both axes (Sec. 3.3): ``s_q`` (and ``s_o`` if given) hold one
+    scale per block of ``q_block`` query rows of every (batch, head), [B, Hq, ceil(L / q_block)];
+    ``s_k`` one per block of ``k_block`` keys of every (batch, KV head), [B, Hkv, ceil(Lk / k_block)]
+    (``k_block`` = 1: per key); ``s_v`` one per KV head.  Returns ``out`` and, with ``taps``,
+    ``row_max_real`` (fp64 maximum of the dequantized logits), ``row_sum``, ``acc``; with
+    ``want_prob``, ``prob``."""
+    B, Hq, Hkv, L, Lk, d = _check_inputs(q, k, v)
+    if q_block < 1 or k_block < 1:
+        raise ValueError("q_block and k_block must be >= 1")
+    nqb, nkb = (L + q_block - 1) // q_block, (Lk + k_block - 1) // k_block
+    sq = np.ascontiguousarray(np.asarray(s_q, dtype=np.float32).reshape(B, Hq, nqb))
+    so = None if s_o is None else np.ascontiguousarray(np.asarray(s_o, dtype=np.float32).reshape(B, Hq, nqb))
+    sk = np.ascontiguousarray(np.asarray(s_k, dtype=np.float32).reshape(B, Hkv, nkb))
+    sv = _f32(s_v)
+    if sv.size != Hkv:
+        raise ValueError("s_v holds one scale per KV head")
+    res = {"out": np.zeros((B, Hq, L, d), dtype=np.int8)}
+    if taps:
+        res["row_max_real"] = np.zeros((B, Hq, L), dtype=np.float64)
+        res["row_sum"] = np.zeros((B, Hq, L), dtype=np.int32)
+        res["acc"] = np.zeros((B, Hq, L, d), dtype=np.int32)
+    if want_prob:
+        res["prob"] = np.zeros((B, Hq, L, Lk), dtype=np.uint8)
+    rc = _load().intattn_oracle_forward_groups(
+        B, Hq, Hkv, L, Lk, d, int(bool(causal)), _ptr(q), _ptr(k), _ptr(v), int(q_block), int(k_block),
+        _ptr(sq), _ptr(sk), _ptr(sv), _ptr(so), lut_bits, clip, _ptr(res["out"]), _ptr(res.get("row_max_real")),
+        _ptr(res.get("row_sum")), _ptr(res.get("acc")), _ptr(res.get("prob")))
+    if rc:
+        raise ValueError(f"intattn_oracle_forward_groups rc={rc}")
     return res
 
 

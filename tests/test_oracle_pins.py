@@ -606,3 +606,159 @@ def test_row_group_quantizer_is_the_per_tensor_quantizer_per_block(oracle):
     ref, s0 = oracle.quantize(x[:1, :1])
     np.testing.assert_array_equal(whole, ref)
     assert s1[0, 0, 0] == s0[0]
+
+
+# ----------------------------------------------------------------------------- finer groups over the key axis
+def grouped_problem(seed, B, Hq, Hkv, L, Lk, d, q_block, k_block, spread_blocks=(0.2, 5.0)):
+    """fp32 Q, K, V whose key blocks (and query blocks) differ in range, quantized per block by the
+    oracle's own per-block quantizer (pinned above): int8 tensors and the scale arrays."""
+    import oracle as orc
+
+    rng = np.random.default_rng(seed)
+    nqb, nkb = -(-L // q_block), -(-Lk // k_block)
+    q = rng.standard_normal((B, Hq, L, d)).astype(np.float32)
+    k = rng.standard_normal((B, Hkv, Lk, d)).astype(np.float32)
+    v = rng.standard_normal((B, Hkv, Lk, d)).astype(np.float32)
+    lo, hi = spread_blocks
+    fq = np.exp(rng.uniform(math.log(lo), math.log(hi), size=(B, Hq, nqb))).astype(np.float32)
+    fk = np.exp(rng.uniform(math.log(lo), math.log(hi), size=(B, Hkv, nkb))).astype(np.float32)
+    q *= np.repeat(fq, q_block, axis=2)[:, :, :L, None]
+    k *= np.repeat(fk, k_block, axis=2)[:, :, :Lk, None]
+    q8, sq = orc.quantize_row_groups(q, q_block)
+    k8, sk = orc.quantize_row_groups(k, k_block)
+    sv = np.zeros(Hkv, dtype=np.float32)
+    v8 = np.zeros((B, Hkv, Lk, d), dtype=np.int8)
+    for h in range(Hkv):  # V per KV head, shared over the batch
+        part, s = orc.quantize(v[:, h:h + 1], per_head=False)
+        v8[:, h:h + 1] = part
+        sv[h] = s[0]
+    return q8, k8, v8, sq, sk, sv
+
+
+def test_key_groups_with_equal_scales_are_the_per_head_pipeline(oracle):
+    """Sec. 3.3 must collapse to Sec. 3.1-3.2 when every group carries the same scale: every byte
+    and tap of the per-head oracle, for blocks of keys and for one scale per key; the real row
+    maximum is then alpha times the integer one."""
+    p = inputs.random_problem(91, 2, 4, 2, 37, 16, True, per_head=True, spread=1.5)
+    ref = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, causal=True, per_head=True, taps=True, want_prob=True)
+    for qb, kb in ((5, 8), (1, 1), (37, 37), (64, 3)):
+        nqb, nkb = -(-p.L // qb), -(-p.L // kb)
+        sq = np.broadcast_to(p.s_q[None, :, None], (2, 4, nqb)).copy()
+        sk = np.broadcast_to(p.s_k[None, :, None], (2, 2, nkb)).copy()
+        r = oracle.forward_groups(p.q, p.k, p.v, sq, sk, p.s_v, q_block=qb, k_block=kb, causal=True, taps=True,
+                                  want_prob=True)
+        for key in ("out", "row_sum", "acc", "prob"):
+            np.testing.assert_array_equal(r[key], ref[key], err_msg=f"{key} q_block {qb} k_block {kb}")
+        alpha = (p.s_q.astype(np.float64)[:, None] * np.repeat(p.s_k.astype(np.float64), 2)[:, None]) / math.sqrt(16)
+        np.testing.assert_array_equal(r["row_max_real"], alpha[None] * ref["row_max"])
+
+
+@pytest.mark.parametrize("causal,kb", [(False, 4), (True, 4), (True, 1), (False, 32)])
+def test_key_groups_are_softmax_of_the_dequantized_logits(oracle, causal, kb):
+    """Brute force: with key blocks (and query blocks) whose scales differ by up to 25x, the
+    probabilities stay within the per-tensor pipeline's distance of fp64 softmax of the DEQUANTIZED
+    logits alpha^(g) A_hat -- plus a factor e^{alpha} for rounding the row maximum into each group's
+    integer units.  Two plausible wrong readings (row maximum over raw integers across groups; each
+    group normalized to its own maximum) are evaluated beside it and must break the same bound, so
+    the bound does discriminate."""
+    B, Hq, Hkv, L, d, qb = 1, 2, 1, 32, 16, 8
+    q8, k8, v8, sq, sk, sv = grouped_problem(5 + kb, B, Hq, Hkv, L, L, d, qb, kb)
+    r = oracle.forward_groups(q8, k8, v8, sq, sk, sv, q_block=qb, k_block=kb, causal=causal, want_prob=True, taps=True)
+    lut = oracle.lut().astype(np.int64)
+    worst_right, worst_intmax, worst_local = 0.0, 0.0, 0.0
+    for h in range(Hq):
+        alpha = (np.repeat(sq[0, h].astype(np.float64), qb)[:L, None] *
+                 np.repeat(sk[0, 0].astype(np.float64), kb)[None, :L]) / math.sqrt(d)
+        a_int = q8[0, h].astype(np.int64) @ k8[0, 0].astype(np.int64).T
+        a = alpha * a_int
+        vis = np.tril(np.ones((L, L), dtype=bool)) if causal else np.ones((L, L), dtype=bool)
+        a_m = np.where(vis, a, -np.inf)
+        w = np.exp(a_m - a_m.max(axis=1, keepdims=True))
+        w /= w.sum(axis=1, keepdims=True)
+        n = vis.sum(axis=1)
+        bound = (np.exp(CLIP / 31 + alpha.max()) - 1.0) + 0.0056 * n
+        l1 = np.abs(r["prob"][0, h].astype(np.float64) / 255.0 - w).sum(axis=1)
+        assert np.all(l1 <= bound), (h, float((l1 - bound).max()))
+        np.testing.assert_allclose(r["row_max_real"][0, h], a_m.max(axis=1), rtol=1e-15)
+        worst_right = max(worst_right, float((l1 / bound).max()))
+        # wrong reading 1: Delta from the maximum of the raw integers of the whole row
+        c_int = np.maximum(1, np.floor(CLIP / alpha + 0.5)).astype(np.int64)
+        for name in ("intmax", "local"):
+            if name == "intmax":
+                m = np.where(vis, a_int, -10**9).max(axis=1, keepdims=True) * np.ones_like(a_int)
+            else:  # wrong reading 2: every key block measured from its own maximum
+                m = np.zeros_like(a_int)
+                for g0 in range(0, L, kb):
+                    blk = np.where(vis[:, g0:g0 + kb], a_int[:, g0:g0 + kb], -10**9).max(axis=1, keepdims=True)
+                    m[:, g0:g0 + kb] = blk
+            dl = np.clip(m - a_int, 0, c_int)
+            idx = (2 * 31 * dl + c_int) // (2 * c_int)
+            e = np.where(vis, lut[idx], 0)
+            pw = e / e.sum(axis=1, keepdims=True)
+            bad = float((np.abs(pw - w).sum(axis=1) / bound).max())
+            if name == "intmax":
+                worst_intmax = max(worst_intmax, bad)
+            else:
+                worst_local = max(worst_local, bad)
+    assert worst_right <= 1.0
+    if kb < L:  # with a single key block both wrong readings coincide with the right one
+        assert worst_intmax > 1.5 and worst_local > 1.5, (worst_intmax, worst_local)
+
+
+def test_key_groups_follow_each_logits_own_scale_exactly(oracle):
+    """Dyadic scales and c = 6.5 make every quantity of Sec. 3.3 exact (alpha^(g) a power of two,
+    c_int^(g) = 6.5 / alpha^(g) an integer): doubling the INT8 values of one key block while
+    halving its scale leaves every dequantized logit, and therefore every probability and output
+    byte, unchanged -- and the rows must equal an exact-rational evaluation of the reading."""
+    rng = np.random.default_rng(17)
+    B, Hq, Hkv, L, d, qb, kb = 1, 2, 2, 24, 16, 6, 4
+    q8 = rng.integers(-127, 128, (B, Hq, L, d), dtype=np.int8)
+    k8 = rng.integers(-60, 61, (B, Hkv, L, d), dtype=np.int8)
+    v8 = rng.integers(-127, 128, (B, Hkv, L, d), dtype=np.int8)
+    sq = (2.0 ** -rng.integers(3, 6, (B, Hq, L // qb))).astype(np.float32)
+    sk = (2.0 ** -rng.integers(2, 6, (B, Hkv, L // kb))).astype(np.float32)
+    sv = np.asarray([0.01, 0.02], dtype=np.float32)
+    kw = dict(q_block=qb, k_block=kb, causal=True, clip=6.5, taps=True, want_prob=True)
+    base = oracle.forward_groups(q8, k8, v8, sq, sk, sv, **kw)
+    k2, sk2 = k8.copy(), sk.copy()
+    for (h, g) in ((0, 1), (0, 4), (1, 0), (1, 5)):
+        k2[0, h, g * kb:(g + 1) * kb] *= 2
+        sk2[0, h, g] /= 2
+    other = oracle.forward_groups(q8, k2, v8, sq, sk2, sv, **kw)
+    # V is untouched and P must be: the accumulators and bytes agree, although the integers differ
+    for key in ("prob", "row_sum", "acc", "out", "row_max_real"):
+        np.testing.assert_array_equal(base[key], other[key], err_msg=key)
+    assert (k2 != k8).any()
+    # exact rationals (every float here is a dyadic rational, so Fraction(float) is exact and no
+    # floating-point rounding enters anywhere)
+    lut = oracle.lut(5, 6.5)
+    for (h, i) in ((0, 0), (0, 13), (1, 23), (1, 7)):
+        n_vis = i + 1
+        al = [Fraction(float(sq[0, h, i // qb])) * Fraction(float(sk2[0, h, j // kb])) / 4 for j in range(n_vis)]
+        a = [int(np.dot(q8[0, h, i].astype(np.int64), k2[0, h, j].astype(np.int64))) for j in range(n_vis)]
+        M = max(x * y for x, y in zip(al, a))
+        e = []
+        for j in range(n_vis):
+            ci = round_half_up(Fraction(13, 2) / al[j])
+            dl = min(max(round_half_up(M / al[j]) - a[j], 0), ci)
+            e.append(int(lut[round_half_up(Fraction(dl * 31, ci))]))
+        s = sum(e)
+        pr = [round_half_up(Fraction(255 * x, s)) for x in e]
+        assert other["row_sum"][0, h, i] == s
+        assert list(other["prob"][0, h, i, :n_vis]) == pr and not other["prob"][0, h, i, n_vis:].any()
+        assert float(M) == other["row_max_real"][0, h, i]
+        acc = [sum(pr[j] * int(v8[0, h, j, c]) for j in range(n_vis)) for c in range(d)]
+        assert list(other["acc"][0, h, i]) == acc
+        mlt, sh = oracle.requant_params(sv[h], sv[h])
+        assert list(other["out"][0, h, i]) == [max(-127, min(127, (x * mlt + (1 << (sh - 1))) >> sh)) for x in acc]
+
+
+def test_key_groups_reject_unusable_scales(oracle):
+    q8, k8, v8, sq, sk, sv = grouped_problem(3, 1, 2, 1, 8, 8, 8, 4, 2)
+    for bad in (0.0, -1.0, np.inf, np.nan):
+        s2 = sk.copy()
+        s2[0, 0, 1] = bad
+        with pytest.raises(ValueError):
+            oracle.forward_groups(q8, k8, v8, sq, s2, sv, q_block=4, k_block=2)
+    with pytest.raises(ValueError):
+        oracle.forward_groups(q8, k8, v8, sq, sk, sv, q_block=4, k_block=0)

@@ -96,7 +96,17 @@ typedef struct {
                                  rows, Sec. 3.3 -- scale_q and scale_out hold one value per
                                  block of q_block consecutive query rows of every (batch,
                                  head), [B, Hq, ceil(L / q_block)] (q_block = 1: per token);
-                                 scale_k and scale_v one per KV head                          */
+                                 scale_k and scale_v one per KV head; 3 (intattn_forward_dynamic
+                                 only): groups over both axes, Sec. 3.3 -- scale_q / scale_out
+                                 as in mode 2, scale_k one value per block of k_block
+                                 consecutive keys of every (batch, KV head),
+                                 [B, Hkv, ceil(Lkv / k_block)] (k_block = 1: per key, i.e. per
+                                 output channel of Q.K^T; multiples of 32 run fastest),
+                                 scale_v one per KV head.  The row maximum is taken over the
+                                 dequantized logits alpha^(g) A_hat in fp64 and every key
+                                 block measures distances from round(M / alpha^(g)) with its
+                                 own c_int^(g) (capped at 2^30); one row sum over all keys.
+                                 dbg_row_max is not written in this mode                      */
     int32_t Lkv;              /* number of keys / values; 0 means L (square self-attention).
                                  Lkv != L: a chunk of queries, or one decoded token, against a
                                  longer (or, without mask, any) key sequence; the causal mask
@@ -110,7 +120,7 @@ typedef struct {
     int32_t *dbg_row_sum;     /* optional DEVICE [B, Hq, L] contiguous: rowSum(E_hat); NULL off */
     int32_t *dbg_acc;         /* optional DEVICE [B, Hq, L, d] contiguous: P_hat.V_hat; NULL off */
     int32_t q_block;          /* scale_mode 2 only: query rows per quantization group, >= 1   */
-    int32_t reserved;         /* must be 0                                                    */
+    int32_t k_block;          /* scale_mode 3 only: keys per quantization group, >= 1; else 0 */
 } intattn_args;
 
 /* Builds LUT_hat for (lut_bits, clip) (Sec. 3.1 Eq. lut_re, Sec. 3.2 Eq. lut16) and binds the

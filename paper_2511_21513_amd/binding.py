@@ -63,7 +63,7 @@ class Args(ctypes.Structure):
         ("scale_q", ctypes.c_void_p), ("scale_k", ctypes.c_void_p),
         ("scale_v", ctypes.c_void_p), ("scale_out", ctypes.c_void_p),
         ("dbg_row_max", ctypes.c_void_p), ("dbg_row_sum", ctypes.c_void_p), ("dbg_acc", ctypes.c_void_p),
-        ("q_block", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("q_block", ctypes.c_int32), ("k_block", ctypes.c_int32),
     ]
 
 
@@ -201,12 +201,13 @@ class IntAttn:
         return int(mode.value), int(mul.value), int(add.value), int(sh.value)
 
     def make_args(self, q, k, v, out, s_q, s_k, s_v, s_o=None, *, causal=False, per_head=False,
-                  row_max=None, row_sum=None, acc=None, device_scales=False, q_block=0):
+                  row_max=None, row_sum=None, acc=None, device_scales=False, q_block=0, k_block=0):
         """Marshals torch int8 tensors [B,H,L,d] (last dim contiguous) into an ``Args``.  Returns
         (args, keepalive): keepalive holds the scale arrays the struct points at: host arrays, or
         with ``device_scales`` the float32 device tensors given (for ``forward_dynamic_args``).
         ``q_block`` > 0 (device scales only): scale mode 2, s_q and s_o hold one value per block of
-        ``q_block`` query rows of every (batch, head), s_k and s_v one per KV head."""
+        ``q_block`` query rows of every (batch, head), s_k and s_v one per KV head.  ``k_block`` > 0 as
+        well: scale mode 3, s_k holds one value per block of ``k_block`` keys of every (batch, KV head)."""
         B, Hq, L, d = q.shape
         Hkv = k.shape[1]
         if k.shape != v.shape or k.shape[0] != B or k.shape[3] != d or out.shape != q.shape:
@@ -242,6 +243,11 @@ class IntAttn:
             n_grp = B * Hq * ((L + q_block - 1) // q_block)
             a.scale_mode, a.q_block = 2, int(q_block)
             want = [n_grp, Hkv, Hkv, n_grp]
+            if k_block:
+                a.scale_mode, a.k_block = 3, int(k_block)
+                want[1] = B * Hkv * ((k.shape[2] + k_block - 1) // k_block)
+        elif k_block:
+            raise ValueError("k_block needs q_block (use q_block = L for one query scale per head)")
         else:
             want = [Hq, Hkv, Hkv, Hq] if per_head else [1, 1, 1, 1]
         for have, need in zip(sizes, want):

@@ -355,9 +355,10 @@ int validate(intattn_ctx *ctx, const intattn_args *a)
     if (a->causal == 1 && Lk < a->L)
         return fail(ctx, INTATTN_ERR_INVALID_ARG, "a causal mask needs Lkv >= L (it is aligned to the end of the keys)");
     if (a->causal != 0 && a->causal != 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "causal must be 0 or 1");
-    if (a->scale_mode < 0 || a->scale_mode > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode must be 0, 1 or 2");
-    if (a->scale_mode == 2 && a->q_block < 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode 2 needs q_block >= 1");
-    if (a->reserved != 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "reserved must be 0");
+    if (a->scale_mode < 0 || a->scale_mode > 3) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode must be 0, 1, 2 or 3");
+    if (a->scale_mode >= 2 && a->q_block < 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode 2 and 3 need q_block >= 1");
+    if (a->scale_mode == 3 && a->k_block < 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode 3 needs k_block >= 1");
+    if (a->scale_mode != 3 && a->k_block != 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "k_block must be 0 unless scale_mode is 3");
     if (!a->q || !a->k || !a->v || !a->out) return fail(ctx, INTATTN_ERR_INVALID_ARG, "q, k, v, out must be non-NULL");
     if (!a->scale_q || !a->scale_k || !a->scale_v)
         return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_q, scale_k, scale_v must be non-NULL");
@@ -486,11 +487,13 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
     int rc = validate(ctx, a);
     if (rc) return rc;
     if (ctx->device < 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "host-only context (device -1) cannot launch");
-    if (a->scale_mode == 2 && (!dynamic || comparator))
-        return fail(ctx, INTATTN_ERR_UNSUPPORTED, "scale_mode 2 (groups of query rows) is served by intattn_forward_dynamic only");
+    if (a->scale_mode >= 2 && (!dynamic || comparator))
+        return fail(ctx, INTATTN_ERR_UNSUPPORTED, "scale_mode 2 and 3 (groups of query rows / of keys) are served by intattn_forward_dynamic only");
+    if (a->scale_mode == 3 && stage != 0)
+        return fail(ctx, INTATTN_ERR_UNSUPPORTED, "scale_mode 3 runs in a single launch: no stages");
     Derived dv;
     if (dynamic) {
-        dv.idx_mode = a->scale_mode == 2 ? IDX_ROW64 : IDX_DEVICE;
+        dv.idx_mode = a->scale_mode == 3 ? IDX_KGROUP : (a->scale_mode == 2 ? IDX_ROW64 : IDX_DEVICE);
     } else if (!rm.reserve) {
         // everything the derivation depends on, bit for bit
         const int n_q = a->scale_mode ? a->Hq : 1, n_kv = a->scale_mode ? a->Hkv : 1;
@@ -591,6 +594,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
     p.top = (1 << ctx->lut_bits) - 1;
     int variant = fwd_choose_variant(ctx->variant, a->B, a->Hq, a->L);
     if (variant == 5 && ctx->lut_bits > 5) variant = 4; // the pipelined sweep C holds 32-entry tables; same tiling otherwise
+    if (a->scale_mode == 3) variant = 1;                // groups over the key axis: the single-launch kernel
     const int rows_per_block = comparator ? 128 : fwd_rows_per_block(variant);
     p.n_qtiles = fwd_row_tiles(p.row_lo, p.L, rows_per_block);
     p.n_chunks = (p.Lk + rows_per_block - 1) / rows_per_block;
@@ -600,7 +604,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
     // Few query rows against many keys: the split-key kernels (all query heads of a KV head, times
     // the query rows, packed into one MFMA operand of at most 31 rows).
     const int64_t packed_rows = (int64_t)p.group * p.L;
-    const bool decode_ok = !comparator && stage == 0 && a->scale_mode != 2 && packed_rows <= 31 && (int64_t)a->B * a->Hkv <= 65535;
+    const bool decode_ok = !comparator && stage == 0 && a->scale_mode < 2 && packed_rows <= 31 && (int64_t)a->B * a->Hkv <= 65535;
     const bool decode = decode_ok && (ctx->variant == 9 || (ctx->variant == 0 && p.Lk >= 1024));
 
     if (dynamic) {
@@ -626,7 +630,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
         dp.sqrt_d = std::sqrt((double)a->d);
         dp.hp_table = d_hp;
         dp.status = ctx->d_status;
-        if (a->scale_mode == 2) {
+        if (a->scale_mode >= 2) {
             dp.n_rowblk = (a->L + a->q_block - 1) / a->q_block;
             dp.n_entries = (int64_t)a->B * a->Hq * dp.n_rowblk;
             if ((size_t)dp.n_entries > ctx->rowtab_cap) {
@@ -641,14 +645,28 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
         if (!rm.reserve) {
             ctx->status_n = a->Hq;
             ctx->hp_host.clear(); // the table no longer holds what the host last sent
-            if (a->scale_mode == 2) {
+            if (a->scale_mode >= 2) {
                 dp.row_table = ctx->d_rowtab;
-                const int e = launch_derive_rows(dp, stream);
+                if (a->scale_mode == 3) {
+                    dp.Hkv = a->Hkv;
+                    dp.n_kblk = (p.Lk + a->k_block - 1) / a->k_block;
+                    dp.n_kentries = (int64_t)a->B * a->Hkv * dp.n_kblk;
+                }
+                const int e = a->scale_mode == 3 ? launch_derive_groups(dp, stream) : launch_derive_rows(dp, stream);
                 if (e != 0) return hip_fail(ctx, (hipError_t)e, "launch(derive row-group parameters)");
                 p.row_table = ctx->d_rowtab;
                 p.q_block = a->q_block;
                 p.n_rowblk = dp.n_rowblk;
                 p.hp_table = nullptr; // the kernels take every parameter from the row table
+                if (a->scale_mode == 3) {
+                    p.sq_rows = a->scale_q;
+                    p.sk_blocks = a->scale_k;
+                    p.k_block = a->k_block;
+                    p.n_kblk = dp.n_kblk;
+                    p.clip = ctx->clip;
+                    p.sqrt_d = dp.sqrt_d;
+                    p.head_status = ctx->d_status;
+                }
             } else {
                 if (stage != 2) { // stage 2 reads what stage 1 derived
                     const int e = launch_derive(dp, stream);

@@ -170,13 +170,25 @@ __global__ __launch_bounds__(256) void derive_rows_kernel(const DeriveParams dp)
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= dp.n_entries) return;
     const int hq = (int)((e / dp.n_rowblk) % dp.Hq), kv = hq / dp.group;
-    const float sq = dp.scale_q[e], sk = dp.scale_k[kv], sv = dp.scale_v[kv];
+    // with groups over the key axis too (n_kentries > 0) the key scales are checked by a kernel of their own
+    // and c_int is formed per logit in the forward kernel: only the requantization is taken from here
+    const float sq = dp.scale_q[e], sk = dp.n_kentries > 0 ? 1.0f : dp.scale_k[kv], sv = dp.scale_v[kv];
     const float so = dp.scale_out ? dp.scale_out[e] : sv;
     HeadParams hp;
     const bool ok = derive_scalars(sq, sk, sv, so, dp.clip, dp.sqrt_d, hp);
     set_fp64_factor(hp, (uint32_t)dp.top);
     dp.row_table[e] = hp;
     if (!ok) dp.status[hq] = 1; // every writer stores the same value
+}
+
+// Scales per block of keys, [B * Hkv][n_kblk]: an unusable one marks every query head of its KV head.
+__global__ __launch_bounds__(256) void check_key_scales_kernel(const DeriveParams dp)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= dp.n_kentries) return;
+    if (good_scale(dp.scale_k[e])) return;
+    const int kv = (int)((e / dp.n_kblk) % dp.Hkv);
+    for (int g = 0; g < dp.group; ++g) dp.status[kv * dp.group + g] = 1; // every writer stores the same value
 }
 
 __global__ __launch_bounds__(256) void zero_status_kernel(int32_t *status, int n)
@@ -191,6 +203,14 @@ int launch_derive_rows(const DeriveParams &dp, void *stream)
 {
     hipLaunchKernelGGL(zero_status_kernel, dim3((unsigned)((dp.Hq + 255) / 256)), dim3(256), 0, (hipStream_t)stream, dp.status, dp.Hq);
     hipLaunchKernelGGL(derive_rows_kernel, dim3((unsigned)((dp.n_entries + 255) / 256)), dim3(256), 0, (hipStream_t)stream, dp);
+    return (int)hipGetLastError();
+}
+
+int launch_derive_groups(const DeriveParams &dp, void *stream)
+{
+    const int e = launch_derive_rows(dp, stream);
+    if (e != 0) return e;
+    hipLaunchKernelGGL(check_key_scales_kernel, dim3((unsigned)((dp.n_kentries + 255) / 256)), dim3(256), 0, (hipStream_t)stream, dp);
     return (int)hipGetLastError();
 }
 

@@ -93,6 +93,19 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     const int rlo = p.row_lo, rhi = p.row_lo + p.L, LQ = p.L;
     const uint32_t top = (uint32_t)p.top;
     const int NIDX = top < 32 ? 32 : 64; // table entries allocated per row
+    // Finer quantization groups over both axes (Sec. 3.3): the lane's query row has the scale of its block
+    // of q_block rows, every key the scale of its block of k_block keys.  alpha^(g) = s_Q^(g) s_K^(g) / sqrt(d)
+    // per logit; the row maximum is taken over the dequantized logits (fp64), and each key block measures
+    // distances from the image of that maximum in its own integer units.
+    constexpr bool KG = MODE == IDX_KGROUP;
+    const float *skp = KG ? p.sk_blocks + (int64_t)(b * p.Hkv + kvh) * p.n_kblk : nullptr;
+    const bool kg_blocks = KG && (p.k_block % 32) == 0; // a 32-key sub-tile lies in one key block (uniform)
+    double sq_row[RB], Mreal[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        sq_row[rb] = 0.0;
+        Mreal[rb] = -__builtin_inf();
+    }
 
     const int q0 = qt * BQ, qw0 = q0 + wave * (RB * 32);
     const int8_t *Qp = p.q + (int64_t)b * p.qs[0] + (int64_t)hq * p.qs[1];
@@ -100,6 +113,18 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     const int8_t *Vp = p.v + (int64_t)b * p.vs[0] + (int64_t)kvh * p.vs[1];
 
     if (tid < 16) lut_lds[tid] = p.lut[tid];
+    if constexpr (KG) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const int row = q0 + wave * (RB * 32) + 32 * rb + n;
+            const int lr = (row >= rlo && row < rhi) ? row - rlo : 0;
+            sq_row[rb] = (double)p.sq_rows[(int64_t)bh * p.n_rowblk + lr / p.q_block];
+        }
+    }
+    // alpha^(g) of the logit (lane's row of row block rb, key); keys past the end take the last block's scale
+    auto kg_alpha = [&](int rb, int key) __attribute__((always_inline)) {
+        return (sq_row[rb] * (double)skp[min(key, L - 1) / p.k_block]) / p.sqrt_d;
+    };
 
     // Q fragments: row block rb, row qw0 + 32 rb + n, bytes [32 kb + 16 h, +16).
     v4i qf[RB][KB];
@@ -227,7 +252,28 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
         for (int st = 0; st < KT; ++st) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                if (MASKED) {
+                if constexpr (KG) {
+                    const int klo = t * BK + 32 * st, row = qw0 + 32 * rb + n;
+                    if (kg_blocks) {
+                        int lmax = INT32_MIN; // no score is INT32_MIN
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            if (!MASKED || visible(klo + acc_key(i, h), row)) lmax = max(lmax, s[st][rb][i]);
+                        if (lmax != INT32_MIN) {
+                            const double x = kg_alpha(rb, klo) * (double)lmax; // alpha > 0: the block's largest logit
+                            Mreal[rb] = x > Mreal[rb] ? x : Mreal[rb];
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const int key = klo + acc_key(i, h);
+                            if (!MASKED || visible(key, row)) {
+                                const double x = kg_alpha(rb, key) * (double)s[st][rb][i];
+                                Mreal[rb] = x > Mreal[rb] ? x : Mreal[rb];
+                            }
+                        }
+                    }
+                } else if (MASKED) {
                     const int klo = t * BK + 32 * st, row = qw0 + 32 * rb + n;
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
@@ -247,6 +293,13 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
         });
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) mx[rb] = max(mx[rb], __shfl_xor(mx[rb], 32));
+        if constexpr (KG) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                const double o = __shfl_xor(Mreal[rb], 32);
+                Mreal[rb] = o > Mreal[rb] ? o : Mreal[rb];
+            }
+        }
     } else {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
@@ -264,7 +317,30 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
     };
     RowIndex<MODE> ri[RB];
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) ri[rb].init(MODE == IDX_ROW64 ? row_hp(qw0 + 32 * rb + n) : hp, mx[rb], top);
+    for (int rb = 0; rb < RB; ++rb) ri[rb].init(MODE == IDX_ROW64 ? row_hp(qw0 + 32 * rb + n) : hp, KG ? 0 : mx[rb], top);
+    if constexpr (KG) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) ri[rb].shift = (int)top; // bound of the index (see RowIndex)
+    }
+    // Key groups: the index constants of the lane's row for the key block of `key` (Sec. 3.3):
+    // c_int^(g) = round(c / alpha^(g)) capped at 2^30, m^(g) = round(M / alpha^(g)), the fp64 index map's
+    // factor for c_int^(g).  m^(g) is clamped to [-2^22, 2^30 + 2^22]: below every logit / far enough above
+    // every logit that the distance exceeds any c_int, so the clamp changes no result and all later
+    // arithmetic fits 32 bits (comparisons written so that a NaN from an unusable scale lands on a bound).
+    auto kg_index = [&](int rb, int key) __attribute__((always_inline)) {
+        const double al = kg_alpha(rb, key);
+        double cd = __builtin_floor(p.clip / al + 0.5);
+        cd = cd >= 1.0 ? cd : 1.0;
+        cd = cd < 1073741824.0 ? cd : 1073741824.0;
+        double md = __builtin_floor(Mreal[rb] / al + 0.5);
+        md = md < 1077936128.0 ? md : 1077936128.0;
+        md = md > -4194304.0 ? md : -4194304.0;
+        const int c_int = (int)cd;
+        ri[rb].mx = (int)md;
+        ri[rb].bound = ri[rb].mx - c_int;
+        const uint64_t bits = (uint64_t)__double_as_longlong((double)top / cd) + 1ull; // the double after top / c_int
+        ri[rb].negr = __longlong_as_double((long long)(bits ^ 0x8000000000000000ull));
+    };
 
     // ================================================================= sweep B: row sum of E_hat
     // transposing read: lanes 2j, 2j+1 of a 16-lane group point at the two 8-byte halves of key
@@ -304,7 +380,17 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
         for (int st = 0; st < KT; ++st) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                if (MASKED) {
+                if constexpr (KG) {
+                    const int klo = t * BK + 32 * st, row = qw0 + 32 * rb + n;
+                    if (kg_blocks) kg_index(rb, klo);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = klo + acc_key(i, h);
+                        if (!kg_blocks) kg_index(rb, key);
+                        const uint32_t e = lut_b[ri[rb](min(max(s[st][rb][i], ri[rb].bound), ri[rb].mx))];
+                        sum[rb] += (!MASKED || visible(key, row)) ? e : 0u;
+                    }
+                } else if (MASKED) {
                     const int klo = t * BK + 32 * st, row = qw0 + 32 * rb + n;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
@@ -319,7 +405,7 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
                 }
             }
         }
-        if (!MASKED) {
+        if (!MASKED && !KG) {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int st = 0; st < KT; ++st)
@@ -405,7 +491,7 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
             pt[kidx * 32 + n] = (pr ^ 0x80u) & 0xffu;
         }
         const int row = qw0 + 32 * rb + n;
-        if (p.dbg_row_max && h == 0 && row >= rlo && row < rhi) p.dbg_row_max[(int64_t)bh * LQ + (row - rlo)] = mx[rb];
+        if (!KG && p.dbg_row_max && h == 0 && row >= rlo && row < rhi) p.dbg_row_max[(int64_t)bh * LQ + (row - rlo)] = mx[rb];
         if (p.dbg_row_sum && h == 0 && row >= rlo && row < rhi) p.dbg_row_sum[(int64_t)bh * LQ + (row - rlo)] = (int32_t)sum[rb];
     }
 
@@ -438,9 +524,11 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
                 const uint32_t *pt = PT + (wave * RB + rb) * NIDX * 32 + n;
+                if (kg_blocks) kg_index(rb, t * BK + 32 * (st0 + st));
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int sc = MASKED ? min(max(s[st][rb][i], ri[rb].bound), ri[rb].mx) : max(s[st][rb][i], ri[rb].bound);
+                    if (KG && !kg_blocks) kg_index(rb, t * BK + 32 * (st0 + st) + acc_key(i, h));
+                    const int sc = (MASKED || KG) ? min(max(s[st][rb][i], ri[rb].bound), ri[rb].mx) : max(s[st][rb][i], ri[rb].bound);
                     s[st][rb][i] = (int)pt[ri[rb](sc) * 32];
                 }
             }
@@ -501,7 +589,8 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
         const int row = qw0 + 32 * rb + n;
         if (row < rlo || row >= rhi) continue;
         int8_t *Op = p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)(row - rlo) * p.os[2];
-        const HeadParams he = MODE == IDX_ROW64 ? row_hp(row) : hp;
+        HeadParams he = (MODE == IDX_ROW64 || KG) ? row_hp(row) : hp;
+        if (KG && p.head_status[hq] != 0) he.rq_mult = 0; // an unusable scale somewhere in the head: all zeros
         const int64_t half = 1ll << (he.rq_shift - 1);
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
@@ -538,6 +627,13 @@ int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
         hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_FP64, PH>), grid, block, sh, st, pf);
         return (int)hipGetLastError();
     }
+    if constexpr (RB == 1 && KT == 2 && PH == 0) {
+        if (idx_mode == IDX_KGROUP) { // groups over the key axis: single-launch kernel only
+            hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_KGROUP, PH>), grid, block, sh, st, p);
+            return (int)hipGetLastError();
+        }
+    }
+    if (idx_mode == IDX_KGROUP) return (int)hipErrorInvalidValue;
     if (idx_mode == IDX_MAD24 || idx_mode == IDX_TOP24) // TOP24 is MAD24 with the shift at 24: same code here
         hipLaunchKernelGGL((fwd_kernel<D, RB, KT, CAUSAL, IDX_MAD24, PH>), grid, block, sh, st, p);
     else if (idx_mode == IDX_MULHI24)

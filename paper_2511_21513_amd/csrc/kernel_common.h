@@ -116,7 +116,7 @@ template <int MODE> struct RowIndex {
         bound = row_max - hp.c_int;
         mul = (int)hp.idx_mul;
         shift = hp.idx_shift;
-        negr = (MODE == IDX_FP64 || MODE == IDX_ROW64) ? idx_fp64_factor(hp) : 0.0;
+        negr = (MODE == IDX_FP64 || MODE == IDX_ROW64 || MODE == IDX_KGROUP) ? idx_fp64_factor(hp) : 0.0;
         (void)top_;
         if (MODE == IDX_MULHI24) addc = hp.idx_add - ((uint32_t)row_max << hp.idx_shift);
         else if (MODE == IDX_MAD24 || MODE == IDX_TOP24) addc = hp.idx_add - (uint32_t)__mul24(row_max, (int)hp.idx_mul);
@@ -146,6 +146,9 @@ template <int MODE> struct RowIndex {
             return scaled(sc) >> 24;
         } else if (MODE == IDX_FP32) {
             return (uint32_t)(int)__builtin_fmaf((float)(sc - mx), __uint_as_float((uint32_t)mul), 0.5f);
+        } else if (MODE == IDX_KGROUP) {
+            // the fp64 map; the index is kept inside the table whatever an unusable scale produced
+            return min((uint32_t)(int)__builtin_fma((double)(sc - mx), negr, 0.5), (uint32_t)shift); // shift holds 2^b - 1 here
         } else {
             return (uint32_t)(int)__builtin_fma((double)(sc - mx), negr, 0.5);
         }

@@ -16,6 +16,7 @@ enum IdxMode : int32_t {
     IDX_DEVICE = 4, // launchers only: each head's scheme (FP32 or FP64) is in its HeadParams, written on the device
     IDX_ROW64 = 5,  // the fp64 scheme with parameters per block of query rows (FwdParams::row_table): finer
                     // quantization groups over the query rows, Sec. 3.3
+    IDX_KGROUP = 7, // per-logit parameters: quantization groups over the key axis (Sec. 3.3), fp64 map per key block
     IDX_TOP24 = 6   // MAD24 with shift 24: the index is the top byte of Delta' * mul + add, which one byte
                     // permute turns into the address of a table row 256 bytes apart (sweep C)
 };
@@ -48,6 +49,12 @@ struct FwdParams {
     const HeadParams *hp_table; // device [Hq] when per-head or derived on the device, else nullptr
     const HeadParams *row_table; // IDX_ROW64: device [B * Hq][n_rowblk], parameters of every block of q_block query rows
     int32_t q_block, n_rowblk;
+    // IDX_KGROUP: scales per block of q_block query rows [B * Hq][n_rowblk] and per block of k_block keys
+    // [B * Hkv][n_kblk] (device), the clip bound c and sqrt(d), and the per-head status words (non-zero: zeros out)
+    const float *sq_rows, *sk_blocks;
+    int32_t k_block, n_kblk;
+    double clip, sqrt_d;
+    const int32_t *head_status;
     int32_t filter;             // 1: a workgroup whose head's HeadParams name another scheme than the kernel's returns at once
     HeadParams hp0;             // the single parameter set when hp_table == nullptr
     uint32_t lut[16];           // LUT_hat, up to 64 bytes packed little-endian (unused tail is 0)
@@ -107,6 +114,10 @@ struct DeriveParams {
     int64_t n_entries;
     int32_t n_rowblk;
     HeadParams *row_table; // device [n_entries] (out)
+    // groups over the key axis as well (launch_derive_groups): scale_k holds n_kentries = B * Hkv * n_kblk values,
+    // one per block of keys; the row table then carries the requantization of each block of query rows only
+    int64_t n_kentries;
+    int32_t n_kblk, Hkv;
 };
 
 // Launchers implemented in the .hip files.  Return a hipError_t cast to int.
@@ -127,6 +138,7 @@ int launch_decode(const FwdParams &p, int d, void *stream);
 int launch_index_softmax(const SoftmaxParams &p, void *stream);
 int launch_derive(const DeriveParams &dp, void *stream);
 int launch_derive_rows(const DeriveParams &dp, void *stream);
+int launch_derive_groups(const DeriveParams &dp, void *stream);
 int launch_quantonly(const FwdParams &p, int d, int variant, void *stream);
 
 } // namespace intattn

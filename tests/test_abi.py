@@ -243,7 +243,7 @@ def test_forward_rejects_bad_arguments_without_a_gpu(host_ctx, lib):
     assert call(mk()) == binding.ERR_INVALID_ARG and "host-only" in host_ctx.last_error()
     assert call(mk(d=96)) == binding.ERR_UNSUPPORTED
     for bad in (dict(L=0), dict(Hq=3, Hkv=2), dict(L=200000), dict(causal=2), dict(scale_mode=3), dict(q=None),
-                dict(Lkv=-1), dict(Lkv=200000), dict(Lkv=4, causal=1), dict(scale_mode=2), dict(reserved=1),
+                dict(Lkv=-1), dict(Lkv=200000), dict(Lkv=4, causal=1), dict(scale_mode=2), dict(scale_mode=4), dict(k_block=1), dict(scale_mode=3, q_block=1),
                 dict(scale_k=None), dict(out=base), dict(k=base + 2049),
                 dict(v_stride=(ctypes.c_int64 * 3)(1024, 512, 60)), dict(q_stride=(ctypes.c_int64 * 3)(1024, 512, 32))):
         assert call(mk(**bad)) == binding.ERR_INVALID_ARG, bad

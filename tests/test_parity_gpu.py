@@ -737,6 +737,138 @@ def test_row_group_scales_bit_exact(torch_mod, ia, oracle, shape):
     assert int((out.cpu().numpy() != want["out"]).sum()) == 0
 
 
+KEY_GROUP_SHAPES = [
+    # B, Hq, Hkv, Lq, Lkv, d, causal, q_block, k_block, with an output scale per group of query rows
+    (1, 2, 1, 37, 37, 64, True, 1, 1, False),        # per token x per key ("per channel")
+    (2, 4, 2, 150, 150, 128, True, 16, 32, True),    # blocks of 32 keys: one group per MFMA sub-tile
+    (1, 4, 4, 300, 300, 64, False, 300, 64, True),   # one query scale per head, 64-key blocks, no mask
+    (1, 2, 2, 260, 260, 128, True, 64, 7, False),    # key blocks that straddle sub-tiles and tiles
+    (2, 2, 1, 40, 333, 64, True, 8, 128, True),      # a chunk of queries against a longer key sequence
+    (1, 2, 1, 600, 600, 128, True, 600, 96, False),  # more than 512 keys: column sums from the small kernel
+    (1, 1, 1, 130, 130, 64, False, 5, 1, True),
+]
+
+
+def key_group_problem(seed, B, Hq, Hkv, lq, lk, d, qb, kb, with_so):
+    """INT8 tensors with scales per block of query rows and per block of keys that differ by up to 25x
+    (one pair far apart, so that the image of the row maximum leaves a block's 32-bit range)."""
+    rng = np.random.default_rng(seed)
+    q = rng.integers(-127, 128, (B, Hq, lq, d), dtype=np.int8)
+    k = rng.integers(-127, 128, (B, Hkv, lk, d), dtype=np.int8)
+    v = rng.integers(-127, 128, (B, Hkv, lk, d), dtype=np.int8)
+    nqb, nkb = -(-lq // qb), -(-lk // kb)
+    s_q = (0.02 * np.exp(rng.uniform(np.log(0.2), np.log(5.0), size=(B, Hq, nqb)))).astype(np.float32)
+    s_k = (0.02 * np.exp(rng.uniform(np.log(0.2), np.log(5.0), size=(B, Hkv, nkb))) / np.sqrt(d / 64)).astype(np.float32)
+    if nkb > 1:
+        s_k[0, 0, nkb - 1] *= np.float32(1e-6)  # m^(g) of this block lies far above its logits: everything clipped
+    s_v = rng.uniform(0.01, 0.03, size=Hkv).astype(np.float32)
+    s_o = (s_v[np.arange(Hq) // (Hq // Hkv)][None, :, None] * rng.uniform(0.02, 0.2, size=(B, Hq, nqb))).astype(np.float32) if with_so else None
+    return q, k, v, s_q, s_k, s_v, s_o
+
+
+def key_group_forward(torch, ia, q, k, v, s_q, s_k, s_v, s_o, causal, qb, kb):
+    dev = torch.device("cuda:0")
+    B, Hq, lq, d = q.shape
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+    sc = [torch.from_numpy(np.ascontiguousarray(x)).to(dev) if x is not None else None for x in (s_q, s_k, s_v, s_o)]
+    out = torch.full(q.shape, 99, dtype=torch.int8, device=dev)
+    taps = {"row_sum": torch.zeros((B, Hq, lq), dtype=torch.int32, device=dev),
+            "acc": torch.zeros((B, Hq, lq, d), dtype=torch.int32, device=dev)}
+    args, keep = ia.make_args(tq, tk, tv, out, *sc, causal=causal, device_scales=True, q_block=qb, k_block=kb, **taps)
+    ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), {key: t.cpu().numpy() for key, t in taps.items()}, ia.dynamic_status()
+
+
+@pytest.mark.parametrize("shape", KEY_GROUP_SHAPES, ids=lambda s: "B{}Hq{}Hkv{}Lq{}Lk{}d{}c{:d}qb{}kb{}so{:d}".format(*s))
+def test_key_group_scales_bit_exact(torch_mod, oracle, shape):
+    """Scale mode 3 (Sec. 3.3, groups over query rows and over keys; per key at k_block = 1): row
+    sums, accumulators and output bytes of the oracle for the same reading, whatever kernel variant
+    the context names (the mode runs its own single-launch kernel)."""
+    from paper_2511_21513_amd import binding
+
+    B, Hq, Hkv, lq, lk, d, causal, qb, kb, with_so = shape
+    print(f"case {shape}", flush=True)
+    q, k, v, s_q, s_k, s_v, s_o = key_group_problem(900 + lq + kb, B, Hq, Hkv, lq, lk, d, qb, kb, with_so)
+    want = oracle.forward_groups(q, k, v, s_q, s_k, s_v, s_o, q_block=qb, k_block=kb, causal=causal, taps=True)
+    for variant in (0, 5):
+        ia = binding.IntAttn(device=0, variant=variant)
+        out, taps, status = key_group_forward(torch_mod, ia, q, k, v, s_q, s_k, s_v, s_o, causal, qb, kb)
+        ia.close()
+        assert status == 0
+        for key in ("row_sum", "acc"):
+            assert int((taps[key] != want[key]).sum()) == 0, (variant, key)
+        assert int((out != want["out"]).sum()) == 0, variant
+    assert np.abs(want["out"]).max() > 5
+
+
+def test_key_groups_with_equal_scales_equal_the_per_head_forward(torch_mod, oracle):
+    """With one scale value in every group the mode must reproduce the per-head forward (and oracle)."""
+    from paper_2511_21513_amd import binding
+
+    p = inputs.random_problem(97, 2, 4, 2, 200, 64, True, per_head=True, spread=1.5)
+    want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, None, causal=True, per_head=True)["out"]
+    ia = binding.IntAttn(device=0)
+    for qb, kb in ((1, 1), (200, 32), (13, 50)):
+        nqb, nkb = -(-200 // qb), -(-200 // kb)
+        s_q = np.broadcast_to(p.s_q[None, :, None], (2, 4, nqb)).copy()
+        s_k = np.broadcast_to(p.s_k[None, :, None], (2, 2, nkb)).copy()
+        out, _, status = key_group_forward(torch_mod, ia, p.q, p.k, p.v, s_q, s_k, p.s_v, None, True, qb, kb)
+        assert status == 0 and int((out != want).sum()) == 0, (qb, kb)
+    ia.close()
+
+
+def test_key_groups_report_unusable_scales(torch_mod, oracle):
+    """A key block with a zero, negative, infinite or NaN scale: status 1, that KV head's query heads
+    all zeros, the other heads as the oracle says; nothing faults."""
+    from paper_2511_21513_amd import binding
+
+    B, Hq, Hkv, L, d, qb, kb = 1, 4, 2, 130, 64, 16, 32
+    q, k, v, s_q, s_k, s_v, s_o = key_group_problem(5, B, Hq, Hkv, L, L, d, qb, kb, False)
+    want = oracle.forward_groups(q, k, v, s_q, s_k, s_v, None, q_block=qb, k_block=kb, causal=True)["out"]
+    ia = binding.IntAttn(device=0)
+    for bad in (0.0, -1.0, np.inf, np.nan):
+        s2 = s_k.copy()
+        s2[0, 1, 2] = bad  # KV head 1 serves query heads 2 and 3
+        out, _, status = key_group_forward(torch_mod, ia, q, k, v, s_q, s2, s_v, None, True, qb, kb)
+        assert status == 1
+        assert not out[:, 2:].any() and int((out[:, :2] != want[:, :2]).sum()) == 0
+    out, _, status = key_group_forward(torch_mod, ia, q, k, v, s_q, s_k, s_v, None, True, qb, kb)
+    assert status == 0 and int((out != want).sum()) == 0
+    ia.close()
+
+
+def test_per_block_quantizers_feed_the_key_group_forward(torch_mod, oracle):
+    """fp16 Q quantized per block of 32 query rows and K per block of 64 keys on the GPU (V per head),
+    then the forward on those device-resident scales, nothing read by the host in between: the bytes
+    of the oracle's per-block quantizer followed by the oracle for groups over both axes."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    rng = np.random.default_rng(89)
+    B, Hq, Hkv, L, d, qb, kb = 2, 4, 2, 300, 128, 32, 64
+    dev = torch.device("cuda:0")
+    qf = torch.from_numpy((rng.standard_normal((B, Hq, L, d)) * rng.uniform(0.2, 5.0, size=(B, Hq, L, 1))).astype(np.float32)).to(dev).half()
+    kf = torch.from_numpy((rng.standard_normal((B, Hkv, L, d)) * rng.uniform(0.2, 5.0, size=(B, Hkv, L, 1))).astype(np.float32)).to(dev).half()
+    vf = torch.from_numpy(rng.standard_normal((B, Hkv, L, d)).astype(np.float32)).to(dev).half()
+    ia = binding.IntAttn(device=0)
+    q, sq = ia.quantize(qf, q_block=qb)
+    k, sk = ia.quantize(kf, q_block=kb)
+    v, sv = ia.quantize(vf, per_head=True)
+    out = torch.empty_like(q)
+    args, keep = ia.make_args(q, k, v, out, sq, sk, sv, None, causal=True, device_scales=True, q_block=qb, k_block=kb)
+    ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
+    torch.cuda.synchronize()
+    assert ia.dynamic_status() == 0
+    oq, osq = oracle.quantize_row_groups(qf.float().cpu().numpy(), qb)
+    ok, osk = oracle.quantize_row_groups(kf.float().cpu().numpy(), kb)
+    ov, osv = oracle.quantize(vf.float().cpu().numpy(), per_head=True)
+    want = oracle.forward_groups(oq, ok, ov, osq, osk, osv, None, q_block=qb, k_block=kb, causal=True)["out"]
+    assert int((q.cpu().numpy() != oq).sum()) == 0 and int((k.cpu().numpy() != ok).sum()) == 0
+    assert int((out.cpu().numpy() != want).sum()) == 0
+    ia.close()
+
+
 @pytest.mark.parametrize("case", [(2, 3, 50, 64, "float16", 1), (1, 2, 77, 128, "float32", 5), (1, 4, 300, 128, "bfloat16", 64),
                                   (2, 2, 33, 8, "float32", 1), (1, 1, 100, 64, "float16", 1000)],
                          ids=lambda c: "B{}H{}L{}d{}{}qb{}".format(*c))

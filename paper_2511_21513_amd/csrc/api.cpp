@@ -902,13 +902,9 @@ int intattn_index_softmax(intattn_ctx *ctx, const intattn_softmax_args *a, void 
     std::memcpy(p.lut, ctx->lut, 64);
     // the cheapest exact index map for this threshold
     p.hp.c_int = a->c_int;
-    typedef bool (*finder)(uint32_t, uint32_t, HeadParams *);
-    const finder finders[4] = {find_mulhi24, find_mad24, find_fp32, find_fp64};
-    const int modes[4] = {IDX_MULHI24, IDX_MAD24, IDX_FP32, IDX_FP64};
-    int m = 0;
-    while (m < 4 && !finders[m]((uint32_t)a->c_int, (uint32_t)p.top, &p.hp)) ++m;
-    if (m == 4) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "no exact index map for this c_int");
-    p.hp.pad[0] = modes[m];
+    if (find_top24((uint32_t)a->c_int, (uint32_t)p.top, &p.hp)) p.hp.pad[0] = IDX_TOP24;
+    else if (find_fp64((uint32_t)a->c_int, (uint32_t)p.top, &p.hp)) p.hp.pad[0] = IDX_FP64;
+    else return fail(ctx, INTATTN_ERR_UNSUPPORTED, "no exact index map for this c_int");
     DeviceGuard guard(ctx->device);
     if (guard.status != hipSuccess) return hip_fail(ctx, guard.status, "hipSetDevice");
     const int herr = launch_index_softmax(p, hip_stream);

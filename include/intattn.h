@@ -242,6 +242,13 @@ typedef struct intattn_quant_args {
  * buffer of the context (allocated by the first call, B * H <= 65535). */
 INTATTN_API int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *args, void *hip_stream);
 
+/* intattn_quantize for `count` tensors at once (1..4; typically Q, K and V of one layer, Sec. 2.1,
+ * Eq. quant): args points at `count` consecutive argument structs, each as for intattn_quantize with
+ * scale_mode 0 or 1 (shapes, element types and scale modes may differ; a tensor with scale_mode 2
+ * goes alone).  Same results as separate calls, in two kernel launches for the whole batch instead of
+ * two per tensor.  Same scratch buffer and ordering rules. */
+INTATTN_API int intattn_quantize_batch(intattn_ctx *ctx, const intattn_quant_args *args, int32_t count, void *hip_stream);
+
 /* Host-only parameter derivation, exposed for tests: c_int of Eq. clipping_thr for
  * (s_q, s_k, d), and the output multiplier/shift for (s_v, s_o).  Any output pointer may be
  * NULL.  Returns INTATTN_ERR_INVALID_ARG for non-positive scales or an unrepresentable ratio. */

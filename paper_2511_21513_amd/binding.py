@@ -27,6 +27,7 @@ SYMBOLS = (
     "intattn_dynamic_status",
     "intattn_forward_quantonly",
     "intattn_quantize",
+    "intattn_quantize_batch",
     "intattn_index_softmax",
     "intattn_derive_params",
     "intattn_derive_index_map",
@@ -119,6 +120,8 @@ def load() -> ctypes.CDLL:
         lib.intattn_index_softmax.restype = ctypes.c_int
         lib.intattn_quantize.argtypes = [vp, ctypes.POINTER(QuantArgs), vp]
         lib.intattn_quantize.restype = i32
+        lib.intattn_quantize_batch.argtypes = [vp, ctypes.POINTER(QuantArgs), i32, vp]
+        lib.intattn_quantize_batch.restype = i32
         lib.intattn_forward_quantonly.argtypes = [vp, ctypes.POINTER(Args), vp]
         lib.intattn_forward_quantonly.restype = i32
         lib.intattn_derive_params.argtypes = [
@@ -348,6 +351,42 @@ class IntAttn:
         if rc != OK:
             raise IntAttnError(rc, self.last_error())
         return out, scales
+
+    def quant_args(self, x, out, scales, per_head: bool = False, q_block: int = 0) -> "QuantArgs":
+        """Marshals one tensor of a quantizer call (see ``quantize``)."""
+        import torch
+
+        dtypes = {torch.float32: 0, torch.float16: 1, torch.bfloat16: 2}
+        if x.dim() != 4 or x.dtype not in dtypes or x.stride(3) != 1:
+            raise ValueError("expected a [B, H, L, d] float32/float16/bfloat16 tensor with contiguous last dimension")
+        a = QuantArgs()
+        a.B, a.H, a.L, a.d = x.shape
+        a.dtype, a.scale_mode = dtypes[x.dtype], 2 if q_block else int(per_head)
+        a.q_block = int(q_block)
+        a.src, a.dst, a.scales = x.data_ptr(), out.data_ptr(), scales.data_ptr()
+        es = x.element_size()
+        for i in range(3):
+            a.src_stride[i] = x.stride(i) * es
+            a.dst_stride[i] = out.stride(i)
+        return a
+
+    def quantize_batch(self, xs, per_head=False, outs=None, scales=None, stream=None):
+        """intattn_quantize_batch: up to four [B, H, L, d] device tensors in one pair of launches.
+        ``per_head``: one flag, or one per tensor.  Returns (list of int8 tensors, list of scale tensors)."""
+        import torch
+
+        n = len(xs)
+        flags = list(per_head) if isinstance(per_head, (list, tuple)) else [per_head] * n
+        if outs is None:
+            outs = [torch.empty(x.shape, dtype=torch.int8, device=x.device) for x in xs]
+        if scales is None:
+            scales = [torch.empty(x.shape[1] if f else 1, dtype=torch.float32, device=x.device) for x, f in zip(xs, flags)]
+        arr = (QuantArgs * n)(*[self.quant_args(x, o, s, f) for x, o, s, f in zip(xs, outs, scales, flags)])
+        st = torch.cuda.current_stream(xs[0].device).cuda_stream if stream is None else stream
+        rc = self._lib.intattn_quantize_batch(self._ctx, arr, n, ctypes.c_void_p(st))
+        if rc != OK:
+            raise IntAttnError(rc, self.last_error())
+        return outs, scales
 
     def forward_stage(self, args: Args, stage: int, stream: int = 0):
         """intattn_forward_stage: 0 = everything, 1 = column sums and sweeps A+B, 2 = sweep C."""

@@ -913,56 +913,76 @@ int intattn_index_softmax(intattn_ctx *ctx, const intattn_softmax_args *a, void 
     return INTATTN_OK;
 }
 
-int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *a, void *hip_stream)
+int intattn_quantize_batch(intattn_ctx *ctx, const intattn_quant_args *args, int32_t count, void *hip_stream)
 {
     if (!ctx) return INTATTN_ERR_INVALID_ARG;
-    if (!a) return fail(ctx, INTATTN_ERR_INVALID_ARG, "args is NULL");
+    if (!args) return fail(ctx, INTATTN_ERR_INVALID_ARG, "args is NULL");
+    if (count < 1 || count > 4) return fail(ctx, INTATTN_ERR_INVALID_ARG, "count must be in 1..4");
     if (ctx->device < 0) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "host-only context: no device to run on");
-    if (a->B < 1 || a->H < 1 || a->L < 1 || a->d < 8) return fail(ctx, INTATTN_ERR_INVALID_ARG, "B, H, L must be >= 1 and d >= 8");
-    if (a->d % 8 != 0) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "d must be a multiple of 8");
-    if ((int64_t)a->B * a->H > 65535) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "B * H must not exceed 65535");
-    if ((int64_t)a->L * (a->d / 8) > 2147483647LL) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "L * d / 8 must fit 31 bits");
-    if (a->dtype < 0 || a->dtype > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "dtype must be 0 (fp32), 1 (fp16) or 2 (bf16)");
-    if (a->scale_mode < 0 || a->scale_mode > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode must be 0, 1 or 2");
-    if (a->scale_mode == 2 && a->q_block < 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode 2 needs q_block >= 1");
-    if (a->reserved != 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "reserved must be 0");
-    if (a->scale_mode == 2 && (int64_t)a->B * a->H * ((a->L + a->q_block - 1) / a->q_block) > 2147483647LL)
-        return fail(ctx, INTATTN_ERR_UNSUPPORTED, "more than 2^31-1 groups");
-    if (!a->src || !a->dst || !a->scales) return fail(ctx, INTATTN_ERR_INVALID_ARG, "src, dst, scales must be non-NULL");
-    if ((const void *)a->dst == a->src) return fail(ctx, INTATTN_ERR_INVALID_ARG, "dst must not alias src");
-    if ((((uintptr_t)a->src) & 15u) || (((uintptr_t)a->dst) & 7u))
-        return fail(ctx, INTATTN_ERR_INVALID_ARG, "src must be 16-byte aligned and dst 8-byte aligned");
-    const int64_t es = a->dtype == 0 ? 4 : 2;
-    for (int i = 0; i < 3; ++i) {
-        if (a->src_stride[i] < 0 || a->dst_stride[i] < 0 || (a->src_stride[i] & 15) != 0 || (a->dst_stride[i] & 7) != 0)
-            return fail(ctx, INTATTN_ERR_INVALID_ARG, "src strides must be non-negative multiples of 16, dst strides of 8");
+    QuantParams ps[4];
+    int64_t groups[4], total = 0;
+    for (int t = 0; t < count; ++t) {
+        const intattn_quant_args *a = args + t;
+        if (a->B < 1 || a->H < 1 || a->L < 1 || a->d < 8) return fail(ctx, INTATTN_ERR_INVALID_ARG, "B, H, L must be >= 1 and d >= 8");
+        if (a->d % 8 != 0) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "d must be a multiple of 8");
+        if ((int64_t)a->B * a->H > 65535) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "B * H must not exceed 65535");
+        if ((int64_t)a->L * (a->d / 8) > 2147483647LL) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "L * d / 8 must fit 31 bits");
+        if (a->dtype < 0 || a->dtype > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "dtype must be 0 (fp32), 1 (fp16) or 2 (bf16)");
+        if (a->scale_mode < 0 || a->scale_mode > 2) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode must be 0, 1 or 2");
+        if (a->scale_mode == 2 && a->q_block < 1) return fail(ctx, INTATTN_ERR_INVALID_ARG, "scale_mode 2 needs q_block >= 1");
+        if (a->scale_mode == 2 && count != 1)
+            return fail(ctx, INTATTN_ERR_UNSUPPORTED, "scale_mode 2 (a scale per block of rows) takes one tensor per call");
+        if (a->reserved != 0) return fail(ctx, INTATTN_ERR_INVALID_ARG, "reserved must be 0");
+        if (a->scale_mode == 2 && (int64_t)a->B * a->H * ((a->L + a->q_block - 1) / a->q_block) > 2147483647LL)
+            return fail(ctx, INTATTN_ERR_UNSUPPORTED, "more than 2^31-1 groups");
+        if (!a->src || !a->dst || !a->scales) return fail(ctx, INTATTN_ERR_INVALID_ARG, "src, dst, scales must be non-NULL");
+        if ((const void *)a->dst == a->src) return fail(ctx, INTATTN_ERR_INVALID_ARG, "dst must not alias src");
+        if ((((uintptr_t)a->src) & 15u) || (((uintptr_t)a->dst) & 7u))
+            return fail(ctx, INTATTN_ERR_INVALID_ARG, "src must be 16-byte aligned and dst 8-byte aligned");
+        const int64_t es = a->dtype == 0 ? 4 : 2;
+        for (int i = 0; i < 3; ++i) {
+            if (a->src_stride[i] < 0 || a->dst_stride[i] < 0 || (a->src_stride[i] & 15) != 0 || (a->dst_stride[i] & 7) != 0)
+                return fail(ctx, INTATTN_ERR_INVALID_ARG, "src strides must be non-negative multiples of 16, dst strides of 8");
+        }
+        if (a->src_stride[2] < es * a->d || a->dst_stride[2] < a->d)
+            return fail(ctx, INTATTN_ERR_INVALID_ARG, "the L strides must cover a row of d elements");
+        QuantParams &p = ps[t];
+        std::memset(&p, 0, sizeof(p));
+        p.src = a->src; p.dst = a->dst;
+        for (int i = 0; i < 3; ++i) { p.ss[i] = a->src_stride[i]; p.ds[i] = a->dst_stride[i]; }
+        p.B = a->B; p.H = a->H; p.L = a->L; p.d = a->d;
+        p.dtype = a->dtype; p.per_head = a->scale_mode;
+        p.q_block = a->q_block;
+        p.scales = a->scales;
+        p.n_partial = quantize_partials_per_slice(a->B, a->H, a->L, a->d);
+        groups[t] = (int64_t)a->B * a->H * p.n_partial;
+        total += groups[t];
     }
-    if (a->src_stride[2] < es * a->d || a->dst_stride[2] < a->d)
-        return fail(ctx, INTATTN_ERR_INVALID_ARG, "the L strides must cover a row of d elements");
+    if (total > 2147483647LL) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "the batch needs more than 2^31-1 workgroups");
     DeviceGuard guard(ctx->device);
     if (guard.status != hipSuccess) return hip_fail(ctx, guard.status, "hipSetDevice");
-    const int n_partial = quantize_partials_per_slice(a->B, a->H, a->L, a->d);
-    const int64_t groups = (int64_t)a->B * a->H * n_partial;
-    if (groups > ctx->amax_cap) {
+    if (total > ctx->amax_cap) {
         float *m = nullptr;
-        const hipError_t e = hipMalloc((void **)&m, sizeof(float) * (size_t)groups);
+        const hipError_t e = hipMalloc((void **)&m, sizeof(float) * (size_t)total);
         if (e != hipSuccess) return fail(ctx, INTATTN_ERR_NOMEM, std::string("hipMalloc of the quantizer scratch: ") + hipGetErrorString(e));
         if (ctx->d_amax) (void)hipFree(ctx->d_amax);
         ctx->d_amax = m;
-        ctx->amax_cap = groups;
+        ctx->amax_cap = total;
     }
-    QuantParams p;
-    std::memset(&p, 0, sizeof(p));
-    p.src = a->src; p.dst = a->dst;
-    for (int i = 0; i < 3; ++i) { p.ss[i] = a->src_stride[i]; p.ds[i] = a->dst_stride[i]; }
-    p.B = a->B; p.H = a->H; p.L = a->L; p.d = a->d;
-    p.dtype = a->dtype; p.per_head = a->scale_mode;
-    p.q_block = a->q_block;
-    p.scales = a->scales; p.partial = ctx->d_amax; p.n_partial = n_partial;
-    const int herr = launch_quantize(p, hip_stream);
+    int64_t off = 0;
+    for (int t = 0; t < count; ++t) {
+        ps[t].partial = ctx->d_amax + off; // each tensor's partial maxima
+        off += groups[t];
+    }
+    const int herr = launch_quantize(ps, count, hip_stream);
     if (herr != 0) return hip_fail(ctx, (hipError_t)herr, "launch(quantize)");
     ctx->err.clear();
     return INTATTN_OK;
+}
+
+int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *a, void *hip_stream)
+{
+    return intattn_quantize_batch(ctx, a, 1, hip_stream);
 }
 
 int intattn_forward_quantonly(intattn_ctx *ctx, const intattn_args *args, void *hip_stream)

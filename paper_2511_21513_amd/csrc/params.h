@@ -88,6 +88,15 @@ struct QuantParams {
     int32_t n_partial;
 };
 
+// Up to four tensors quantized by one pair of launches: workgroups [first[i], first[i + 1]) of the flat grid
+// belong to tensor i; gx[i] = workgroups along the items of one (b, h) slice in the second pass.
+struct QuantBatch {
+    QuantParams t[4];
+    int32_t n;
+    uint32_t first[5];
+    uint32_t gx[4];
+};
+
 // Arguments of IndexSoftmax as an operator on INT32 logits (Sec. 3.1-3.2).
 struct SoftmaxParams {
     const int32_t *logits; // device [rows, cols]
@@ -133,7 +142,7 @@ inline int fwd_row_tiles(int row_lo, int n_rows, int rows_per_tile)
 }
 bool fwd_variant_known(int variant);
 int quantize_partials_per_slice(int B, int H, int L, int d);
-int launch_quantize(const QuantParams &p, void *stream);
+int launch_quantize(const QuantParams *ps, int n, void *stream);
 int launch_decode(const FwdParams &p, int d, void *stream);
 int launch_index_softmax(const SoftmaxParams &p, void *stream);
 int launch_derive(const DeriveParams &dp, void *stream);

@@ -5,9 +5,12 @@
 // per wave and per workgroup and stored (no atomics: two thousand updates of one word cost more
 // than reading the tensor); (2) every workgroup reduces the partial maxima of its group, then one
 // IEEE fp32 division per element, nearest integer with ties to even (v_rndne_f32), eight INT8
-// results per 8-byte store.
+// results per 8-byte store.  Up to four tensors (Q, K, V) share the two launches: a flat grid whose
+// workgroups find their tensor from cumulative counts.  The second pass walks the grid backwards, so
+// that it starts in what the first pass left in the caches.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 #include "kernel_common.h"
 #include "params.h"
@@ -17,7 +20,9 @@ namespace intattn {
 namespace {
 
 constexpr int QNT = 256;   // threads per workgroup
-constexpr int QITEMS = 4;  // 8-element items per thread
+constexpr int QITEMS = 4;  // 8-element items per thread in flight
+constexpr int QLOOP = 4;   // rounds of QITEMS items per thread in the second pass: the reduction of the partial
+                           // maxima at the start of a workgroup is paid once per 64 KiB of input
 
 // eight consecutive elements of a row as fp32 (widening fp16 / bf16 is exact)
 template <int DTYPE>
@@ -57,23 +62,39 @@ __device__ __forceinline__ void item_offsets(const QuantParams &p, uint32_t it, 
     }
 }
 
-// blockIdx.y = b * H + h; blockIdx.x walks the (L * d / 8) items of that slice.
+// Tensor and position of a workgroup in the flat grid of a batch: workgroups [first[i], first[i + 1])
+// belong to tensor i and are numbered x-fastest inside it.
+struct BatchSlot {
+    int ti;
+    uint32_t bx, by;
+};
+__device__ __forceinline__ BatchSlot batch_slot(const QuantBatch &qb, uint32_t lin, const uint32_t (&gx)[4])
+{
+    int ti = 0;
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+        if (i < qb.n && lin >= qb.first[i]) ti = i;
+    const uint32_t rel = lin - qb.first[ti];
+    return BatchSlot{ti, rel % gx[ti], rel / gx[ti]};
+}
+
+// by = b * H + h; bx walks the (L * d / 8) items of that slice.
 template <int DTYPE>
-__global__ __launch_bounds__(QNT) void absmax_kernel(const QuantParams p)
+__device__ __forceinline__ void absmax_body(const QuantParams &p, uint32_t bx, uint32_t gdx, uint32_t by)
 {
     constexpr int ES = DTYPE == 0 ? 4 : 2;
     __shared__ float wmax[QNT / 64];
-    const int bh = blockIdx.y, b = bh / p.H, h = bh % p.H;
+    const int bh = (int)by, b = bh / p.H, h = bh % p.H;
     const uint8_t *src = (const uint8_t *)p.src + (int64_t)b * p.ss[0] + (int64_t)h * p.ss[1];
     const int ipr = p.d / 8; // items per row
     const int64_t items = (int64_t)p.L * ipr;
     float m = 0.0f;
     // grid-stride walk, QITEMS loads in flight per thread
-    for (int64_t base = (int64_t)blockIdx.x * QNT + threadIdx.x; base < items; base += (int64_t)gridDim.x * QNT * QITEMS) {
+    for (int64_t base = (int64_t)bx * QNT + threadIdx.x; base < items; base += (int64_t)gdx * QNT * QITEMS) {
         float x[QITEMS][8];
 #pragma unroll
         for (int j = 0; j < QITEMS; ++j) {
-            const int64_t it = base + (int64_t)j * gridDim.x * QNT;
+            const int64_t it = base + (int64_t)j * gdx * QNT;
 #pragma unroll
             for (int i = 0; i < 8; ++i) x[j][i] = 0.0f;
             if (it < items) {
@@ -94,15 +115,27 @@ __global__ __launch_bounds__(QNT) void absmax_kernel(const QuantParams p)
     if (threadIdx.x == 0) {
 #pragma unroll
         for (int w = 1; w < QNT / 64; ++w) m = fmaxf(m, wmax[w]);
-        p.partial[(int64_t)bh * gridDim.x + blockIdx.x] = m;
+        p.partial[(int64_t)bh * gdx + bx] = m;
     }
 }
 
+__global__ __launch_bounds__(QNT) void absmax_kernel(const QuantBatch qb)
+{
+    uint32_t gx[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) gx[i] = (uint32_t)qb.t[i].n_partial;
+    const BatchSlot sl = batch_slot(qb, blockIdx.x, gx);
+    const QuantParams &p = qb.t[sl.ti];
+    if (p.dtype == 0) absmax_body<0>(p, sl.bx, gx[sl.ti], sl.by);
+    else if (p.dtype == 1) absmax_body<1>(p, sl.bx, gx[sl.ti], sl.by);
+    else absmax_body<2>(p, sl.bx, gx[sl.ti], sl.by);
+}
+
 template <int DTYPE>
-__global__ __launch_bounds__(QNT) void quantize_kernel(const QuantParams p)
+__device__ __forceinline__ void quantize_body(const QuantParams &p, uint32_t bx, uint32_t by)
 {
     constexpr int ES = DTYPE == 0 ? 4 : 2;
-    const int bh = blockIdx.y, b = bh / p.H, h = bh % p.H;
+    const int bh = (int)by, b = bh / p.H, h = bh % p.H;
     const int g = p.per_head ? h : 0;
     // max|X| of the group from the partial maxima: slices (b', h') with h' = h, or all slices
     __shared__ float wmax[QNT / 64];
@@ -121,29 +154,53 @@ __global__ __launch_bounds__(QNT) void quantize_kernel(const QuantParams p)
     for (int w = 0; w < QNT / 64; ++w) m = fmaxf(m, wmax[w]);
     const float amax = fmaxf(m, 1e-12f);
     const float s = amax / 127.0f; // one IEEE fp32 division
-    if (blockIdx.x == 0 && threadIdx.x == 0 && b == 0 && (p.per_head || h == 0)) p.scales[g] = s;
+    if (bx == 0 && threadIdx.x == 0 && b == 0 && (p.per_head || h == 0)) p.scales[g] = s;
     const uint8_t *src = (const uint8_t *)p.src + (int64_t)b * p.ss[0] + (int64_t)h * p.ss[1];
     int8_t *dst = p.dst + (int64_t)b * p.ds[0] + (int64_t)h * p.ds[1];
     const int ipr = p.d / 8;
     const int64_t items = (int64_t)p.L * ipr;
+    for (int r = 0; r < QLOOP; ++r) {
+        // QITEMS loads in flight per thread, then the arithmetic and the stores
+        float x[QITEMS][8];
+        int64_t dofs[QITEMS];
+        bool live[QITEMS];
 #pragma unroll
-    for (int j = 0; j < QITEMS; ++j) {
-        const int64_t it = ((int64_t)blockIdx.x * QITEMS + j) * QNT + threadIdx.x;
-        if (it < items) {
-            int64_t so, dofs;
-            item_offsets<ES>(p, (uint32_t)it, (uint32_t)ipr, so, dofs);
-            float x[8];
-            load8<DTYPE>(src + so, x);
+        for (int j = 0; j < QITEMS; ++j) {
+            const int64_t it = ((int64_t)(bx * QLOOP + r) * QITEMS + j) * QNT + threadIdx.x;
+            live[j] = it < items;
+            dofs[j] = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[j][i] = 0.0f;
+            if (live[j]) {
+                int64_t so;
+                item_offsets<ES>(p, (uint32_t)it, (uint32_t)ipr, so, dofs[j]);
+                load8<DTYPE>(src + so, x[j]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < QITEMS; ++j) {
             uint32_t w[2] = {0u, 0u};
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                float r = __builtin_rintf(x[i] / s); // IEEE division; nearest integer, ties to even
-                r = fminf(fmaxf(r, -127.0f), 127.0f);
-                w[i / 4] |= ((uint32_t)(int)r & 0xffu) << (8 * (i % 4));
+                float q = __builtin_rintf(x[j][i] / s); // IEEE division; nearest integer, ties to even
+                q = fminf(fmaxf(q, -127.0f), 127.0f);
+                w[i / 4] |= ((uint32_t)(int)q & 0xffu) << (8 * (i % 4));
             }
-            *(uint2 *)(dst + dofs) = make_uint2(w[0], w[1]);
+            if (live[j]) *(uint2 *)(dst + dofs[j]) = make_uint2(w[0], w[1]);
         }
     }
+}
+
+__global__ __launch_bounds__(QNT) void quantize_kernel(const QuantBatch qb)
+{
+    uint32_t gx[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) gx[i] = qb.gx[i];
+    const BatchSlot sl = batch_slot(qb, qb.first[qb.n] - 1u - blockIdx.x, gx); // backwards through the grid
+    const QuantParams &p = qb.t[sl.ti];
+    if (p.dtype == 0) quantize_body<0>(p, sl.bx, sl.by);
+    else if (p.dtype == 1) quantize_body<1>(p, sl.bx, sl.by);
+    else quantize_body<2>(p, sl.bx, sl.by);
 }
 
 // One scale per block of q_block rows of a (b, h) slice (Sec. 3.3; per token at q_block = 1).  A
@@ -199,43 +256,64 @@ __global__ __launch_bounds__(QNT) void quantize_rows_kernel(const QuantParams p)
 }
 
 template <int DTYPE>
-int launch_dtype(const QuantParams &p, hipStream_t st)
+int launch_rows(const QuantParams &p, hipStream_t st)
 {
-    if (p.per_head == 2) {
-        const int64_t groups = (int64_t)p.B * p.H * ((p.L + p.q_block - 1) / p.q_block);
-        if ((int64_t)p.q_block * p.d <= 4096)
-            hipLaunchKernelGGL((quantize_rows_kernel<DTYPE, 64>), dim3((unsigned)((groups + 3) / 4)), dim3(QNT), 0, st, p);
-        else
-            hipLaunchKernelGGL((quantize_rows_kernel<DTYPE, QNT>), dim3((unsigned)groups), dim3(QNT), 0, st, p);
-        return (int)hipGetLastError();
-    }
-    const int64_t items = (int64_t)p.L * (p.d / 8);
-    const dim3 grid((unsigned)((items + QNT * QITEMS - 1) / (QNT * QITEMS)), (unsigned)(p.B * p.H)), block(QNT);
-    const dim3 rgrid((unsigned)p.n_partial, grid.y); // the reduction pass: each workgroup walks its part of a slice
-    hipLaunchKernelGGL(absmax_kernel<DTYPE>, rgrid, block, 0, st, p);
-    hipLaunchKernelGGL(quantize_kernel<DTYPE>, grid, block, 0, st, p);
+    const int64_t groups = (int64_t)p.B * p.H * ((p.L + p.q_block - 1) / p.q_block);
+    if ((int64_t)p.q_block * p.d <= 4096)
+        hipLaunchKernelGGL((quantize_rows_kernel<DTYPE, 64>), dim3((unsigned)((groups + 3) / 4)), dim3(QNT), 0, st, p);
+    else
+        hipLaunchKernelGGL((quantize_rows_kernel<DTYPE, QNT>), dim3((unsigned)groups), dim3(QNT), 0, st, p);
     return (int)hipGetLastError();
 }
 
 } // namespace
 
-// Partial maxima per (b, h) slice: about 2048 workgroups in all, never more than the slice has
-// work for.
+// Partial maxima per (b, h) slice: about 1024 workgroups in all (four per compute unit, each with 64
+// KiB of loads in flight), never more than the slice has work for.
 int quantize_partials_per_slice(int B, int H, int L, int d)
 {
     const int64_t items = (int64_t)L * (d / 8);
     const int64_t blocks = (items + QNT * QITEMS - 1) / (QNT * QITEMS);
-    const int64_t want = (2048 + (int64_t)B * H - 1) / ((int64_t)B * H);
+    const int64_t want = (1024 + (int64_t)B * H - 1) / ((int64_t)B * H);
     return (int)(blocks < want ? blocks : want);
 }
 
-int launch_quantize(const QuantParams &p, void *stream)
+// n tensors (1..4), each with per_head 0 or 1 and its own partial buffer, in two launches; or one tensor with
+// per_head 2 (a scale per block of rows) in one.
+int launch_quantize(const QuantParams *ps, int n, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    if (p.dtype == 0) return launch_dtype<0>(p, st);
-    if (p.dtype == 1) return launch_dtype<1>(p, st);
-    if (p.dtype == 2) return launch_dtype<2>(p, st);
-    return (int)hipErrorInvalidValue;
+    if (n < 1 || n > 4) return (int)hipErrorInvalidValue;
+    if (ps[0].per_head == 2) {
+        if (n != 1) return (int)hipErrorInvalidValue;
+        if (ps[0].dtype == 0) return launch_rows<0>(ps[0], st);
+        if (ps[0].dtype == 1) return launch_rows<1>(ps[0], st);
+        if (ps[0].dtype == 2) return launch_rows<2>(ps[0], st);
+        return (int)hipErrorInvalidValue;
+    }
+    QuantBatch qb;
+    memset(&qb, 0, sizeof(qb));
+    qb.n = n;
+    uint64_t tot_a = 0, tot_q = 0;
+    uint32_t first_a[5] = {0, 0, 0, 0, 0};
+    for (int i = 0; i < n; ++i) {
+        const QuantParams &p = ps[i];
+        if (p.per_head == 2 || p.dtype < 0 || p.dtype > 2) return (int)hipErrorInvalidValue;
+        qb.t[i] = p;
+        const int64_t items = (int64_t)p.L * (p.d / 8);
+        qb.gx[i] = (uint32_t)((items + QNT * QITEMS * QLOOP - 1) / (QNT * QITEMS * QLOOP));
+        first_a[i] = (uint32_t)tot_a;
+        qb.first[i] = (uint32_t)tot_q;
+        tot_a += (uint64_t)p.n_partial * (uint64_t)(p.B * p.H);
+        tot_q += (uint64_t)qb.gx[i] * (uint64_t)(p.B * p.H);
+        if (tot_a > 0x7fffffffull || tot_q > 0x7fffffffull) return (int)hipErrorInvalidValue;
+    }
+    for (int i = n; i <= 4; ++i) first_a[i] = (uint32_t)tot_a, qb.first[i] = (uint32_t)tot_q;
+    QuantBatch qa = qb; // the reduction pass: each workgroup walks its part of a slice
+    for (int i = 0; i <= 4; ++i) qa.first[i] = first_a[i];
+    hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)tot_a), dim3(QNT), 0, st, qa);
+    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)tot_q), dim3(QNT), 0, st, qb);
+    return (int)hipGetLastError();
 }
 
 } // namespace intattn

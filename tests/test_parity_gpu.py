@@ -445,6 +445,33 @@ def test_dynamic_forward_reports_unusable_scales(torch_mod, oracle):
     ia.close()
 
 
+def test_quantizer_batch_equals_separate_calls_and_the_oracle(torch_mod, oracle):
+    """intattn_quantize_batch on three tensors of different shapes, element types and scale modes (a
+    ragged tail, a strided source): the bytes and scales of the oracle quantizer, tensor by tensor."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    rng = np.random.default_rng(101)
+    dev = torch.device("cuda:0")
+    xq = torch.from_numpy((rng.standard_normal((2, 6, 333, 128)) * 3.0).astype(np.float32)).to(dev).half()
+    xk = torch.from_numpy((rng.standard_normal((2, 2, 1000, 128)) * np.asarray([1.0, 7.0])[None, :, None, None]).astype(np.float32)).to(dev)
+    wide = torch.from_numpy(rng.standard_normal((2, 2, 77, 80)).astype(np.float32)).to(dev).bfloat16()
+    xv = wide[:, :, :, :64]  # rows 160 bytes apart, 128 used
+    ia = binding.IntAttn(device=0)
+    outs, scs = ia.quantize_batch([xq, xk, xv], per_head=[False, True, True])
+    torch.cuda.synchronize()
+    for x, o, s, ph in zip((xq, xk, xv), outs, scs, (False, True, True)):
+        want, wsc = oracle.quantize(x.float().cpu().numpy(), per_head=ph)
+        assert int((s.cpu().numpy() != wsc).sum()) == 0
+        assert int((o.cpu().numpy() != want).sum()) == 0
+        single, ssc = ia.quantize(x, per_head=ph)
+        torch.cuda.synchronize()
+        assert torch.equal(single, o) and torch.equal(ssc, s)
+    with pytest.raises(binding.IntAttnError):
+        ia.quantize_batch([xq] * 5)
+    ia.close()
+
+
 def test_quantizer_to_dynamic_forward_without_host_reads(torch_mod, oracle):
     """fp16 Q, K, V -> on-GPU quantizer (per head) -> dynamic forward, all enqueued before the
     first synchronization: the bytes of the oracle quantizer followed by the oracle forward."""

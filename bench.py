@@ -33,21 +33,21 @@ VALU_PEAK_LANE_OPS = 64 * 256 * 2.4e9
 CSRC = os.path.join(ROOT, "paper_2511_21513_amd", "csrc")
 
 
-def kernel_source_hash():
-    """SHA-256 over the kernel sources, in name order: what a stored counter reading is valid for."""
+def kernel_source_hash(names):
+    """SHA-256 over the named kernel sources (in the order given): what a stored counter reading is valid for."""
     import hashlib
 
     h = hashlib.sha256()
-    for fn in sorted(os.listdir(CSRC)):
-        if fn.endswith((".hip", ".h", ".cpp")):
-            with open(os.path.join(CSRC, fn), "rb") as f:
-                h.update(fn.encode() + b"\0" + f.read())
+    for fn in names:
+        with open(os.path.join(CSRC, fn), "rb") as f:
+            h.update(fn.encode() + b"\0" + f.read())
     return h.hexdigest()
 
 
 def stored_counters(tag):
-    """`key: number` lines of profiles/counters_<tag>.md (rocprofv3 --pmc readings that a timing run
-    cannot take itself), or {} when there is no such file or it was taken on other kernel sources."""
+    """`key: value` lines of profiles/counters_<tag>.md (rocprofv3 --pmc readings that a timing run
+    cannot take itself), or {} when there is no such file or the kernel sources it names
+    (`kernel_sources:`) no longer hash to its `kernel_source_sha256:`."""
     path = os.path.join(ROOT, "profiles", f"counters_{tag}.md")
     if not os.path.exists(path):
         return {}
@@ -57,9 +57,12 @@ def stored_counters(tag):
             key, sep, val = line.strip().lstrip("-* ").partition(":")
             if sep and key and " " not in key:
                 vals[key] = val.strip()
-    if vals.get("kernel_source_sha256") != kernel_source_hash():
+    try:
+        if vals.get("kernel_source_sha256") != kernel_source_hash(vals.get("kernel_sources", "").split()):
+            return {}
+    except OSError:
         return {}
-    out = {}
+    out = {"source": f"profiles/counters_{tag}.md"}
     for key, val in vals.items():
         try:
             out[key] = float(val)

@@ -719,9 +719,11 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
     if (decode) {
         const size_t groups = (size_t)a->B * a->Hkv, R = (size_t)packed_rows;
         const size_t nt32 = 4 * (((size_t)p.Lk + 127) / 128);
-        // tiles per workgroup: as many as leave about a thousand workgroups, at most 8
+        // tiles per workgroup: as many as leave about a thousand workgroups (four per compute unit: all of
+        // them resident at once, so no second, partly filled round of workgroups; five per unit measured
+        // slower), at most 64
         const size_t tiles = groups * (nt32 / 4);
-        const size_t tpw = tiles / 1024 < 1 ? 1 : (tiles / 1024 > 8 ? 8 : tiles / 1024);
+        const size_t tpw = tiles / 1024 < 1 ? 1 : (tiles / 1024 > 64 ? 64 : tiles / 1024);
         const size_t chunks = (nt32 / 4 + tpw - 1) / tpw;
         const size_t n_scores = groups * nt32 * 2 * R * 16, n_idx = groups * nt32 * 2 * R * 4, n_part = groups * chunks * 4 * R;
         const size_t n_acc = groups * chunks * R * (size_t)a->d;

@@ -73,11 +73,15 @@ __device__ __forceinline__ uint64_t set_fp64_factor(HeadParams &hp, uint32_t top
     return bits;
 }
 
-// One wave per query head; lane l holds two check points x of the index map (numbers l and l + 64):
-// x = 0, x = c_int, and both sides of each of the (at most 63) steps of the exact map.  Every map in
+// One wave per query head.  Lane l computes two check points x of the index map (numbers l and l + 64):
+// x = 0, x = c_int, and both sides of each of the (at most 63) steps of the exact map; every map in
 // question is a monotone step function, so agreement at these points is agreement on all of [0, c_int].
+// The points go to LDS; then every lane tests one candidate multiplier of the top-byte scheme against
+// all of them (two rounds of 64 candidates at most), so the search costs the same few microseconds
+// whether or not constants exist.
 __global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
 {
+    __shared__ uint32_t px[128], pk[128];
     const int h = blockIdx.x, lane = threadIdx.x;
     const int si = dp.per_head ? h : 0;
     const int kv = dp.per_head ? h / dp.group : 0;
@@ -102,37 +106,39 @@ __global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
             have[q] = k <= top && t <= c_int && t >= below;
             x[q] = (uint32_t)t - below;
         }
-        if (!have[q]) x[q] = 0u;
+        if (!have[q]) x[q] = 0u; // a second copy of the point x = 0
         want[q] = exact_index(x[q], c_int, top);
+        px[id] = x[q];
+        pk[id] = want[q];
     }
+    __syncthreads();
 
     // (x * mul + add) >> 24 with a 23-bit multiplier (the host's find_top24, candidate for candidate):
     // a check point with exact index k confines add to [k 2^24 - x mul, (k + 1) 2^24 - 1 - x mul];
     // the first multiplier around top 2^24 / c_int whose intervals intersect is taken
     bool found = false;
-    if (ok && c_int < (1u << 23)) {
+    if (ok && c_int < (1u << 23)) { // wave-uniform
         const long long m0 = (long long)(((unsigned long long)top << 24) / c_int);
-        for (int cand = 0; cand < 80 && !found; ++cand) { // wave-uniform
+        for (int round = 0; round < 2 && !found; ++round) {
+            const int cand = lane + 64 * round;
             const long long dm = cand >> 1, mul = (cand & 1) ? m0 - dm : m0 + 1 + dm;
-            if (mul < 1 || mul >= (1ll << 23)) continue;
-            long long lo = 0, hi = (1ll << 31) - 1 - (long long)c_int * mul;
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                if (!have[q]) continue;
-                const long long xm = (long long)x[q] * mul;
-                lo = max(lo, ((long long)want[q] << 24) - xm);
-                hi = min(hi, (((long long)want[q] + 1) << 24) - 1 - xm);
+            const bool valid = cand < 80 && mul >= 1 && mul < (1ll << 23);
+            long long lo = 0, hi = valid ? (1ll << 31) - 1 - (long long)c_int * mul : -1;
+            if (valid) {
+                for (int i = 0; i < 128; ++i) {
+                    const long long xm = (long long)px[i] * mul, k = (long long)pk[i];
+                    lo = max(lo, (k << 24) - xm);
+                    hi = min(hi, ((k + 1) << 24) - 1 - xm);
+                }
             }
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                lo = max(lo, __shfl_xor(lo, off));
-                hi = min(hi, __shfl_xor(hi, off));
-            }
-            if (lo <= hi) {
+            const unsigned long long good = __ballot(lo <= hi);
+            if (good != 0ull) {
+                const int src = __builtin_ctzll(good); // the first candidate in the host's order
+                const long long mul_s = __shfl(mul, src), lo_s = __shfl(lo, src), hi_s = __shfl(hi, src);
                 found = true;
                 hp.pad[0] = IDX_TOP24;
-                hp.idx_mul = (uint32_t)(-(int32_t)mul);
-                hp.idx_add = (uint32_t)(lo + (hi - lo) / 2);
+                hp.idx_mul = (uint32_t)(-(int32_t)mul_s);
+                hp.idx_add = (uint32_t)(lo_s + (hi_s - lo_s) / 2);
                 hp.idx_shift = 24;
             }
         }
@@ -158,6 +164,24 @@ __global__ __launch_bounds__(64) void derive_kernel(const DeriveParams dp)
     if (lane == 0) {
         dp.hp_table[h] = hp;
         dp.status[h] = ok ? 0 : 1;
+    }
+}
+
+// All heads of a call run one index scheme: a launch that serves only some head indices leaves most of
+// the chip idle, because the workgroups of a head index share an XCD.  If any head lacks top-byte
+// constants, every head takes the fp64 map (exact for every threshold).  One wave.
+__global__ __launch_bounds__(64) void unify_schemes_kernel(HeadParams *table, int n_heads, uint32_t top)
+{
+    bool mixed = false;
+    for (int h = threadIdx.x; h < n_heads; h += 64) mixed |= table[h].pad[0] != IDX_TOP24;
+    if (!__any(mixed)) return;
+    for (int h = threadIdx.x; h < n_heads; h += 64) {
+        HeadParams hp = table[h];
+        if (hp.pad[0] == IDX_TOP24) {
+            hp.pad[0] = IDX_FP64;
+            set_fp64_factor(hp, top);
+            table[h] = hp;
+        }
     }
 }
 
@@ -217,6 +241,7 @@ int launch_derive_groups(const DeriveParams &dp, void *stream)
 int launch_derive(const DeriveParams &dp, void *stream)
 {
     hipLaunchKernelGGL(derive_kernel, dim3((unsigned)dp.Hq), dim3(64), 0, (hipStream_t)stream, dp);
+    hipLaunchKernelGGL(unify_schemes_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, dp.hp_table, dp.Hq, (uint32_t)dp.top);
     return (int)hipGetLastError();
 }
 

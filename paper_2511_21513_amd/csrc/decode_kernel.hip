@@ -7,7 +7,7 @@
 //   lookup:  global row max -> clip, index map, LUT_hat           -> table indices, per-tile row sum
 //   pv:      global row sum -> P_hat (Eq. uint8-prob), P_hat V_hat -> per-tile partial accumulators
 //   finish:  sum of the partial accumulators, requantization to INT8
-// Integer sums do not depend on the order of the additions, so the result is the oracle's bit for bit.
+// Integer sums do not depend on the order of the additions, so the result equals the row-by-row definition bit for bit.
 // Probabilities go to the signed MFMA as P - 128; row 31 of the operand is all ones, which yields
 // the column sums of V of the tile for the correction 128 * colsum.
 #include <hip/hip_runtime.h>

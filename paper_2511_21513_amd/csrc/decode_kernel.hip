@@ -117,7 +117,7 @@ __global__ __launch_bounds__(NT) void decode_scores_kernel(const FwdParams p)
     }
     const int sw = swz_k<D>(n);
     int32_t m = INT32_MIN;
-    __syncthreads(); // tile t0 is in LDS (the barrier waits for the loads)
+    publish_tiles_barrier(); // tile t0 is in LDS
     // One tile: the next one is requested first, into the buffer that was read one step ago (a
     // barrier lies in between).  The buffers are named statically in the loop below, so that the
     // compiler lets the reads of one proceed while loads into the other are in flight.
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(NT) void decode_scores_kernel(const FwdParams p)
 #pragma unroll
             for (int g = 0; g < 4; ++g) *(v4i *)(dst + 4 * g) = v4i{s[4 * g], s[4 * g + 1], s[4 * g + 2], s[4 * g + 3]};
         }
-        __syncthreads(); // the next tile has arrived, and every wave is done with this one
+        publish_tiles_barrier(); // the next tile has arrived, and every wave is done with this one
     };
     for (int t = t0; t < t1; t += 2) {
         step(t, Ks0, Ks1);
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(NT) void decode_pv_kernel(const FwdParams p)
     const int8_t *Vp = p.v + (int64_t)b * p.vs[0] + (int64_t)kvh * p.vs[1];
     stage_tile<D, true>(Vp, p.vs[2], p.Lk, t0, Vs0, wave, lane);
     if (tid < 16) lut_lds[tid] = p.lut[tid];
-    reduce_partials<false>(p.dec_psum + (int64_t)grp * p.dec_np * R, p.dec_np, R, row_sum, tid); // its barriers also cover Vs0 and lut_lds
+    reduce_partials<false>(p.dec_psum + (int64_t)grp * p.dec_np * R, p.dec_np, R, row_sum, tid); // ends with a barrier: lut_lds is visible
 
     if (p.dbg_row_sum && chunk == 0 && tid < R) {
         const RowOf ro = row_of(p, kvh, tid);
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(NT) void decode_pv_kernel(const FwdParams p)
         const uint32_t ev = idx < 64 ? ((const uint8_t *)lut_lds)[idx] : 0u;
         PT[r][idx] = (uint8_t)((((510u * ev + S) / (2u * S)) ^ 0x80u) & 0xffu);
     }
-    __syncthreads();
+    publish_tiles_barrier(); // the tables, and V tile t0 (requested at the top) are in LDS
     const uint8_t *pt = PT[n < R ? n : 0];
     // address of the transposing LDS read of V^T fragments within a 32-key sub-tile
     const int tr_i = lane & 15, tr_g = (lane >> 4) & 1, jj = tr_i >> 1;
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(NT) void decode_pv_kernel(const FwdParams p)
             const v4i vf = v4i{x0[0], x0[1], x1[0], x1[1]};
             o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf, o[cb], 0, 0, 0);
         }
-        __syncthreads(); // the next tile has arrived, and every wave is done with this one
+        publish_tiles_barrier(); // the next tile has arrived, and every wave is done with this one
     };
     for (int t = t0; t < t1; t += 2) {
         step(t, Vs0, Vs1);

@@ -181,21 +181,21 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
         constexpr bool WITH_V = decltype(with_v)::value;
         dma_k(0, Ks0);
         if (WITH_V) dma_v(0, Vs0);
-        __syncthreads();
+        publish_tiles_barrier();
         for (int t = 0; t < ntiles; t += 2) {
             if (t + 1 < ntiles) {
                 dma_k(t + 1, Ks1);
                 if (WITH_V) dma_v(t + 1, Vs1);
             }
             body(t, (const int8_t *)Ks0, (const int8_t *)Vs0);
-            __syncthreads();
+            publish_tiles_barrier();
             if (t + 1 < ntiles) {
                 if (t + 2 < ntiles) {
                     dma_k(t + 2, Ks0);
                     if (WITH_V) dma_v(t + 2, Vs0);
                 }
                 body(t + 1, (const int8_t *)Ks1, (const int8_t *)Vs1);
-                __syncthreads();
+                publish_tiles_barrier();
             }
         }
     };

@@ -155,6 +155,15 @@ template <int MODE> struct RowIndex {
     }
 };
 
+// The barrier that publishes tiles filled by direct-to-LDS loads: a wave's own loads must have landed before
+// it signals, because the other waves read what it loaded.  (On this target the compiler also drains every
+// counter before s_barrier; the wait is spelled out so that correctness does not rest on that.)
+__device__ __forceinline__ void publish_tiles_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+}
+
 // Key (within a 32-key block) held in accumulator register i of a 32x32 MFMA result by a
 // lane of half-wave h; the same key sits in byte i of that lane's next B operand.
 __device__ __forceinline__ int acc_key(int i, int h) { return 8 * (i >> 2) + 4 * h + (i & 3); }

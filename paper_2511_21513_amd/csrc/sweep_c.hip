@@ -240,7 +240,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
         for (int c = 0; c < nchunk; ++c) acc += cp[(int64_t)c * D];
         colsum[tid] = acc;
     }
-    __syncthreads(); // LUT_hat, K tiles 0 and 1, V tile 0 are in LDS
+    publish_tiles_barrier(); // LUT_hat, K tiles 0 and 1, V tile 0 are in LDS
 
     // per-row probability table of the general path: PT[idx] = round(255 * LUT_hat[idx] / sum) - 128 as a
     // byte; each lane of a row's pair computes half of the entries and stores them into both lanes' columns
@@ -412,7 +412,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
             step(masked_tag, path_tag, NSUB * T + u, Krd + u * SUB, Vrd + u * SUB, sA, sB, lB, lA, pfB, pfA);
             step(masked_tag, path_tag, NSUB * T + u + 1, Krd + (u + 1) * SUB, Vrd + (u + 1) * SUB, sB, sA, lA, lB, pfA, pfB);
         }
-        __syncthreads();
+        publish_tiles_barrier(); // K tile T + 2 and V tile T + 1 have landed; every wave is done with tile T
     };
 
     // ---- prologue: scores of sub-tile 0, fragments of sub-tile 1 (the last two sub-tiles of K tile 0);

@@ -68,8 +68,10 @@ typedef struct {
     int32_t lut_bits; /* b of Sec. 3.1: the table has 2^b entries; 1..6; paper default 5     */
     double clip;      /* c of Sec. 3.1: clip threshold in logit units; > 0; paper default 6.6 */
     int32_t variant;  /* kernel variant: 0 = automatic choice.  Tuning knobs, all bit-identical: 1, 2 = one
-                         launch with 32 / 64 query rows per wave; 4, 5 = two launches (row max and row
-                         sum, then P.V) with the phase-ordered / the software-pipelined second kernel;
+                         launch with 32 / 64 query rows per wave; 3 = one launch, a workgroup per 32 query
+                         rows with the keys split over its waves (small and mid-size problems); 4, 5 = two
+                         launches (row max and row sum, then P.V) with the phase-ordered / the
+                         software-pipelined second kernel;
                          9 = the split-key kernels for few query rows wherever the shape allows.
                          Other values are rejected                                                    */
     int32_t reserved; /* must be 0                                                           */

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libintattn.so")
-SOURCES = ["api.cpp", "fwd_kernel.hip", "fwd_single.hip", "fwd_split.hip", "sweep_c.hip",
+SOURCES = ["api.cpp", "fwd_kernel.hip", "fwd_single.hip", "fwd_split.hip", "fwd_splitk.hip", "sweep_c.hip",
            "quantize_kernel.hip", "derive_kernel.hip", "decode_kernel.hip", "softmax_kernel.hip", "quantonly_kernel.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

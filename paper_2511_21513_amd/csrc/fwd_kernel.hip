@@ -63,19 +63,25 @@ int launch_colsum(const FwdParams &p, int d, int chunk, hipStream_t st)
 
 // Kernel variants (0 = automatic choice; the others are tuning knobs, all bit-identical):
 //   1  one launch, 32 query rows per wave, 64-key tiles     2  one launch, 64 rows per wave
+//   3  one launch, a workgroup per 32 query rows with the keys split over its four waves (fwd_splitk.hip)
 //   4  two launches: sweeps A+B (64 rows per wave), then sweep C (32 rows per wave), phase-ordered kernels
 //   5  as 4 with the software-pipelined sweep C kernel
 //   9  the split-key kernels of decode_kernel.hip whenever the shape allows them, else as 0
-// Automatic choice among the tiled kernels: enough workgroups to amortise three launches -> variant 5;
-// small problems take the single launch.
-int fwd_choose_variant(int variant, int B, int Hq, int L)
+// Automatic choice among the tiled kernels, by measurement on shapes from 8 x 12 x 197 to 2 x 32 x 4096 (W = workgroups
+// of 128 query rows): W >= 1024 fills the chip with the two-launch path (variant 5); up to 256 the 128-row kernels
+// leave most SIMDs with one long-running wave and the split-key single launch (variant 3) is 1.1 to 2.3 times faster;
+// in between variant 3 still wins at d = 64 on long rows, otherwise variant 1 (at d = 128 the four waves of variant 3
+// each stream their own K fragments from L2, which costs more than the better fill gains).
+int fwd_choose_variant(int variant, int B, int Hq, int L, int d)
 {
     if (variant != 0 && variant != 9) return variant;
     const int64_t workgroups = (int64_t)B * Hq * ((L + 127) / 128);
-    return workgroups >= 1024 ? 5 : 1;
+    if (workgroups >= 1024) return 5;
+    if (workgroups <= 256) return 3;
+    return (d == 64 && L >= 1024) ? 3 : 1;
 }
-bool fwd_variant_known(int variant) { return variant == 0 || variant == 1 || variant == 2 || variant == 4 || variant == 5 || variant == 9; }
-int fwd_rows_per_block(int variant) { return variant == 2 ? 256 : 128; }
+bool fwd_variant_known(int variant) { return variant == 0 || (variant >= 1 && variant <= 5) || variant == 9; }
+int fwd_rows_per_block(int variant) { return variant == 2 ? 256 : (variant == 3 ? 32 : 128); }
 
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, void *stream)
 {
@@ -84,6 +90,9 @@ int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, 
     if (stage != 0 && !two_launches) return (int)hipErrorNotSupported;
     // all launches go to the same stream: V chunk sums first, then the sweeps
     int e = 0;
+    if (variant == 3) {
+        return launch_fwd_splitk(p, d, idx_mode, stream); // sums V itself
+    }
     if (!two_launches && p.Lk <= 512) {
         // short key sequences: the single-launch kernels sum V themselves (one launch less)
         FwdParams ps = p;

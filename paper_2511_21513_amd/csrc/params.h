@@ -133,7 +133,8 @@ struct DeriveParams {
 // stage 0: everything; 1: V column sums + sweeps A+B; 2: sweep C (two-launch variants only; else hipErrorNotSupported)
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, void *stream);
 int launch_sweep_c(const FwdParams &p, int d, int idx_mode, void *stream);
-int fwd_choose_variant(int variant, int B, int Hq, int L); // resolves 0 (automatic) to a concrete variant
+int launch_fwd_splitk(const FwdParams &p, int d, int idx_mode, void *stream);
+int fwd_choose_variant(int variant, int B, int Hq, int L, int d); // resolves 0 (automatic) to a concrete variant
 int fwd_rows_per_block(int variant);
 // tiles of `rows_per_tile` rows, aligned to multiples of it, that rows [row_lo, row_lo + n_rows) touch
 inline int fwd_row_tiles(int row_lo, int n_rows, int rows_per_tile)

@@ -239,7 +239,7 @@ typedef struct intattn_quant_args {
 
 /* Dynamic symmetric INT8 quantization of one of Q, K, V (Sec. 2.1, Eq. quant): s = max|X| / 127
  * over the tensor (or over each head index), X_hat = clamp(round(X / s), -127, 127), computed in
- * fp32 (one IEEE division per element, ties to even; max|X| is floored at 1e-12).  Enqueued on
+ * fp32 (the result of one IEEE division per element, ties to even; max|X| is floored at 1e-12).  Enqueued on
  * hip_stream; the scales stay in device memory.  Inputs must be finite.  Uses a small scratch
  * buffer of the context (allocated by the first call, B * H <= 65535). */
 INTATTN_API int intattn_quantize(intattn_ctx *ctx, const intattn_quant_args *args, void *hip_stream);

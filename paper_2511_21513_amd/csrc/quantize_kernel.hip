@@ -4,8 +4,8 @@
 // both bound by HBM: (1) max|X| of each workgroup's part of a (b, h) slice, 16-byte loads, reduced
 // per wave and per workgroup and stored (no atomics: two thousand updates of one word cost more
 // than reading the tensor); (2) every workgroup reduces the partial maxima of its group, then one
-// IEEE fp32 division per element, nearest integer with ties to even (v_rndne_f32), eight INT8
-// results per 8-byte store.  Up to four tensors (Q, K, V) share the two launches: a flat grid whose
+// IEEE fp32 division per element (done as a multiplication where that provably rounds alike, see quantize8),
+// nearest integer with ties to even (v_rndne_f32), eight INT8 results per 8-byte store.  Up to four tensors (Q, K, V) share the two launches: a flat grid whose
 // workgroups find their tensor from cumulative counts.  The second pass walks the grid backwards, so
 // that it starts in what the first pass left in the caches.
 #include <hip/hip_runtime.h>
@@ -44,6 +44,36 @@ __device__ __forceinline__ void load8(const uint8_t *p, float (&x)[8])
                 x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
             }
         }
+    }
+}
+
+// Eight elements to INT8: q = clamp(rint(x / s), -127, 127) with x / s the IEEE fp32 quotient and rint to nearest,
+// ties to even -- two words of four bytes.  The division is replaced by a multiplication wherever that provably gives
+// the same integer: with r = fl(1 / s) (one IEEE division per group) and t = fl(x r), t differs from fl(x / s) by at
+// most |x / s| * 3 * 2^-24 (1 + 2^-23) < 2.3e-5 (|x / s| <= 127.5: x is an element of the group whose maximum defines
+// s), so whenever t is farther than 2^-14 from every half-integer, t and fl(x / s) lie strictly between the same two
+// half-integers and round to the same integer.  Items with an element closer than that (about 1 in 25 for random data)
+// take the division itself; the branch is per item of eight elements.
+__device__ __forceinline__ void quantize8(const float (&x)[8], float s, float r, uint32_t (&w)[2])
+{
+    float t[8];
+    bool near = false;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        t[i] = x[i] * r;
+        const float f = t[i] - __builtin_floorf(t[i]); // in [0, 1]
+        near |= __builtin_fabsf(f - 0.5f) < 6.103515625e-05f;
+    }
+    if (near) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] = x[i] / s; // IEEE division
+    }
+    w[0] = w[1] = 0u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float q = __builtin_rintf(t[i]); // nearest integer, ties to even
+        q = fminf(fmaxf(q, -127.0f), 127.0f);
+        w[i / 4] |= ((uint32_t)(int)q & 0xffu) << (8 * (i % 4));
     }
 }
 
@@ -154,6 +184,7 @@ __device__ __forceinline__ void quantize_body(const QuantParams &p, uint32_t bx,
     for (int w = 0; w < QNT / 64; ++w) m = fmaxf(m, wmax[w]);
     const float amax = fmaxf(m, 1e-12f);
     const float s = amax / 127.0f; // one IEEE fp32 division
+    const float rs = 1.0f / s;     // and its reciprocal, for quantize8
     if (bx == 0 && threadIdx.x == 0 && b == 0 && (p.per_head || h == 0)) p.scales[g] = s;
     const uint8_t *src = (const uint8_t *)p.src + (int64_t)b * p.ss[0] + (int64_t)h * p.ss[1];
     int8_t *dst = p.dst + (int64_t)b * p.ds[0] + (int64_t)h * p.ds[1];
@@ -179,13 +210,8 @@ __device__ __forceinline__ void quantize_body(const QuantParams &p, uint32_t bx,
         }
 #pragma unroll
         for (int j = 0; j < QITEMS; ++j) {
-            uint32_t w[2] = {0u, 0u};
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                float q = __builtin_rintf(x[j][i] / s); // IEEE division; nearest integer, ties to even
-                q = fminf(fmaxf(q, -127.0f), 127.0f);
-                w[i / 4] |= ((uint32_t)(int)q & 0xffu) << (8 * (i % 4));
-            }
+            uint32_t w[2];
+            quantize8(x[j], s, rs, w);
             if (live[j]) *(uint2 *)(dst + dofs[j]) = make_uint2(w[0], w[1]);
         }
     }
@@ -239,18 +265,14 @@ __global__ __launch_bounds__(QNT) void quantize_rows_kernel(const QuantParams p)
         for (int w = 0; w < QNT / 64; ++w) m = fmaxf(m, wmax[w]);
     }
     const float s = fmaxf(m, 1e-12f) / 127.0f; // one IEEE fp32 division
+    const float rs = 1.0f / s;                 // and its reciprocal, for quantize8
     if (t == 0) p.scales[gi] = s;
     for (int it = t; it < items; it += NTHR) {
         const int row = it / ipr, c = it - row * ipr;
         float x[8];
         load8<DTYPE>(src + (int64_t)row * p.ss[2] + (int64_t)c * 8 * ES, x);
-        uint32_t w[2] = {0u, 0u};
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            float r = __builtin_rintf(x[i] / s); // IEEE division; nearest integer, ties to even
-            r = fminf(fmaxf(r, -127.0f), 127.0f);
-            w[i / 4] |= ((uint32_t)(int)r & 0xffu) << (8 * (i % 4));
-        }
+        uint32_t w[2];
+        quantize8(x, s, rs, w);
         *(uint2 *)(dst + (int64_t)row * p.ds[2] + (int64_t)c * 8) = make_uint2(w[0], w[1]);
     }
 }

@@ -445,6 +445,49 @@ def test_dynamic_forward_reports_unusable_scales(torch_mod, oracle):
     ia.close()
 
 
+@pytest.mark.parametrize("scale", [0.0371, 1.0, 3.0e-3, 777.7], ids=lambda v: f"s{v}")
+def test_quantizer_quotients_next_to_half_integers_bit_exact(torch_mod, oracle, scale):
+    """Elements whose quotient x / s lies on, or a few units in the last place beside, k + 1/2 for
+    every k in -127..126 (where a shortcut for the division would round differently from the IEEE
+    quotient), plus exact integers and random fill: the bytes of the oracle quantizer."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    s = np.float32(scale)
+    amax = np.float32(127.0) * s  # the group maximum; s = amax / 127 may differ from `scale` in the last place
+    s_eff = np.float32(amax / np.float32(127.0))
+    vals = []
+    for k in range(-127, 127):
+        c = np.float32(np.float32(k + 0.5) * s_eff)
+        x = c
+        for _ in range(6):
+            x = np.nextafter(x, np.float32(-np.inf), dtype=np.float32)
+        for _ in range(13):
+            vals.append(x)
+            x = np.nextafter(x, np.float32(np.inf), dtype=np.float32)
+        vals.append(np.float32(np.float32(k) * s_eff))
+    vals = np.asarray(vals, dtype=np.float32)
+    rng = np.random.default_rng(7)
+    n = 2 * 2 * 64 * 64
+    x = (rng.uniform(-1, 1, n).astype(np.float32) * amax).astype(np.float32)
+    x[: vals.size] = vals
+    x[-1] = amax
+    x[-2] = -amax
+    x = x.reshape(2, 2, 64, 64)
+    tx = torch.from_numpy(x).to("cuda:0")
+    ia = binding.IntAttn(device=0)
+    for kw in (dict(), dict(per_head=True), dict(q_block=16)):
+        got, sc = ia.quantize(tx, **kw)
+        torch.cuda.synchronize()
+        if "q_block" in kw:
+            want, wsc = oracle.quantize_row_groups(x, 16)
+        else:
+            want, wsc = oracle.quantize(x, per_head=bool(kw))
+        assert int((sc.cpu().numpy().reshape(-1) != wsc.reshape(-1)).sum()) == 0, kw
+        assert int((got.cpu().numpy() != want).sum()) == 0, kw
+    ia.close()
+
+
 def test_quantizer_batch_equals_separate_calls_and_the_oracle(torch_mod, oracle):
     """intattn_quantize_batch on three tensors of different shapes, element types and scale modes (a
     ragged tail, a strided source): the bytes and scales of the oracle quantizer, tensor by tensor."""

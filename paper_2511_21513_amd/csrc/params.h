@@ -13,7 +13,7 @@ enum IdxMode : int32_t {
     IDX_MAD24 = 1,  // (Delta' * mul + add) >> shift, 24-bit operands, 32-bit result
     IDX_MULHI24 = 2,// high 32 bits of the 48-bit product ((Delta' << pre) + add) * mul
     IDX_FP32 = 3,   // trunc(fma(Delta', top/c_int, 0.5)) in IEEE fp32 (idx_mul holds the bits of -top/c_int)
-    IDX_DEVICE = 4, // launchers only: each head's scheme (FP32 or FP64) is in its HeadParams, written on the device
+    IDX_DEVICE = 4, // launchers only: the scheme (TOP24 or FP64, one for all heads of the call) is in the HeadParams, written on the device
     IDX_ROW64 = 5,  // the fp64 scheme with parameters per block of query rows (FwdParams::row_table): finer
                     // quantization groups over the query rows, Sec. 3.3
     IDX_KGROUP = 7, // per-logit parameters: quantization groups over the key axis (Sec. 3.3), fp64 map per key block

@@ -165,10 +165,13 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     dma_k(1, Ks1);
 
     // ---- class of every row
-    // class n = 1, 2, 3: S > max(510 LUT_hat[8 n], 510), the row needs n register pairs; 4: the general path.
+    // class n = 1, 2, 3: S > max(510 LUT_hat[8 n], 510), the row needs n register pairs and no probability exceeds
+    // 127; 4: the whole table in four register pairs, for any row sum, with the probabilities stored as P - 128
+    // like the LDS tables (only when the table has exactly 2^5 entries, so that its last entry, which is 0 by
+    // Eq. lut16, can stand for hidden keys); 5: the tables in LDS.
     auto lut_at = [&](int k) { return (uint32_t)k <= top ? (p.lut[k / 4] >> (8 * (k % 4))) & 0xffu : 0u; };
     auto row_class = [&](uint32_t s_row, const HeadParams &hr) {
-        int c = 4;
+        int c = top == 31u ? 4 : 5;
 #pragma unroll
         for (int nn = 3; nn >= 1; --nn) {
             // first clipped distance whose index is 8 nn; its own index is the "probability 0" selector and
@@ -184,7 +187,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     const bool valid = row >= rlo && row < rhi;
     // the wave's path: the largest class among its rows (0: general path); rows outside [rlo, rhi) are inert
     const int my_cls = valid ? row_class((uint32_t)p.ws_row_sum[(int64_t)bh * LQ + (row - rlo)], MODE == IDX_ROW64 ? row_hp(row) : hp) : 1;
-    const int path = __any(my_cls == 4) ? 0 : __any(my_cls == 3) ? 3 : __any(my_cls == 2) ? 2 : 1;
+    const int path = __any(my_cls == 5) ? 0 : __any(my_cls == 4) ? 4 : __any(my_cls == 3) ? 3 : __any(my_cls == 2) ? 2 : 1;
 
     // Q fragments: row `row`, bytes [32 kb + 16 h, +16)
     v4i qf[RB][KB];
@@ -210,21 +213,22 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     // ---- register tables of the permute paths: tab[2 k], tab[2 k + 1] hold entries 8 k .. 8 k + 7 of
     // P_hat[idx] = round(255 LUT_hat[idx] / S); the clip of path n at the first distance of index 8 n
     RowIndex<MODE> rif[RB];
-    uint32_t tab[6] = {0u, 0u, 0u, 0u, 0u, 0u};
+    uint32_t tab[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
     rif[0] = ri[0];
     if (path != 0) {
         const int64_t cap = 8 * path > (int)top ? hrow.c_int : ((int64_t)(16 * path - 1) * hrow.c_int + 2 * (int64_t)top - 1) / (2 * (int64_t)top);
         rif[0].bound = ri[0].mx - (int)cap;
-        // quotients below 128 of numerators below 2^26: a single-precision estimate, corrected by at most one
+        // quotients below 256 of numerators below 2^24: a single-precision estimate, corrected by at most one
         const float rs = 1.0f / (float)(2u * sum[0]);
 #pragma unroll
-        for (int k = 0; k < 24; ++k) {
+        for (int k = 0; k < 32; ++k) {
             if (k < 8 * path) { // wave-uniform
                 const uint32_t num = 510u * lut_at(k) + sum[0], den = 2u * sum[0];
                 uint32_t q = (uint32_t)((float)num * rs);
                 if (q * den > num) --q;
                 if ((q + 1u) * den <= num) ++q;
-                tab[k / 4] |= (valid ? q : 0u) << (8 * (k % 4));
+                if (path == 4) q ^= 0x80u; // P - 128 as a byte; rows outside the problem: probability 0
+                tab[k / 4] |= (valid ? q : (path == 4 ? 0x80u : 0u)) << (8 * (k % 4));
             }
         }
     }
@@ -340,8 +344,13 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
             const uint32_t sa = lift(s4);
             return __builtin_amdgcn_perm(tab[1], tab[0], sa) & __builtin_amdgcn_perm(tab[3], tab[2], sa ^ 0x18181818u);
         }
+        if (NP == 3)
+            return __builtin_amdgcn_perm(tab[1], tab[0], lift(s4)) & __builtin_amdgcn_perm(tab[3], tab[2], lift(s4 ^ 0x08080808u)) &
+                   __builtin_amdgcn_perm(tab[5], tab[4], s4 ^ 0x10101010u);
+        // NP = 4: every index is 0 .. 31 (hidden keys take 31, whose entry is probability 0, the byte 0x80 in this
+        // path); pair k sees lift(s ^ 8 k), which is 0 .. 7 for its own indices and 16 .. 31 for all others
         return __builtin_amdgcn_perm(tab[1], tab[0], lift(s4)) & __builtin_amdgcn_perm(tab[3], tab[2], lift(s4 ^ 0x08080808u)) &
-               __builtin_amdgcn_perm(tab[5], tab[4], s4 ^ 0x10101010u);
+               __builtin_amdgcn_perm(tab[5], tab[4], lift(s4 ^ 0x10101010u)) & __builtin_amdgcn_perm(tab[7], tab[6], lift(s4 ^ 0x18181818u));
     };
     auto step = [&](auto masked_tag, auto path_tag, int j, const int8_t *Knext, const int8_t *Vcur, const v16i (&sc)[RB], v16i (&sn)[RB],
                     const uint32_t (&lp)[NEL], uint32_t (&lc)[NEL], v4i (&pfp)[RB], v4i (&pfc)[RB]) __attribute__((always_inline)) {
@@ -366,7 +375,8 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
                 // registers.  IDX_TOP24: the index is the top byte of the scaled score and is picked up
                 // there; the other schemes deliver it in the low byte.
                 constexpr uint32_t PAIR = MODE == IDX_TOP24 ? 0x0c0c0703u : 0x0c0c0400u;
-                constexpr uint32_t CLIPPED = MODE == IDX_TOP24 ? (uint32_t)(8 * NP) << 24 : (uint32_t)(8 * NP);
+                constexpr uint32_t HID = NP == 4 ? 31u : (uint32_t)(8 * NP); // index that stands for a hidden key
+                constexpr uint32_t CLIPPED = MODE == IDX_TOP24 ? HID << 24 : HID;
                 uint32_t ivp = 0;
 #pragma unroll
                 for (int w = sl * EPS; w < (sl + 1) * EPS; ++w) {
@@ -471,6 +481,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     if (path == 1) sweep(std::integral_constant<int, 1>{});
     else if (path == 2) sweep(std::integral_constant<int, 2>{});
     else if (path == 3) sweep(std::integral_constant<int, 3>{});
+    else if (path == 4) sweep(std::integral_constant<int, 4>{});
     else sweep(std::integral_constant<int, 0>{});
 
     // ================================================================= epilogue (Sec. 3.2: requantization)
@@ -486,7 +497,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     // the general path fed P - 128 to the signed MFMA: add 128 times the column sums of V back
-                    const int32_t acc = o[0][cb][4 * g + r] + (path == 0 ? 128 * colsum[ch0 + r] : 0);
+                    const int32_t acc = o[0][cb][4 * g + r] + ((path == 0 || path == 4) ? 128 * colsum[ch0 + r] : 0);
                     if (p.dbg_acc) p.dbg_acc[((int64_t)bh * LQ + (row - rlo)) * D + ch0 + r] = acc;
                     int64_t v = ((int64_t)acc * hrow.rq_mult + half) >> hrow.rq_shift;
                     v = v > 127 ? 127 : (v < -127 ? -127 : v);

@@ -83,9 +83,12 @@ int fwd_choose_variant(int variant, int B, int Hq, int L, int d)
 bool fwd_variant_known(int variant) { return variant == 0 || (variant >= 1 && variant <= 5) || variant == 9; }
 int fwd_rows_per_block(int variant) { return variant == 2 ? 256 : (variant == 3 ? 32 : 128); }
 
-int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, void *stream)
+int launch_fwd(const FwdParams &p_in, int d, int idx_mode, int variant, int stage, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
+    FwdParams p = p_in;
+    const int64_t k_bytes = (int64_t)p.Lk * d; // K of one (batch, KV head) group; V is as large
+    p.group_batch = fwd_group_batch(p.B, p.Hkv, 2 * k_bytes); // kernels that stream K and V
     const bool two_launches = variant == 4 || variant == 5;
     if (stage != 0 && !two_launches) return (int)hipErrorNotSupported;
     // all launches go to the same stream: V chunk sums first, then the sweeps
@@ -108,6 +111,7 @@ int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, 
         if (stage != 2) {
             FwdParams pab = p;
             pab.n_qtiles = fwd_row_tiles(p.row_lo, p.L, 256); // 64 query rows per wave in the first launch
+            pab.group_batch = fwd_group_batch(p.B, p.Hkv, k_bytes); // streams K only
             e = launch_shape<2, 2, 1>(pab, d, idx_mode, st);
             if (e != 0 || stage == 1) return e;
         }

@@ -16,8 +16,22 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 // Workgroups are dealt round-robin to the 8 XCDs (workgroup id mod 8), and each XCD has its
 // own L2.  All query heads that share one KV head -- i.e. one (batch, KV head) group -- are
 // therefore sent to the same XCD, so that K and V of the group are fetched into one L2 only.
-// Within an XCD the longest (latest) causal query tiles come first.
+// Within an XCD the groups are taken in batches of FwdParams::group_batch groups: inside a batch the longest
+// (latest) causal query tiles of all its groups come first, which balances the compute units; the batch is sized
+// so that the K and V its workgroups read at the same time fit the XCD's L2 (with the tiles of all 64 groups of
+// an XCD interleaved, and no sharing between query heads, sweep C of the batched prefill workload streamed
+// 4.3 TB/s of K and V from HBM and was bound by it).
 constexpr int NUM_XCD = 8;
+constexpr int64_t XCD_L2_BUDGET = 4 << 20; // bytes of K (and V) that a batch of groups may hold in flight: the L2 of an XCD
+                                           // (1 to 16 MiB measured within 3 % of each other on the batched prefill workload)
+
+// groups per batch for kernels that stream `bytes_per_group` of K (and V) per (batch, KV head) group
+inline int fwd_group_batch(int B, int Hkv, int64_t bytes_per_group)
+{
+    const int64_t gpx = ((int64_t)B * Hkv + NUM_XCD - 1) / NUM_XCD;
+    const int64_t fit = bytes_per_group > 0 ? XCD_L2_BUDGET / bytes_per_group : gpx;
+    return (int)(fit < 1 ? 1 : (fit > gpx ? gpx : fit));
+}
 
 __host__ __device__ inline int64_t fwd_grid_size(int B, int Hq, int Hkv, int n_qtiles)
 {
@@ -37,9 +51,13 @@ __device__ __forceinline__ WorkItem fwd_work_item(const FwdParams &p, int bid)
     const int groups = p.B * p.Hkv;
     const int groups_per_xcd = (groups + NUM_XCD - 1) / NUM_XCD;
     const int xcd = bid % NUM_XCD, slot = bid / NUM_XCD;
-    const int hg = slot % g;
-    const int j = (slot / g) % groups_per_xcd;
-    const int qt_rev = slot / (g * groups_per_xcd);
+    const int gb = p.group_batch > 0 ? min(p.group_batch, groups_per_xcd) : groups_per_xcd;
+    const int per_batch = g * gb * p.n_qtiles; // slots of a full batch; the last batch may hold fewer groups
+    const int batch = slot / per_batch, rem = slot - batch * per_batch;
+    const int gbb = min(gb, groups_per_xcd - batch * gb);
+    const int hg = rem % g;
+    const int j = batch * gb + (rem / g) % gbb;
+    const int qt_rev = rem / (g * gbb);
     const int gi = j * NUM_XCD + xcd; // (batch, KV head) group
     WorkItem w;
     w.valid = gi < groups;

@@ -56,6 +56,7 @@ struct FwdParams {
     double clip, sqrt_d;
     const int32_t *head_status;
     int32_t filter;             // 1: a workgroup whose head's HeadParams name another scheme than the kernel's returns at once
+    int32_t group_batch;        // (batch, KV head) groups of an XCD whose query tiles are interleaved; 0: all of them
     HeadParams hp0;             // the single parameter set when hp_table == nullptr
     uint32_t lut[16];           // LUT_hat, up to 64 bytes packed little-endian (unused tail is 0)
     int32_t *dbg_row_max, *dbg_row_sum, *dbg_acc;

@@ -223,9 +223,11 @@ __global__ __launch_bounds__(NT, 2) void quantonly_kernel(const FwdParams p)
 
 } // namespace
 
-int launch_quantonly(const FwdParams &p, int d, int /*variant*/, void *stream)
+int launch_quantonly(const FwdParams &p_in, int d, int /*variant*/, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
+    FwdParams p = p_in;
+    p.group_batch = fwd_group_batch(p.B, p.Hkv, 2 * (int64_t)p.Lk * d); // the same workgroup order as the integer path
     const dim3 grid((unsigned)fwd_grid_size(p.B, p.Hq, p.Hkv, p.n_qtiles)), block(NT);
     if (d == 64) {
         if (p.causal) hipLaunchKernelGGL((quantonly_kernel<64, true>), grid, block, 0, st, p);

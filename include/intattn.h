@@ -72,7 +72,10 @@ typedef struct {
                          rows with the keys split over its waves (small and mid-size problems); 4, 5 = two
                          launches (row max and row sum, then P.V) with the phase-ordered / the
                          software-pipelined second kernel;
-                         9 = the split-key kernels for few query rows wherever the shape allows.
+                         9 = the split-key path for few query rows wherever the shape allows (one launch
+                         whose workgroups meet at counters in device memory when the scales are host
+                         values and every clip threshold fits 16 bits, else four launches);
+                         10 = the split-key path with the four launches always.
                          Other values are rejected                                                    */
     int32_t reserved; /* must be 0                                                           */
 } intattn_config;
@@ -135,7 +138,12 @@ INTATTN_API int intattn_create(intattn_ctx **out, const intattn_config *cfg);
  * a later, larger call re-allocates (hipMalloc / hipFree wait for the device and are not for use
  * under graph capture: call intattn_reserve first, or use intattn_forward_noalloc); the
  * kernels of a call pass intermediate results through it, so calls on ONE context must not
- * overlap in time (same stream, or ordered by the caller); use one context per concurrent stream. */
+ * overlap in time (same stream, or ordered by the caller); use one context per concurrent stream.
+ * The one-launch split-key path (few query rows; see intattn_config.variant) lets the workgroups of a
+ * (batch, KV head) group wait for each other at a counter in device memory.  The wait is bounded (a few
+ * seconds): on a GPU that another process keeps so busy that a group is not scheduled together in that
+ * time, the workgroups give up, the call's output is undefined and so are later calls of this path on the
+ * context until intattn_reserve has cleared the counters; variant 10 never waits. */
 INTATTN_API int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
 
 /* Pre-sizes the context's device memory (workspace, per-head tables) for a problem of the shape and

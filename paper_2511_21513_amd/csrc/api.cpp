@@ -50,6 +50,8 @@ struct intattn_ctx {
     int32_t *d_ws = nullptr;
     size_t ws_cap = 0; // in int32 elements
     HeadParams *d_rowtab = nullptr; // parameters per block of query rows (scale_mode 2), grown on demand
+    uint32_t *d_dec_state = nullptr; // fused split-key kernel: DEC_STATE_WORDS per (batch, KV head) group, zero between launches
+    size_t dec_state_groups = 0;
     size_t rowtab_cap = 0;
     int32_t *d_status = nullptr; // per head: what the last derivation on the device found (intattn_dynamic_status)
     int status_cap = 0, status_n = 0;
@@ -606,7 +608,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
     // the query rows, packed into one MFMA operand of at most 31 rows).
     const int64_t packed_rows = (int64_t)p.group * p.L;
     const bool decode_ok = !comparator && stage == 0 && a->scale_mode < 2 && packed_rows <= 31 && (int64_t)a->B * a->Hkv <= 65535;
-    const bool decode = decode_ok && (ctx->variant == 9 || (ctx->variant == 0 && p.Lk >= 1024));
+    const bool decode = decode_ok && (ctx->variant == 9 || ctx->variant == 10 || (ctx->variant == 0 && p.Lk >= 1024));
 
     if (dynamic) {
         if (rm.no_alloc) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "intattn_forward_noalloc takes host scales");
@@ -724,22 +726,49 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
         // them resident at once, so no second, partly filled round of workgroups; five per unit measured
         // slower), at most 64
         const size_t tiles = groups * (nt32 / 4);
-        const size_t tpw = tiles / 1024 < 1 ? 1 : (tiles / 1024 > 64 ? 64 : tiles / 1024);
+        size_t tpw = tiles / 1024 < 1 ? 1 : (tiles / 1024 > 64 ? 64 : tiles / 1024);
+        // One launch, with the scores of a chunk held in LDS as 16-bit distances, where every clip threshold fits
+        // 16 bits and is known here (host scales); the chunk is then at most 64 / R tiles.  Callers that may not
+        // allocate, thresholds derived on the device, wider thresholds and variant 10 take the separate launches,
+        // which keep 32-bit scores in the workspace.
+        bool fused = !rm.no_alloc && !dynamic && ctx->variant != 10;
+        if (fused && !rm.reserve)
+            for (const HeadParams &h : dv.hp) fused = fused && h.c_int <= 65535;
+        if (fused && tpw > 64 / R) tpw = 64 / R;
         const size_t chunks = (nt32 / 4 + tpw - 1) / tpw;
         const size_t n_scores = groups * nt32 * 2 * R * 16, n_idx = groups * nt32 * 2 * R * 4, n_part = groups * chunks * 4 * R;
         const size_t n_acc = groups * chunks * R * (size_t)a->d;
-        rc = get_ws(n_scores + n_idx + 2 * n_part + n_acc);
+        rc = get_ws(fused && !rm.reserve ? n_acc : n_scores + n_idx + 2 * n_part + n_acc);
         if (rc) return rc;
+        if (fused && groups > ctx->dec_state_groups) {
+            uint32_t *stt = nullptr;
+            hipError_t e = hipMalloc((void **)&stt, groups * DEC_STATE_WORDS * sizeof(uint32_t));
+            if (e == hipSuccess && (e = hipMemset(stt, 0, groups * DEC_STATE_WORDS * sizeof(uint32_t))) != hipSuccess) (void)hipFree(stt);
+            if (e != hipSuccess) return fail(ctx, INTATTN_ERR_NOMEM, std::string("hipMalloc of the split-key group state: ") + hipGetErrorString(e));
+            if (ctx->d_dec_state) (void)hipFree(ctx->d_dec_state); // waits for work that may still use it
+            ctx->d_dec_state = stt;
+            ctx->dec_state_groups = groups;
+        } else if (fused && rm.reserve) {
+            // a launch that gave up waiting leaves counters behind: reserving again starts from zero
+            const hipError_t e = hipMemset(ctx->d_dec_state, 0, ctx->dec_state_groups * DEC_STATE_WORDS * sizeof(uint32_t));
+            if (e != hipSuccess) return hip_fail(ctx, e, "hipMemset(split-key group state)");
+        }
         if (rm.reserve) return INTATTN_OK;
         p.dec_rows = (int32_t)R;
         p.dec_nt32 = (int32_t)nt32;
         p.dec_tpw = (int32_t)tpw;
         p.dec_np = (int32_t)(chunks * 4);
-        p.dec_scores = d_ws; // every part is a multiple of 4 words: 16-byte alignment holds
-        p.dec_idx = p.dec_scores + n_scores;
-        p.dec_acc = p.dec_idx + n_idx;
-        p.dec_pmax = p.dec_acc + n_acc;
-        p.dec_psum = p.dec_pmax + n_part;
+        if (fused) {
+            p.dec_acc = d_ws;
+            p.dec_state = ctx->d_dec_state;
+            p.dec_spin_limit = 1 << 22;
+        } else {
+            p.dec_scores = d_ws; // every part is a multiple of 4 words: 16-byte alignment holds
+            p.dec_idx = p.dec_scores + n_scores;
+            p.dec_acc = p.dec_idx + n_idx;
+            p.dec_pmax = p.dec_acc + n_acc;
+            p.dec_psum = p.dec_pmax + n_part;
+        }
         const int herr = launch_decode(p, a->d, stream);
         if (herr != 0) return hip_fail(ctx, (hipError_t)herr, "launch(split-key forward)");
         ctx->err.clear();
@@ -1068,6 +1097,7 @@ void intattn_destroy(intattn_ctx *ctx)
         if (ctx->d_amax) (void)hipFree(ctx->d_amax);
         if (ctx->d_status) (void)hipFree(ctx->d_status);
         if (ctx->d_rowtab) (void)hipFree(ctx->d_rowtab);
+        if (ctx->d_dec_state) (void)hipFree(ctx->d_dec_state);
         for (Staging &sg : ctx->stage) {
             if (sg.pending) (void)hipEventSynchronize(sg.done);
             if (sg.done) (void)hipEventDestroy(sg.done);

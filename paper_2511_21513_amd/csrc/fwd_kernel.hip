@@ -80,7 +80,7 @@ int fwd_choose_variant(int variant, int B, int Hq, int L, int d)
     if (workgroups <= 256) return 3;
     return (d == 64 && L >= 1024) ? 3 : 1;
 }
-bool fwd_variant_known(int variant) { return variant == 0 || (variant >= 1 && variant <= 5) || variant == 9; }
+bool fwd_variant_known(int variant) { return variant == 0 || (variant >= 1 && variant <= 5) || variant == 9 || variant == 10; }
 int fwd_rows_per_block(int variant) { return variant == 2 ? 256 : (variant == 3 ? 32 : 128); }
 
 int launch_fwd(const FwdParams &p_in, int d, int idx_mode, int variant, int stage, void *stream)

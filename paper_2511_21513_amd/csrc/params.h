@@ -69,11 +69,17 @@ struct FwdParams {
     int32_t dec_rows, dec_nt32;
     int32_t dec_tpw, dec_np; // 128-key tiles per workgroup; partial maxima / sums per row = 4 * ceil(tiles / dec_tpw)
     int32_t *dec_scores, *dec_idx, *dec_pmax, *dec_psum, *dec_acc;
+    // fused split-key kernel: DEC_STATE_WORDS words per (batch, KV head) group, zero between launches (arrival and
+    // departure counters of the group's workgroups, row maxima, row sums); nullptr: the separate launches
+    uint32_t *dec_state;
+    int32_t dec_spin_limit; // polls of a group counter before a workgroup gives up (and raises the group's status word)
     // comparator only
     float alpha0, sv_over_so0;  // per-tensor values when the float tables are null
     const float *alpha_table;   // device [Hq]
     const float *svso_table;    // device [Hq]
 };
+
+constexpr int DEC_STATE_WORDS = 96; // [0] arrivals, [1] departures, [2] status, [32, 63) row maxima (biased), [64, 95) row sums
 
 // Arguments of the dynamic quantizer (Sec. 2.1, Eq. quant).
 struct QuantParams {

@@ -76,7 +76,7 @@ def test_create_rejects_bad_config(lib):
         assert lib.intattn_create(ctypes.byref(ctx), ctypes.byref(cfg)) == binding.ERR_UNSUPPORTED
     for cfg in (binding.Config(-1, 5, 0.0, 0, 0), binding.Config(-1, 5, float("nan"), 0, 0),
                 binding.Config(-1, 5, 6.6, 0, 7), binding.Config(-5, 5, 6.6, 0, 0),
-                binding.Config(-1, 5, 6.6, 10, 0), binding.Config(-1, 5, 6.6, -1, 0)):  # unknown kernel variants
+                binding.Config(-1, 5, 6.6, 11, 0), binding.Config(-1, 5, 6.6, -1, 0)):  # unknown kernel variants
         assert lib.intattn_create(ctypes.byref(ctx), ctypes.byref(cfg)) == binding.ERR_INVALID_ARG
         assert lib.intattn_last_error(None)
     lib.intattn_destroy(None)  # allowed

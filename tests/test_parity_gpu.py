@@ -636,6 +636,7 @@ SPLIT_KEY_SHAPES = [
     (4, 8, 4, 1, 20000, 128, True),      # 2512 tiles: two tiles per workgroup, odd tile count, ragged last tile
     (24, 8, 8, 2, 5000, 64, False),      # 7680 tiles: seven tiles per workgroup, no mask
     (1, 4, 4, 3, 131071, 64, True),      # the longest key sequence
+    (32, 16, 4, 1, 16384, 64, True),     # 16 tiles per workgroup with 4 packed rows: the largest chunk the single launch holds
 ]
 
 
@@ -653,25 +654,30 @@ def test_split_key_kernels_bit_exact(torch_mod, oracle, shape):
     q = rng.integers(-127, 128, size=(B, Hq, lq, d)).astype(np.int8)
     k = rng.integers(-127, 128, size=(B, Hkv, lk, d)).astype(np.int8)
     v = rng.integers(-127, 128, size=(B, Hkv, lk, d)).astype(np.int8)
-    s_q = rng.uniform(0.004, 0.02, Hq).astype(np.float32)
-    s_k = rng.uniform(0.004, 0.02, Hkv).astype(np.float32)
     s_v = rng.uniform(0.01, 0.05, Hkv).astype(np.float32)
     s_o = (s_v[np.arange(Hq) // (Hq // Hkv)] * np.float32(0.05)).astype(np.float32)
-    want = oracle.forward(q, k, v, s_q, s_k, s_v, s_o, causal=causal, per_head=True, taps=True, threads=16)
-    ia = binding.IntAttn(device=0, variant=9)
+    s_q0 = rng.uniform(0.004, 0.02, Hq).astype(np.float32)
+    s_k0 = rng.uniform(0.004, 0.02, Hkv).astype(np.float32)
     dev = torch.device("cuda:0")
     tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
-    got = ia.forward(tq, tk, tv, s_q, s_k, s_v, s_o, causal=causal, per_head=True, taps=True)
-    torch.cuda.synchronize()
-    for key in ("row_max", "row_sum", "acc", "out"):
-        assert int((got[key].cpu().numpy() != want[key]).sum()) == 0, key
-    sc = [torch.from_numpy(x).to(dev) for x in (s_q, s_k, s_v, s_o)]
-    out = torch.empty_like(tq)
-    args, keep = ia.make_args(tq, tk, tv, out, *sc, causal=causal, per_head=True, device_scales=True)
-    ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
-    torch.cuda.synchronize()
-    assert ia.dynamic_status() == 0 and int((out.cpu().numpy() != want["out"]).sum()) == 0
-    ia.close()
+    # thresholds of 10^5..10^6 (32-bit scores through the workspace: separate launches) and of a few thousand
+    # (one launch, 16-bit distances in LDS; variant 10 keeps the separate launches for those too)
+    for variant, mul in ((9, 1.0), (9, 8.0), (10, 8.0)):
+        s_q, s_k = (s_q0 * np.float32(mul)).astype(np.float32), (s_k0 * np.float32(mul)).astype(np.float32)
+        want = oracle.forward(q, k, v, s_q, s_k, s_v, s_o, causal=causal, per_head=True, taps=True, threads=16)
+        ia = binding.IntAttn(device=0, variant=variant)
+        for rep in range(2):  # the second call finds the group state as the first one left it
+            got = ia.forward(tq, tk, tv, s_q, s_k, s_v, s_o, causal=causal, per_head=True, taps=True)
+            torch.cuda.synchronize()
+            for key in ("row_max", "row_sum", "acc", "out"):
+                assert int((got[key].cpu().numpy() != want[key]).sum()) == 0, (variant, mul, rep, key)
+        sc = [torch.from_numpy(x).to(dev) for x in (s_q, s_k, s_v, s_o)]
+        out = torch.empty_like(tq)
+        args, keep = ia.make_args(tq, tk, tv, out, *sc, causal=causal, per_head=True, device_scales=True)
+        ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
+        torch.cuda.synchronize()
+        assert ia.dynamic_status() == 0 and int((out.cpu().numpy() != want["out"]).sum()) == 0, (variant, mul)
+        ia.close()
 
 
 # ---------------------------------------------------------------- IndexSoftmax as an operator

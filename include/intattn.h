@@ -143,7 +143,9 @@ INTATTN_API int intattn_create(intattn_ctx **out, const intattn_config *cfg);
  * (batch, KV head) group wait for each other at a counter in device memory.  The wait is bounded (a few
  * seconds): on a GPU that another process keeps so busy that a group is not scheduled together in that
  * time, the workgroups give up, the call's output is undefined and so are later calls of this path on the
- * context until intattn_reserve has cleared the counters; variant 10 never waits. */
+ * context until intattn_reserve has cleared the counters; variant 10 never waits.  (Testing aid: the
+ * environment variable INTATTN_SPLITKEY_SPIN_LIMIT, read at every such call, lowers the bound, counted in
+ * polls of the counter.) */
 INTATTN_API int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
 
 /* Pre-sizes the context's device memory (workspace, per-head tables) for a problem of the shape and

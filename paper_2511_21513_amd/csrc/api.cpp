@@ -6,6 +6,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -762,6 +763,11 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
             p.dec_acc = d_ws;
             p.dec_state = ctx->d_dec_state;
             p.dec_spin_limit = 1 << 22;
+            // testing aid: a smaller bound makes the workgroups give up, which the tests of that path need
+            if (const char *lim = std::getenv("INTATTN_SPLITKEY_SPIN_LIMIT")) {
+                const long v = std::strtol(lim, nullptr, 10);
+                p.dec_spin_limit = v < 0 ? 0 : (v > (1 << 22) ? (1 << 22) : (int32_t)v);
+            }
         } else {
             p.dec_scores = d_ws; // every part is a multiple of 4 words: 16-byte alignment holds
             p.dec_idx = p.dec_scores + n_scores;

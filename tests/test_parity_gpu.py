@@ -680,6 +680,47 @@ def test_split_key_kernels_bit_exact(torch_mod, oracle, shape):
         ia.close()
 
 
+@pytest.mark.gpu
+def test_split_key_wait_is_bounded_and_reserve_recovers(torch_mod, oracle, monkeypatch):
+    """The one-launch split-key path with its wait bound forced to a single poll: the workgroups of the large
+    groups give up instead of waiting, every kernel exits, and after intattn_reserve (which clears the
+    counters they left behind) the same context computes the oracle's bytes again."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    B, Hq, Hkv, lq, lk, d = 1, 4, 4, 3, 131071, 64  # 256 workgroups per (batch, KV head) group
+    rng = np.random.default_rng(77)
+    q = rng.integers(-127, 128, size=(B, Hq, lq, d)).astype(np.int8)
+    k = rng.integers(-127, 128, size=(B, Hkv, lk, d)).astype(np.int8)
+    v = rng.integers(-127, 128, size=(B, Hkv, lk, d)).astype(np.int8)
+    s_q = rng.uniform(0.03, 0.16, Hq).astype(np.float32)
+    s_k = rng.uniform(0.03, 0.16, Hkv).astype(np.float32)
+    s_v = rng.uniform(0.01, 0.05, Hkv).astype(np.float32)
+    want = oracle.forward(q, k, v, s_q, s_k, s_v, None, causal=True, per_head=True, threads=16)["out"]
+    dev = torch.device("cuda:0")
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+    out = torch.empty_like(tq)
+    ia = binding.IntAttn(device=0, variant=9)
+    args, keep = ia.make_args(tq, tk, tv, out, s_q, s_k, s_v, None, causal=True, per_head=True)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    ia.forward_args(args, stream)
+    torch.cuda.synchronize()
+    assert int((out.cpu().numpy() != want).sum()) == 0
+    print("bound of one poll", flush=True)
+    monkeypatch.setenv("INTATTN_SPLITKEY_SPIN_LIMIT", "0")
+    ia.forward_args(args, stream)
+    torch.cuda.synchronize()  # returns: nothing waits for ever (the output of this call is undefined)
+    monkeypatch.delenv("INTATTN_SPLITKEY_SPIN_LIMIT")
+    print("reserve, then the full bound again", flush=True)
+    ia.reserve(args)
+    out.zero_()
+    for _ in range(2):
+        ia.forward_args(args, stream)
+        torch.cuda.synchronize()
+        assert int((out.cpu().numpy() != want).sum()) == 0
+    ia.close()
+
+
 # ---------------------------------------------------------------- IndexSoftmax as an operator
 
 SOFTMAX_SHAPES = [

@@ -379,7 +379,7 @@ int validate(intattn_ctx *ctx, const intattn_args *a)
         if (s[2] < a->d) return fail(ctx, INTATTN_ERR_INVALID_ARG, "the L stride must be at least d");
         if (s[2] > (1 << 24)) return fail(ctx, INTATTN_ERR_UNSUPPORTED, "the L stride must not exceed 2^24 bytes");
     }
-    const int64_t rows_per_block = fwd_rows_per_block(fwd_choose_variant(ctx->variant, a->B, a->Hq, a->L, a->d));
+    const int64_t rows_per_block = fwd_rows_per_block(fwd_choose_variant(ctx->variant, a->B, a->Hq, a->L, Lk, a->d, a->causal));
     const int64_t n_qtiles = fwd_row_tiles(a->causal == 1 ? Lk - a->L : 0, a->L, (int)rows_per_block);
     // the launch grid pads the (batch, KV head) groups to a multiple of the 8 XCDs
     const int64_t groups_padded = (((int64_t)a->B * a->Hkv + 7) / 8) * 8;
@@ -595,7 +595,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
     p.causal = a->causal;
     p.group = a->Hq / a->Hkv;
     p.top = (1 << ctx->lut_bits) - 1;
-    int variant = fwd_choose_variant(ctx->variant, a->B, a->Hq, a->L, a->d);
+    int variant = fwd_choose_variant(ctx->variant, a->B, a->Hq, a->L, p.Lk, a->d, a->causal);
     if (variant == 5 && ctx->lut_bits > 5) variant = 4; // the pipelined sweep C holds 32-entry tables; same tiling otherwise
     if (a->scale_mode == 3) variant = 1;                // groups over the key axis: the single-launch kernel
     if (variant == 3 && a->scale_mode == 2) variant = 1; // the split-key single launch takes per-tensor / per-head parameters

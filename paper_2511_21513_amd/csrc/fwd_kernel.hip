@@ -66,17 +66,21 @@ int launch_colsum(const FwdParams &p, int d, int chunk, hipStream_t st)
 //   3  one launch, a workgroup per 32 query rows with the keys split over its four waves (fwd_splitk.hip)
 //   4  two launches: sweeps A+B (64 rows per wave), then sweep C (32 rows per wave), phase-ordered kernels
 //   5  as 4 with the software-pipelined sweep C kernel
-//   9  the split-key kernels of decode_kernel.hip whenever the shape allows them, else as 0
+//   9, 10  the split-key kernels of decode_kernel.hip (one launch / four launches) whenever the shape allows them, else as 0
 // Automatic choice among the tiled kernels, by measurement on shapes from 8 x 12 x 197 to 2 x 32 x 4096 (W = workgroups
-// of 128 query rows): W >= 1024 fills the chip with the two-launch path (variant 5); up to 256 the 128-row kernels
+// of 128 query rows): W >= 1024 fills the chip with the two-launch path (variant 5), short rows excepted; up to 256 the 128-row kernels
 // leave most SIMDs with one long-running wave and the split-key single launch (variant 3) is 1.1 to 2.3 times faster;
 // in between variant 3 still wins at d = 64 on long rows, otherwise variant 1 (at d = 128 the four waves of variant 3
 // each stream their own K fragments from L2, which costs more than the better fill gains).
-int fwd_choose_variant(int variant, int B, int Hq, int L, int d)
+int fwd_choose_variant(int variant, int B, int Hq, int L, int Lk, int d, int causal)
 {
-    if (variant != 0 && variant != 9) return variant;
-    const int64_t workgroups = (int64_t)B * Hq * ((L + 127) / 128);
-    if (workgroups >= 1024) return 5;
+    if (variant != 0 && variant != 9 && variant != 10) return variant;
+    const int nt = (L + 127) / 128;
+    const int64_t workgroups = (int64_t)B * Hq * nt;
+    // Short key runs (at most three key tiles per query tile on average: up to Lk = 384, or L = Lk = 640 under the
+    // causal mask): one launch, which stages K once, beats two (c2 at batch 512: 0.29 against 0.37 ms).
+    const int kt2 = causal ? 2 * ((Lk - L + 127) / 128) + nt + 1 : 2 * ((Lk + 127) / 128); // twice the average
+    if (workgroups >= 1024) return kt2 <= 6 ? 1 : 5;
     if (workgroups <= 256) return 3;
     return (d == 64 && L >= 1024) ? 3 : 1;
 }

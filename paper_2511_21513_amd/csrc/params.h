@@ -141,7 +141,7 @@ struct DeriveParams {
 int launch_fwd(const FwdParams &p, int d, int idx_mode, int variant, int stage, void *stream);
 int launch_sweep_c(const FwdParams &p, int d, int idx_mode, void *stream);
 int launch_fwd_splitk(const FwdParams &p, int d, int idx_mode, void *stream);
-int fwd_choose_variant(int variant, int B, int Hq, int L, int d); // resolves 0 (automatic) to a concrete variant
+int fwd_choose_variant(int variant, int B, int Hq, int L, int Lk, int d, int causal); // resolves 0 (automatic) to a concrete variant
 int fwd_rows_per_block(int variant);
 // tiles of `rows_per_tile` rows, aligned to multiples of it, that rows [row_lo, row_lo + n_rows) touch
 inline int fwd_row_tiles(int row_lo, int n_rows, int rows_per_tile)

@@ -342,19 +342,19 @@ __global__ __launch_bounds__(NT, 4) void decode_pv_kernel(const FwdParams p)
 
     // The four waves' sums meet in LDS (the V buffers are free now).  Register 4g + r of lane (n, h):
     // row n, channel 32 cb + 8 g + 4 h + r; row 31 holds the column sums of V over the wave's keys.
-    int32_t *part = (int32_t *)&Vw[0][0]; // 31 * D words fit: the four buffers hold 128 * D bytes = 32 * D words
-    for (int e = tid; e < R * D; e += NT) part[e] = 0;
+    int32_t *part = (int32_t *)&Vw[0][0]; // R + 1 <= 32 rows of D words fit: the four buffers hold 128 * D bytes
+    for (int e = tid; e < (R + 1) * D; e += NT) part[e] = 0;
     __syncthreads();
+    if (n < R || n == 31) { // row R of `part` takes the column sums
+        int32_t *dstl = part + (n < R ? n : R) * D + 4 * h;
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
+        for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int32_t cs = __shfl(o[cb][i], 31 + 32 * h);
-            if (n < R) atomicAdd(part + n * D + cb * 32 + 8 * (i >> 2) + 4 * h + (i & 3), o[cb][i] + 128 * cs); // LDS
-        }
+            for (int i = 0; i < 16; ++i) atomicAdd(dstl + cb * 32 + 8 * (i >> 2) + (i & 3), o[cb][i]); // LDS
+    }
     __syncthreads();
     int32_t *dst = p.dec_acc + ((int64_t)grp * (p.dec_np / 4) + chunk) * R * D;
-    for (int e = tid; e < R * D; e += NT) dst[e] = part[e];
+    for (int e = tid; e < R * D; e += NT) dst[e] = part[e] + 128 * part[R * D + e % D];
 }
 
 // One workgroup per output row: sum of the tiles' partial accumulators (thread = four channels of
@@ -556,28 +556,37 @@ __global__ __launch_bounds__(NT, 4) void decode_fused_kernel(const FwdParams p)
     {
         const uint8_t *lut_b = (const uint8_t *)lut_lds;
         const int nq = (t1 - t0) * 4 * 2 * R * 4; // units of four scores: q = ((sub-tile * 2 + h) * R + row) * 4 + g
+        int acc_row = -1; // a thread's sums go to LDS when its row changes (never, where R divides 64)
+        uint32_t acc = 0;
         for (int q = tid; q < nq; q += NT) {
             const int g = q & 3, rn = q >> 2, nn = rn % R, sh = rn / R, hh = sh & 1, tl = sh >> 1;
             const int key0 = (t0 * 4 + tl) * 32;
             const uint32_t lo = sc16[2 * q], hi = sc16[2 * q + 1];
-            const int64_t base = (int64_t)row_max[nn] - (int64_t)sub_max[tl * R + nn]; // >= 0 where the row sees a key of the sub-tile
+            // >= 0 and below 2^23 where the row sees a key of the sub-tile (meaningless, and unused, where it sees none)
+            const int base = (int)((uint32_t)row_max[nn] - (uint32_t)sub_max[tl * R + nn]);
             const int ri = row_i[nn];
             const HeadParams &hp = row_hp[nn];
+            const bool full = key0 + 32 <= p.Lk && (!p.causal || key0 + 31 <= p.row_lo + ri);
             uint32_t w = 0, sum = 0;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 uint32_t idx = 64u; // hidden key: probability 0
-                if (key_visible(p, key0 + acc_key(4 * g + j, hh), ri)) {
-                    const int64_t delta = base + (int64_t)(((j & 2) ? hi : lo) >> (16 * (j & 1)) & 0xffffu);
-                    const int dclip = delta < (int64_t)hp.c_int ? (int)delta : hp.c_int;
-                    idx = index_any(hp, -dclip, (uint32_t)p.top);
+                if (full || key_visible(p, key0 + acc_key(4 * g + j, hh), ri)) {
+                    const int delta = base + (int)(((j & 2) ? hi : lo) >> (16 * (j & 1)) & 0xffffu);
+                    idx = index_any(hp, -min(delta, hp.c_int), (uint32_t)p.top);
                     sum += lut_b[idx];
                 }
                 w |= idx << (8 * j);
             }
             sc16[2 * q] = w; // the unit's first word now holds its four indices
-            atomicAdd(row_sum + nn, (int32_t)sum); // LDS
+            if (nn != acc_row) {
+                if (acc_row >= 0) atomicAdd(row_sum + acc_row, (int32_t)acc); // LDS
+                acc_row = nn;
+                acc = 0;
+            }
+            acc += sum;
         }
+        if (acc_row >= 0) atomicAdd(row_sum + acc_row, (int32_t)acc); // LDS
     }
     lds_barrier();
     if (tid < R) atomicAdd(state + 64 + tid, (uint32_t)row_sum[tid]);
@@ -652,20 +661,21 @@ __global__ __launch_bounds__(NT, 4) void decode_fused_kernel(const FwdParams p)
     lds_barrier(); // every wave is done with its V buffer
 
     // the four waves' sums meet in LDS; row 31 of the operand holds the column sums of V over the wave's keys
-    int32_t *part = (int32_t *)&Vw[0][0]; // 31 * D words fit: the four buffers hold 128 * D bytes = 32 * D words
-    for (int e = tid; e < R * D; e += NT) part[e] = 0;
+    int32_t *part = (int32_t *)&Vw[0][0]; // R + 1 <= 32 rows of D words fit: the four buffers hold 128 * D bytes
+    for (int e = tid; e < (R + 1) * D; e += NT) part[e] = 0;
     lds_barrier();
+    if (n < R || n == 31) { // row R of `part` takes the column sums
+        int32_t *dst = part + (n < R ? n : R) * D + 4 * h;
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
+        for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int32_t cs = __shfl(o[cb][i], 31 + 32 * h);
-            if (n < R) atomicAdd(part + n * D + cb * 32 + 8 * (i >> 2) + 4 * h + (i & 3), o[cb][i] + 128 * cs); // LDS
-        }
+            for (int i = 0; i < 16; ++i) atomicAdd(dst + cb * 32 + 8 * (i >> 2) + (i & 3), o[cb][i]); // LDS
+    }
     lds_barrier();
     int32_t *acc_grp = p.dec_acc + (int64_t)grp * C * R * D;
     // (device-scope stores and loads for what another workgroup reads: they pass the L2 of the XCD)
-    for (int e = tid; e < R * D; e += NT) __hip_atomic_store(acc_grp + (int64_t)chunk * R * D + e, part[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int e = tid; e < R * D; e += NT)
+        __hip_atomic_store(acc_grp + (int64_t)chunk * R * D + e, part[e] + 128 * part[R * D + e % D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // departure: the last workgroup of the group finishes the rows
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_barrier();

@@ -73,8 +73,8 @@ typedef struct {
                          launches (row max and row sum, then P.V) with the phase-ordered / the
                          software-pipelined second kernel;
                          9 = the split-key path for few query rows wherever the shape allows (one launch
-                         whose workgroups meet at counters in device memory when the scales are host
-                         values and every clip threshold fits 16 bits, else four launches);
+                         whose workgroups meet at counters in device memory; intattn_forward_noalloc
+                         takes four launches);
                          10 = the split-key path with the four launches always.
                          Other values are rejected                                                    */
     int32_t reserved; /* must be 0                                                           */

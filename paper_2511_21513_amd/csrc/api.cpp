@@ -728,14 +728,15 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
         // slower), at most 64
         const size_t tiles = groups * (nt32 / 4);
         size_t tpw = tiles / 1024 < 1 ? 1 : (tiles / 1024 > 64 ? 64 : tiles / 1024);
-        // One launch, with the scores of a chunk held in LDS as 16-bit distances, where every clip threshold fits
-        // 16 bits and is known here (host scales); the chunk is then at most 64 / R tiles.  Callers that may not
-        // allocate, thresholds derived on the device, wider thresholds and variant 10 take the separate launches,
-        // which keep 32-bit scores in the workspace.
-        bool fused = !rm.no_alloc && !dynamic && ctx->variant != 10;
-        if (fused && !rm.reserve)
-            for (const HeadParams &h : dv.hp) fused = fused && h.c_int <= 65535;
-        if (fused && tpw > 64 / R) tpw = 64 / R;
+        // One launch, with the scores of a chunk held in LDS: as 16-bit distances where every clip threshold fits
+        // 16 bits and is known here (host scales; chunks of at most 64 / R tiles), else as raw 32-bit scores
+        // (chunks of at most 32 / R tiles).  Callers that may not allocate and variant 10 take the separate
+        // launches, which pass 32-bit scores through the workspace.
+        const bool fused = !rm.no_alloc && ctx->variant != 10;
+        bool wide = dynamic;
+        if (fused && !dynamic && !rm.reserve)
+            for (const HeadParams &h : dv.hp) wide = wide || h.c_int > 65535;
+        if (fused && tpw > (wide ? 32 : 64) / R) tpw = (wide ? 32 : 64) / R;
         const size_t chunks = (nt32 / 4 + tpw - 1) / tpw;
         const size_t n_scores = groups * nt32 * 2 * R * 16, n_idx = groups * nt32 * 2 * R * 4, n_part = groups * chunks * 4 * R;
         const size_t n_acc = groups * chunks * R * (size_t)a->d;
@@ -763,6 +764,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
             p.dec_acc = d_ws;
             p.dec_state = ctx->d_dec_state;
             p.dec_spin_limit = 1 << 22;
+            p.dec_wide = wide ? 1 : 0;
             // testing aid: a smaller bound makes the workgroups give up, which the tests of that path need
             if (const char *lim = std::getenv("INTATTN_SPLITKEY_SPIN_LIMIT")) {
                 const long v = std::strtol(lim, nullptr, 10);

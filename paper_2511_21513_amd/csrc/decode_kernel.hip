@@ -398,7 +398,8 @@ __global__ __launch_bounds__(NT) void decode_finish_kernel(const FwdParams p)
 // the output and the partial accumulators only.  A score is kept as a 16-bit distance below the row maximum of
 // its own 32-key sub-tile (saturated at 65535; the sub-tile's maximum is kept beside it): with the global row
 // maximum M, Delta = (M - sub-tile maximum) + distance, and a saturated distance is past every clip threshold
-// up to 65535, which the host checks.  Waiting is bounded: a workgroup whose group does not arrive within
+// up to 65535, which the host checks.  WIDE: the raw 32-bit scores instead, for thresholds that are larger or
+// known on the device only; the chunk a workgroup can hold is then half as long.  Waiting is bounded: a workgroup whose group does not arrive within
 // dec_spin_limit polls raises the group's status word and returns, so the grid always drains.
 // The last workgroup of a group to finish adds up the partial accumulators, requantizes, and clears the group's state.
 __device__ __forceinline__ uint32_t bias_i32(int32_t x) { return (uint32_t)x ^ 0x80000000u; }
@@ -429,13 +430,15 @@ __device__ __forceinline__ bool group_meet(uint32_t *ctr, uint32_t target, int l
     return *flag != 0;
 }
 
-template <int D>
+template <int D, bool WIDE>
 __global__ __launch_bounds__(NT, 4) void decode_fused_kernel(const FwdParams p)
 {
     constexpr int KB = D / 32, CB = D / 32;
     constexpr int NBLK = 32 * D / 1024, CPR = D / 16, RPB = 1024 / D;
-    constexpr int MAX_UNITS = 2048; // 8-byte units of four scores: 4 tpw * 2 R * 4 <= 2048, i.e. R * tpw <= 64
-    __shared__ __attribute__((aligned(16))) uint32_t sc16[MAX_UNITS * 2]; // [sub-tile][h][row][16] distances, 16 bits each; later the index words
+    constexpr int UW = WIDE ? 4 : 2; // words per unit of four scores
+    // 16 KiB: 4 tpw * 2 R * 4 units, i.e. R * tpw <= 64 (32 when WIDE); [sub-tile][h][row][16] distances of 16 bits
+    // each (scores of 32 when WIDE); later the first word of every unit holds its four table indices
+    __shared__ __attribute__((aligned(16))) uint32_t sc16[4096];
     __shared__ __attribute__((aligned(1024))) int8_t Vw[WAVES][32 * D];
     __shared__ int32_t sub_max[256]; // [sub-tile][row]: 4 tpw * R <= 256 entries
     __shared__ int32_t row_max[32], row_sum[32], row_i[32], meet_flag;
@@ -493,6 +496,14 @@ __global__ __launch_bounds__(NT, 4) void decode_fused_kernel(const FwdParams p)
         }
         sm = max(sm, __shfl_xor(sm, 32));
         m = max(m, sm);
+        if (WIDE) {
+            if (n < R) {
+                uint32_t *dst = sc16 + ((tl * 2 + h) * R + n) * 16;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) *(v4i *)(dst + 4 * g) = v4i{s[4 * g], s[4 * g + 1], s[4 * g + 2], s[4 * g + 3]};
+            }
+            return;
+        }
         uint32_t w[8];
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
@@ -561,9 +572,16 @@ __global__ __launch_bounds__(NT, 4) void decode_fused_kernel(const FwdParams p)
         for (int q = tid; q < nq; q += NT) {
             const int g = q & 3, rn = q >> 2, nn = rn % R, sh = rn / R, hh = sh & 1, tl = sh >> 1;
             const int key0 = (t0 * 4 + tl) * 32;
-            const uint32_t lo = sc16[2 * q], hi = sc16[2 * q + 1];
+            uint32_t u[4]; // the unit's distances (WIDE: its raw scores)
+            if (WIDE) {
+                const v4i x = *(const v4i *)(sc16 + 4 * q);
+                u[0] = (uint32_t)x[0], u[1] = (uint32_t)x[1], u[2] = (uint32_t)x[2], u[3] = (uint32_t)x[3];
+            } else {
+                const uint32_t lo = sc16[2 * q], hi = sc16[2 * q + 1];
+                u[0] = lo & 0xffffu, u[1] = lo >> 16, u[2] = hi & 0xffffu, u[3] = hi >> 16;
+            }
             // >= 0 and below 2^23 where the row sees a key of the sub-tile (meaningless, and unused, where it sees none)
-            const int base = (int)((uint32_t)row_max[nn] - (uint32_t)sub_max[tl * R + nn]);
+            const int base = WIDE ? row_max[nn] : (int)((uint32_t)row_max[nn] - (uint32_t)sub_max[tl * R + nn]);
             const int ri = row_i[nn];
             const HeadParams &hp = row_hp[nn];
             const bool full = key0 + 32 <= p.Lk && (!p.causal || key0 + 31 <= p.row_lo + ri);
@@ -572,13 +590,13 @@ __global__ __launch_bounds__(NT, 4) void decode_fused_kernel(const FwdParams p)
             for (int j = 0; j < 4; ++j) {
                 uint32_t idx = 64u; // hidden key: probability 0
                 if (full || key_visible(p, key0 + acc_key(4 * g + j, hh), ri)) {
-                    const int delta = base + (int)(((j & 2) ? hi : lo) >> (16 * (j & 1)) & 0xffffu);
+                    const int delta = WIDE ? base - (int)u[j] : base + (int)u[j]; // scores are below 2^22 in magnitude
                     idx = index_any(hp, -min(delta, hp.c_int), (uint32_t)p.top);
                     sum += lut_b[idx];
                 }
                 w |= idx << (8 * j);
             }
-            sc16[2 * q] = w; // the unit's first word now holds its four indices
+            sc16[UW * q] = w; // the unit's first word now holds its four indices
             if (nn != acc_row) {
                 if (acc_row >= 0) atomicAdd(row_sum + acc_row, (int32_t)acc); // LDS
                 acc_row = nn;
@@ -627,10 +645,10 @@ __global__ __launch_bounds__(NT, 4) void decode_fused_kernel(const FwdParams p)
         }
         v4i pf = {0, 0, 0, 0};
         if (n < R) {
-            const uint32_t *iw = sc16 + ((((t - t0) * 4 + wave) * 2 + h) * R + n) * 8; // index words of the lane's four units
+            const uint32_t *iw = sc16 + ((((t - t0) * 4 + wave) * 2 + h) * R + n) * 4 * UW; // index words of the lane's four units
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const uint32_t ix = iw[2 * g];
+                const uint32_t ix = iw[UW * g];
                 uint32_t wq = 0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) wq |= (uint32_t)pt[(ix >> (8 * j)) & 0xffu] << (8 * j);
@@ -711,8 +729,9 @@ int launch_d(const FwdParams &p, hipStream_t st)
 {
     const dim3 grid((unsigned)(p.dec_np / 4), (unsigned)(p.B * p.Hkv)), block(NT);
     if (p.dec_state) {
-        if (p.dec_rows * p.dec_tpw > 64) return (int)hipErrorInvalidValue;
-        hipLaunchKernelGGL(decode_fused_kernel<D>, grid, block, 0, st, p);
+        if (p.dec_rows * p.dec_tpw > (p.dec_wide ? 32 : 64)) return (int)hipErrorInvalidValue;
+        if (p.dec_wide) hipLaunchKernelGGL((decode_fused_kernel<D, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((decode_fused_kernel<D, false>), grid, block, 0, st, p);
         return (int)hipGetLastError();
     }
     hipLaunchKernelGGL(decode_scores_kernel<D>, grid, block, 0, st, p);

@@ -73,6 +73,7 @@ struct FwdParams {
     // departure counters of the group's workgroups, row maxima, row sums); nullptr: the separate launches
     uint32_t *dec_state;
     int32_t dec_spin_limit; // polls of a group counter before a workgroup gives up (and raises the group's status word)
+    int32_t dec_wide;       // 1: the fused kernel keeps raw 32-bit scores in LDS (any clip threshold; chunks half as long)
     // comparator only
     float alpha0, sv_over_so0;  // per-tensor values when the float tables are null
     const float *alpha_table;   // device [Hq]

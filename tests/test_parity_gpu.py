@@ -660,8 +660,8 @@ def test_split_key_kernels_bit_exact(torch_mod, oracle, shape):
     s_k0 = rng.uniform(0.004, 0.02, Hkv).astype(np.float32)
     dev = torch.device("cuda:0")
     tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
-    # thresholds of 10^5..10^6 (32-bit scores through the workspace: separate launches) and of a few thousand
-    # (one launch, 16-bit distances in LDS; variant 10 keeps the separate launches for those too)
+    # thresholds of 10^5..10^6 (one launch with 32-bit scores in LDS) and of a few thousand (one launch, 16-bit
+    # distances in LDS; the device-scale entry takes 32-bit scores); variant 10: the four launches
     for variant, mul in ((9, 1.0), (9, 8.0), (10, 8.0)):
         s_q, s_k = (s_q0 * np.float32(mul)).astype(np.float32), (s_k0 * np.float32(mul)).astype(np.float32)
         want = oracle.forward(q, k, v, s_q, s_k, s_v, s_o, causal=causal, per_head=True, taps=True, threads=16)

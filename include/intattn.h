@@ -164,7 +164,12 @@ INTATTN_API int intattn_reserve(intattn_ctx *ctx, const intattn_args *args, int3
  * or more than 512 query heads with per-head scales) is rejected with INTATTN_ERR_UNSUPPORTED and a
  * message naming both sizes.  The array is shared by every context on the GPU and keeps the last
  * call's contents (everything a call reads it has written first): calls that overlap in time on one
- * GPU race -- order them on one stream. */
+ * GPU race -- order them on one stream.
+ * Under graph capture: with per-tensor scales (scale_mode 0) the call records kernels only.  With per-head
+ * scales it also copies the parameter table from a host staging buffer of the context on every call, and a
+ * replayed graph would copy whatever that buffer holds by then: capture intattn_forward instead (after one
+ * eager call with the same scales the table is resident and the captured call records kernels only), or
+ * intattn_forward_dynamic, which derives the parameters on the device. */
 #define INTATTN_NOALLOC_SCRATCH_BYTES (4u << 20)
 INTATTN_API int intattn_forward_noalloc(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);
 

@@ -186,6 +186,22 @@ __device__ __forceinline__ void publish_tiles_barrier()
 // lane of half-wave h; the same key sits in byte i of that lane's next B operand.
 __device__ __forceinline__ int acc_key(int i, int h) { return 8 * (i >> 2) + 4 * h + (i & 3); }
 
+// Output requantization (Sec. 3.2): clamp(floor((acc * M + 2^(sh-1)) / 2^sh), -127, 127) with M < 2^31 and
+// 1 <= sh <= 62.  For sh >= 33 (every ratio s_V / (255 s_O) below 1/4) the rounding addend lies wholly in the high
+// word of the 64-bit product and the low word cannot change the floor of a division by 2^(sh-32) >= 2, so the
+// high word alone gives the same value: multiply-high, add, shift.  FAST is the caller's statement that sh >= 33.
+template <bool FAST> __device__ __forceinline__ int requant(int32_t acc, int32_t M, int32_t sh)
+{
+    int v;
+    if (FAST) {
+        v = (__mulhi(acc, M) + (1 << (sh - 33))) >> (sh - 32);
+    } else {
+        const int64_t w = ((int64_t)acc * M + (1ll << (sh - 1))) >> sh;
+        v = w > 127 ? 127 : (w < -127 ? -127 : (int)w);
+    }
+    return v > 127 ? 127 : (v < -127 ? -127 : v);
+}
+
 // XOR swizzles of the 16-byte chunk index inside a key row.
 // K fragments are read with ds_read_b128, lane -> key row, all lanes of a half-wave on the same
 // chunk.  The LDS serves 16 consecutive lanes (256 bytes, all 64 banks) per clock, so the 16 rows

@@ -164,29 +164,57 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     dma_v(0, Vs0);
     dma_k(1, Ks1);
 
+    auto lut_at = [&](int k) { return (uint32_t)k <= top ? (p.lut[k / 4] >> (8 * (k % 4))) & 0xffu : 0u; };
+    // The clip points of classes 1 .. 3, per head: cap[n] = the first clipped distance whose index is >= 8 n, i.e. the
+    // smallest x with 2 top x >= (16 n - 1) c_int (c_int where the table ends before index 8 n); ok[n]: that distance's
+    // own index, the "probability 0" selector of the class, is exactly 8 n (thresholds below two per index step can
+    // jump past it).  No integer division: the quotient comes from a double-precision estimate (the numerator is
+    // below 2^36, so the estimate is off by one at most) and is corrected against the exact products.
+    struct ClassCaps {
+        int32_t cap[4];
+        bool ok[4];
+    };
+    auto class_caps = [&](const HeadParams &hr) {
+        ClassCaps cc;
+        const double inv = __builtin_amdgcn_rcp((double)(2u * top));
+        const int64_t den = 2 * (int64_t)top, c2 = 2 * (int64_t)hr.c_int;
+        cc.cap[0] = hr.c_int;
+        cc.ok[0] = false;
+#pragma unroll
+        for (int nn = 1; nn <= 3; ++nn) {
+            cc.cap[nn] = hr.c_int;
+            cc.ok[nn] = true;
+            if (8 * nn <= (int)top) {
+                const int64_t num = (int64_t)(16 * nn - 1) * hr.c_int;
+                int64_t x = (int64_t)(uint32_t)((double)num * inv); // below c_int: 16 n - 1 < 2 top here
+                if (den * x < num) ++x;
+                if (den * x < num) ++x;
+                if (x > 0 && den * (x - 1) >= num) --x;
+                const int64_t at = den * x + hr.c_int; // 2 c_int (index of x) <= at < 2 c_int (index of x + 1)
+                cc.ok[nn] = x <= hr.c_int && at >= 8 * nn * c2 && at < (8 * nn + 1) * c2;
+                cc.cap[nn] = (int32_t)min(x, (int64_t)hr.c_int);
+            }
+        }
+        return cc;
+    };
     // ---- class of every row
     // class n = 1, 2, 3: S > max(510 LUT_hat[8 n], 510), the row needs n register pairs and no probability exceeds
     // 127; 4: the whole table in four register pairs, for any row sum, with the probabilities stored as P - 128
     // like the LDS tables (only when the table has exactly 2^5 entries, so that its last entry, which is 0 by
     // Eq. lut16, can stand for hidden keys); 5: the tables in LDS.
-    auto lut_at = [&](int k) { return (uint32_t)k <= top ? (p.lut[k / 4] >> (8 * (k % 4))) & 0xffu : 0u; };
-    auto row_class = [&](uint32_t s_row, const HeadParams &hr) {
+    auto row_class = [&](uint32_t s_row, const ClassCaps &cc) {
         int c = top == 31u ? 4 : 5;
 #pragma unroll
-        for (int nn = 3; nn >= 1; --nn) {
-            // first clipped distance whose index is 8 nn; its own index is the "probability 0" selector and
-            // must be exactly 8 nn (thresholds below two per index step can jump past it)
-            const int64_t cap = 8 * nn > (int)top ? hr.c_int : ((int64_t)(16 * nn - 1) * hr.c_int + 2 * (int64_t)top - 1) / (2 * (int64_t)top);
-            const bool exact = 8 * nn > (int)top || (cap <= hr.c_int && (2 * (int64_t)top * cap + hr.c_int) / (2 * (int64_t)hr.c_int) == 8 * nn);
-            if (exact && s_row > max(510u * lut_at(8 * nn), 510u)) c = nn;
-        }
+        for (int nn = 3; nn >= 1; --nn)
+            if (cc.ok[nn] && s_row > max(510u * lut_at(8 * nn), 510u)) c = nn;
         return c;
     };
     const int qw0 = q0 + 32 * wave;
     const int row = qw0 + n; // this lane's query row
     const bool valid = row >= rlo && row < rhi;
     // the wave's path: the largest class among its rows (0: general path); rows outside [rlo, rhi) are inert
-    const int my_cls = valid ? row_class((uint32_t)p.ws_row_sum[(int64_t)bh * LQ + (row - rlo)], MODE == IDX_ROW64 ? row_hp(row) : hp) : 1;
+    const ClassCaps caps = class_caps(MODE == IDX_ROW64 ? row_hp(row) : hp);
+    const int my_cls = valid ? row_class((uint32_t)p.ws_row_sum[(int64_t)bh * LQ + (row - rlo)], caps) : 1;
     const int path = __any(my_cls == 5) ? 0 : __any(my_cls == 4) ? 4 : __any(my_cls == 3) ? 3 : __any(my_cls == 2) ? 2 : 1;
 
     // Q fragments: row `row`, bytes [32 kb + 16 h, +16)
@@ -216,8 +244,8 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     uint32_t tab[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
     rif[0] = ri[0];
     if (path != 0) {
-        const int64_t cap = 8 * path > (int)top ? hrow.c_int : ((int64_t)(16 * path - 1) * hrow.c_int + 2 * (int64_t)top - 1) / (2 * (int64_t)top);
-        rif[0].bound = ri[0].mx - (int)cap;
+        const int cap = path == 1 ? caps.cap[1] : (path == 2 ? caps.cap[2] : (path == 3 ? caps.cap[3] : hrow.c_int));
+        rif[0].bound = ri[0].mx - cap;
         // quotients below 256 of numerators below 2^24: a single-precision estimate, corrected by at most one
         const float rs = 1.0f / (float)(2u * sum[0]);
 #pragma unroll
@@ -485,9 +513,12 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     else sweep(std::integral_constant<int, 0>{});
 
     // ================================================================= epilogue (Sec. 3.2: requantization)
-    if (valid) {
+    // (instantiated for the shift range and for the debug tap, so that the 64 values of a lane meet no branch)
+    auto epilogue = [&](auto fast_tag, auto dbg_tag) __attribute__((always_inline)) {
+        constexpr bool FAST = decltype(fast_tag)::value, DBG = decltype(dbg_tag)::value;
         int8_t *Op = p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)(row - rlo) * p.os[2];
-        const int64_t half = 1ll << (hrow.rq_shift - 1);
+        // the general path fed P - 128 to the signed MFMA: add 128 times the column sums of V back
+        const int32_t cfac = (path == 0 || path == 4) ? 128 : 0;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
 #pragma unroll
@@ -496,15 +527,22 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
                 uint32_t packed = 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    // the general path fed P - 128 to the signed MFMA: add 128 times the column sums of V back
-                    const int32_t acc = o[0][cb][4 * g + r] + ((path == 0 || path == 4) ? 128 * colsum[ch0 + r] : 0);
-                    if (p.dbg_acc) p.dbg_acc[((int64_t)bh * LQ + (row - rlo)) * D + ch0 + r] = acc;
-                    int64_t v = ((int64_t)acc * hrow.rq_mult + half) >> hrow.rq_shift;
-                    v = v > 127 ? 127 : (v < -127 ? -127 : v);
-                    packed |= ((uint32_t)(int)v & 0xffu) << (8 * r);
+                    const int32_t acc = o[0][cb][4 * g + r] + cfac * colsum[ch0 + r];
+                    if (DBG) p.dbg_acc[((int64_t)bh * LQ + (row - rlo)) * D + ch0 + r] = acc;
+                    packed |= ((uint32_t)requant<FAST>(acc, hrow.rq_mult, hrow.rq_shift) & 0xffu) << (8 * r);
                 }
                 *(uint32_t *)(Op + ch0) = packed;
             }
+        }
+    };
+    if (valid) {
+        const bool fast = hrow.rq_shift >= 33;
+        if (p.dbg_acc) {
+            if (fast) epilogue(std::true_type{}, std::true_type{});
+            else epilogue(std::false_type{}, std::true_type{});
+        } else {
+            if (fast) epilogue(std::true_type{}, std::false_type{});
+            else epilogue(std::false_type{}, std::false_type{});
         }
     }
 }

@@ -379,14 +379,11 @@ __global__ __launch_bounds__(NT) void decode_finish_kernel(const FwdParams p)
 #pragma unroll
     for (int k = 1; k < TL; ++k) a += *(const v4i *)&red[k][c0];
     const HeadParams hp = p.hp_table[hq];
-    const int64_t half = 1ll << (hp.rq_shift - 1);
     uint32_t packed = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         if (p.dbg_acc) p.dbg_acc[(int64_t)row * D + c0 + q] = a[q];
-        int64_t v = ((int64_t)a[q] * hp.rq_mult + half) >> hp.rq_shift;
-        v = v > 127 ? 127 : (v < -127 ? -127 : v);
-        packed |= ((uint32_t)(int)v & 0xffu) << (8 * q);
+        packed |= ((uint32_t)requant_any(a[q], hp.rq_mult, hp.rq_shift) & 0xffu) << (8 * q);
     }
     *(uint32_t *)(p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)i * p.os[2] + c0) = packed;
 }
@@ -709,14 +706,11 @@ __global__ __launch_bounds__(NT, 4) void decode_fused_kernel(const FwdParams p)
                 a[q] += __hip_atomic_load(acc_grp + ((int64_t)c * R + r) * D + c0 + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int hq = kvh * p.group + r / p.L, i = r % p.L;
         const HeadParams &hp = row_hp[r];
-        const int64_t half = 1ll << (hp.rq_shift - 1);
         uint32_t packed = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             if (p.dbg_acc) p.dbg_acc[((int64_t)(b * p.Hq + hq) * p.L + i) * D + c0 + q] = a[q];
-            int64_t v = ((int64_t)a[q] * hp.rq_mult + half) >> hp.rq_shift;
-            v = v > 127 ? 127 : (v < -127 ? -127 : v);
-            packed |= ((uint32_t)(int)v & 0xffu) << (8 * q);
+            packed |= ((uint32_t)requant_any(a[q], hp.rq_mult, hp.rq_shift) & 0xffu) << (8 * q);
         }
         *(uint32_t *)(p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)i * p.os[2] + c0) = packed;
     }

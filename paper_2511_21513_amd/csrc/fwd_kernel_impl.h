@@ -591,7 +591,6 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
         int8_t *Op = p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)(row - rlo) * p.os[2];
         HeadParams he = (MODE == IDX_ROW64 || KG) ? row_hp(row) : hp;
         if (KG && p.head_status[hq] != 0) he.rq_mult = 0; // an unusable scale somewhere in the head: all zeros
-        const int64_t half = 1ll << (he.rq_shift - 1);
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
 #pragma unroll
@@ -602,9 +601,7 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
                 for (int r = 0; r < 4; ++r) {
                     const int32_t acc = o[rb][cb][4 * g + r] + 128 * colsum[ch0 + r];
                     if (p.dbg_acc) p.dbg_acc[((int64_t)bh * LQ + (row - rlo)) * D + ch0 + r] = acc;
-                    int64_t v = ((int64_t)acc * he.rq_mult + half) >> he.rq_shift;
-                    v = v > 127 ? 127 : (v < -127 ? -127 : v);
-                    packed |= ((uint32_t)(int)v & 0xffu) << (8 * r);
+                    packed |= ((uint32_t)requant_any(acc, he.rq_mult, he.rq_shift) & 0xffu) << (8 * r);
                 }
                 *(uint32_t *)(Op + ch0) = packed;
             }

@@ -272,7 +272,6 @@ __global__ __launch_bounds__(NT, D == 64 ? 4 : 2) void fwd_splitk_kernel(const F
     const int er = tid >> 3, ec0 = (tid & 7) * CPT, erow = q0 + er;
     if (erow >= rlo && erow < rhi) {
         int8_t *Op = p.out + (int64_t)b * p.os[0] + (int64_t)hq * p.os[1] + (int64_t)(erow - rlo) * p.os[2];
-        const int64_t half = 1ll << (hp.rq_shift - 1);
 #pragma unroll
         for (int c4 = 0; c4 < CPT; c4 += 4) {
             uint32_t packed = 0;
@@ -281,9 +280,7 @@ __global__ __launch_bounds__(NT, D == 64 ? 4 : 2) void fwd_splitk_kernel(const F
                 const int ch = ec0 + c4 + r;
                 const int32_t acc = acc_lds[er][ch];
                 if (p.dbg_acc) p.dbg_acc[((int64_t)bh * LQ + (erow - rlo)) * D + ch] = acc;
-                int64_t v = ((int64_t)acc * hp.rq_mult + half) >> hp.rq_shift;
-                v = v > 127 ? 127 : (v < -127 ? -127 : v);
-                packed |= ((uint32_t)(int)v & 0xffu) << (8 * r);
+                packed |= ((uint32_t)requant_any(acc, hp.rq_mult, hp.rq_shift) & 0xffu) << (8 * r);
             }
             *(uint32_t *)(Op + ec0 + c4) = packed;
         }

@@ -202,6 +202,12 @@ template <bool FAST> __device__ __forceinline__ int requant(int32_t acc, int32_t
     return v > 127 ? 127 : (v < -127 ? -127 : v);
 }
 
+// the same with the form chosen at run time (sh is uniform over a head)
+__device__ __forceinline__ int requant_any(int32_t acc, int32_t M, int32_t sh)
+{
+    return sh >= 33 ? requant<true>(acc, M, sh) : requant<false>(acc, M, sh);
+}
+
 // XOR swizzles of the 16-byte chunk index inside a key row.
 // K fragments are read with ds_read_b128, lane -> key row, all lanes of a half-wave on the same
 // chunk.  The LDS serves 16 consecutive lanes (256 bytes, all 64 banks) per clock, so the 16 rows

@@ -721,6 +721,41 @@ def test_split_key_wait_is_bounded_and_reserve_recovers(torch_mod, oracle, monke
     ia.close()
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("ratio", [1.0, 1 / 30.0, 1 / 50.0, 1 / 64.0, 1 / 100.0, 1 / 1000.0, 255.0], ids=lambda r: f"so_over_sv_{r:.4g}")
+def test_requantization_shift_range_bit_exact(torch_mod, oracle, ratio):
+    """Output scales from s_V * 255 down to s_V / 1000: requantization shifts on both sides of 33, where the
+    kernels change from the high word of the product to the 64-bit form, and outputs that saturate at +-127;
+    tiled kernels, split-key kernels and device-resident scales."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    dev = torch.device("cuda:0")
+    p = inputs.random_problem(17, 2, 4, 2, 300, 128, True, per_head=True, spread=1.1)
+    s_o = (np.repeat(p.s_v, p.Hq // p.Hkv) * np.float32(ratio)).astype(np.float32)
+    want = oracle.forward(p.q, p.k, p.v, p.s_q, p.s_k, p.s_v, s_o, causal=True, per_head=True, threads=8)["out"]
+    q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
+    for variant in (1, 3, 5):
+        ia = binding.IntAttn(device=0, variant=variant)
+        got = ia.forward(q, k, v, p.s_q, p.s_k, p.s_v, s_o, causal=True, per_head=True)
+        torch.cuda.synchronize()
+        assert int((got.cpu().numpy() != want).sum()) == 0, variant
+        sc = [torch.from_numpy(x).to(dev) for x in (p.s_q, p.s_k, p.s_v, s_o)]
+        out = torch.empty_like(q)
+        args, keep = ia.make_args(q, k, v, out, *sc, causal=True, per_head=True, device_scales=True)
+        ia.forward_dynamic_args(args, torch.cuda.current_stream(dev).cuda_stream)
+        torch.cuda.synchronize()
+        assert ia.dynamic_status() == 0 and int((out.cpu().numpy() != want).sum()) == 0, ("device scales", variant)
+        ia.close()
+    q1 = torch.from_numpy(np.ascontiguousarray(p.q[:, :, -2:])).to(dev)
+    for variant in (9, 10):
+        ia = binding.IntAttn(device=0, variant=variant)
+        got = ia.forward(q1, k, v, p.s_q, p.s_k, p.s_v, s_o, causal=True, per_head=True)
+        torch.cuda.synchronize()
+        assert int((got.cpu().numpy() != want[:, :, -2:]).sum()) == 0, variant
+        ia.close()
+
+
 # ---------------------------------------------------------------- IndexSoftmax as an operator
 
 SOFTMAX_SHAPES = [

@@ -285,7 +285,7 @@ __global__ __launch_bounds__(NT, 4) void decode_pv_kernel(const FwdParams p)
         const int r = e / 65, idx = e % 65;
         const uint32_t S = (uint32_t)row_sum[r]; // >= 255: the key of the row maximum is visible
         const uint32_t ev = idx < 64 ? ((const uint8_t *)lut_lds)[idx] : 0u;
-        PT[r][idx] = (uint8_t)((((510u * ev + S) / (2u * S)) ^ 0x80u) & 0xffu);
+        PT[r][idx] = (uint8_t)((prob_u8(ev, S, __builtin_amdgcn_rcpf((float)(2u * S))) ^ 0x80u) & 0xffu);
     }
     lds_barrier(); // the tables are in LDS
     const uint8_t *pt = PT[n < R ? n : 0];
@@ -619,7 +619,7 @@ __global__ __launch_bounds__(NT, 4) void decode_fused_kernel(const FwdParams p)
         const int r = e / 65, idx = e % 65;
         const uint32_t S = (uint32_t)row_sum[r]; // >= 255: the key of the row maximum is visible
         const uint32_t ev = idx < 64 ? ((const uint8_t *)lut_lds)[idx] : 0u;
-        PT[r][idx] = (uint8_t)((((510u * ev + S) / (2u * S)) ^ 0x80u) & 0xffu);
+        PT[r][idx] = (uint8_t)((prob_u8(ev, S, __builtin_amdgcn_rcpf((float)(2u * S))) ^ 0x80u) & 0xffu);
     }
     lds_barrier();
 

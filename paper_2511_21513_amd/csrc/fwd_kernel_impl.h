@@ -484,11 +484,10 @@ __global__ __launch_bounds__(NT, PH == 1 ? (RB * KT <= 2 ? 4 : 3) : (RB == 1 ? (
         if (sum[rb] == 0) sum[rb] = 1; // only rows outside [rlo, rhi); never stored
         // per-row probability table: PT[idx] = round(255 * LUT_hat[idx] / sum) - 128 as a byte
         uint32_t *pt = PT + (wave * RB + rb) * NIDX * 32;
+        const float inv_2s = __builtin_amdgcn_rcpf((float)(2u * sum[rb]));
         for (int j = 0; j < NIDX / 2; ++j) {
             const int kidx = (NIDX / 2) * h + j;
-            const uint32_t e = lut_b[kidx];
-            const uint32_t pr = (510u * e + sum[rb]) / (2u * sum[rb]);
-            pt[kidx * 32 + n] = (pr ^ 0x80u) & 0xffu;
+            pt[kidx * 32 + n] = (prob_u8(lut_b[kidx], sum[rb], inv_2s) ^ 0x80u) & 0xffu;
         }
         const int row = qw0 + 32 * rb + n;
         if (!KG && p.dbg_row_max && h == 0 && row >= rlo && row < rhi) p.dbg_row_max[(int64_t)bh * LQ + (row - rlo)] = mx[rb];

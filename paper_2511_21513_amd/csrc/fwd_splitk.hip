@@ -180,7 +180,7 @@ __global__ __launch_bounds__(NT, D == 64 ? 4 : 2) void fwd_splitk_kernel(const F
         const uint32_t S = (uint32_t)red[1][0][r] + (uint32_t)red[1][1][r] + (uint32_t)red[1][2][r] + (uint32_t)red[1][3][r];
         const uint32_t Sd = S ? S : 1u;
         const uint32_t ev = (uint32_t)idx <= top ? lut_b[idx] : 0u;
-        PT[e] = (((510u * ev + Sd) / (2u * Sd)) ^ 0x80u) & 0xffu;
+        PT[e] = (prob_u8(ev, Sd, __builtin_amdgcn_rcpf((float)(2u * Sd))) ^ 0x80u) & 0xffu;
     }
     __syncthreads();
 

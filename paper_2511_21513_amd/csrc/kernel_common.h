@@ -186,6 +186,18 @@ __device__ __forceinline__ void publish_tiles_barrier()
 // lane of half-wave h; the same key sits in byte i of that lane's next B operand.
 __device__ __forceinline__ int acc_key(int i, int h) { return 8 * (i >> 2) + 4 * h + (i & 3); }
 
+// Eq. uint8-prob: round-half-up(255 E / S) = floor((510 E + S) / (2 S)) for E <= 255 and 1 <= S < 2^25, without an
+// integer division: a single-precision estimate of the quotient (below 256, so off by one at most) corrected against
+// the exact products.  inv_2s: the reciprocal of (float)(2 S) to within a few units in the last place (v_rcp_f32).
+__device__ __forceinline__ uint32_t prob_u8(uint32_t e, uint32_t S, float inv_2s)
+{
+    const uint32_t num = 510u * e + S, den = 2u * S;
+    uint32_t q = (uint32_t)((float)num * inv_2s);
+    if (q * den > num) --q;
+    if ((q + 1u) * den <= num) ++q;
+    return q;
+}
+
 // Output requantization (Sec. 3.2): clamp(floor((acc * M + 2^(sh-1)) / 2^sh), -127, 127) with M < 2^31 and
 // 1 <= sh <= 62.  For sh >= 33 (every ratio s_V / (255 s_O) below 1/4) the rounding addend lies wholly in the high
 // word of the 64-bit product and the low word cannot change the floor of a division by 2^(sh-32) >= 2, so the

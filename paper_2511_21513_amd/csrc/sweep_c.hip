@@ -246,15 +246,11 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     if (path != 0) {
         const int cap = path == 1 ? caps.cap[1] : (path == 2 ? caps.cap[2] : (path == 3 ? caps.cap[3] : hrow.c_int));
         rif[0].bound = ri[0].mx - cap;
-        // quotients below 256 of numerators below 2^24: a single-precision estimate, corrected by at most one
-        const float rs = 1.0f / (float)(2u * sum[0]);
+        const float rs = __builtin_amdgcn_rcpf((float)(2u * sum[0]));
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
             if (k < 8 * path) { // wave-uniform
-                const uint32_t num = 510u * lut_at(k) + sum[0], den = 2u * sum[0];
-                uint32_t q = (uint32_t)((float)num * rs);
-                if (q * den > num) --q;
-                if ((q + 1u) * den <= num) ++q;
+                uint32_t q = prob_u8(lut_at(k), sum[0], rs);
                 if (path == 4) q ^= 0x80u; // P - 128 as a byte; rows outside the problem: probability 0
                 tab[k / 4] |= (valid ? q : (path == 4 ? 0x80u : 0u)) << (8 * (k % 4));
             }
@@ -284,7 +280,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
         for (int j = 0; j < 16; ++j) {
             const int kidx = 16 * h + j;
             const uint32_t e = lut_b[kidx];
-            const uint32_t pr = (510u * e + sum[0]) / (2u * sum[0]);
+            const uint32_t pr = prob_u8(e, sum[0], __builtin_amdgcn_rcpf((float)(2u * sum[0])));
             const uint8_t byte = (uint8_t)((pr ^ 0x80u) & 0xffu);
             PT[kidx * 256 + 4 * n + wave] = byte;
             PT[kidx * 256 + 4 * (n + 32) + wave] = byte;

@@ -22,7 +22,7 @@ namespace {
 
 constexpr int WAVES = 4;
 constexpr int NT = WAVES * 64;
-constexpr int BK = 128; // keys per workgroup: one 32-key sub-tile per wave
+// a workgroup walks tiles of 128 keys: one 32-key sub-tile per wave
 
 // packed row r of a (batch, KV head) group: query head kvh * group + r / L, query row r % L
 struct RowOf {

@@ -39,9 +39,9 @@ __global__ __launch_bounds__(NT, D == 64 ? 4 : 2) void fwd_splitk_kernel(const F
     constexpr int KB = D / 32;  // 32-wide blocks of the head dimension
     constexpr int CB = D / 32;  // 32-wide blocks of output channels
     constexpr int SUB = 32 * D; // bytes of a 32-key sub-tile
-    constexpr int NBLK = SUB / 1024; // 1 KiB blocks of a sub-tile: one wave-wide 16-byte load each
-    constexpr int CPR = D / 16;      // 16-byte chunks per key row
-    constexpr int RPB = 1024 / D;    // key rows per block
+    [[maybe_unused]] constexpr int NBLK = SUB / 1024; // 1 KiB blocks of a sub-tile: one wave-wide 16-byte load each
+    [[maybe_unused]] constexpr int CPR = D / 16;      // 16-byte chunks per key row
+    [[maybe_unused]] constexpr int RPB = 1024 / D;    // key rows per block
 
     // wave-private V sub-tiles, two buffers as separate arrays (the compiler tracks each direct-to-LDS load by
     // the array it targets, so reads of one buffer need not wait for loads into the other)

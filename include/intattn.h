@@ -140,10 +140,13 @@ INTATTN_API int intattn_create(intattn_ctx **out, const intattn_config *cfg);
  * kernels of a call pass intermediate results through it, so calls on ONE context must not
  * overlap in time (same stream, or ordered by the caller); use one context per concurrent stream.
  * The one-launch split-key path (few query rows; see intattn_config.variant) lets the workgroups of a
- * (batch, KV head) group wait for each other at a counter in device memory.  The wait is bounded (a few
- * seconds): on a GPU that another process keeps so busy that a group is not scheduled together in that
- * time, the workgroups give up, the call's output is undefined and so are later calls of this path on the
- * context until intattn_reserve has cleared the counters; variant 10 never waits.  (Testing aid: the
+ * (batch, KV head) group wait for each other at a counter in device memory.  Alone on the GPU a group's
+ * workgroups are always scheduled together (they have consecutive ids).  The wait is bounded (a few
+ * seconds): where other work keeps a group from being scheduled together for that long -- another process
+ * that fills the GPU, or two calls of this path running at the same time on different streams, each
+ * holding compute units the other's groups wait for -- the workgroups give up, the call's output is
+ * undefined and so are later calls of this path on the context until intattn_reserve has cleared the
+ * counters.  Order such calls on one stream, or use variant 10, which never waits.  (Testing aid: the
  * environment variable INTATTN_SPLITKEY_SPIN_LIMIT, read at every such call, lowers the bound, counted in
  * polls of the counter.) */
 INTATTN_API int intattn_forward(intattn_ctx *ctx, const intattn_args *args, void *hip_stream);

@@ -62,6 +62,7 @@ struct intattn_ctx {
     // microseconds per head; serving loops pass the same scales again and again)
     std::vector<uint32_t> dv_key;
     std::vector<HeadParams> dv_hp;
+    std::vector<HeadParams> dv_hp_c;
     std::vector<float> dv_alpha, dv_svso;
     int dv_mode = 0;
     std::vector<HeadParams> hp_host;  // what d_hp currently holds
@@ -340,6 +341,7 @@ bool find_fp64(uint32_t c_int, uint32_t top, HeadParams *hp)
 
 struct Derived {
     std::vector<HeadParams> hp;
+    std::vector<HeadParams> hp_c; // per head, for sweep C alone: top-byte constants where they exist (pad[0] names the scheme); empty: as hp
     std::vector<float> alpha, svso;
     int idx_mode = IDX_MAD24;
 };
@@ -403,6 +405,7 @@ int derive_all(intattn_ctx *ctx, const intattn_args *a, Derived *out)
     bool all_ok[5] = {true, true, true, true, true};
     std::vector<HeadParams> cand[5];
     for (auto &c : cand) c.assign((size_t)n, HeadParams{});
+    std::vector<char> top_ok((size_t)n, 0);
     for (int h = 0; h < n; ++h) {
         const int kv = a->scale_mode ? h / g : 0;
         const float sq = a->scale_q[h], sk = a->scale_k[kv], sv = a->scale_v[kv];
@@ -415,7 +418,12 @@ int derive_all(intattn_ctx *ctx, const intattn_args *a, Derived *out)
             return fail(ctx, INTATTN_ERR_INVALID_ARG, "s_V / (255 s_O) is outside the representable range");
         for (int m = 0; m < 5; ++m) {
             cand[m][(size_t)h] = hp;
-            if (all_ok[m] && !finders[m]((uint32_t)hp.c_int, top, &cand[m][(size_t)h])) all_ok[m] = false;
+            if (m == 0) { // the top-byte scheme: per head, for the mixed table of sweep C
+                top_ok[(size_t)h] = finders[0]((uint32_t)hp.c_int, top, &cand[0][(size_t)h]);
+                if (!top_ok[(size_t)h]) all_ok[0] = false;
+            } else if (all_ok[m] && !finders[m]((uint32_t)hp.c_int, top, &cand[m][(size_t)h])) {
+                all_ok[m] = false;
+            }
         }
         out->alpha[(size_t)h] = (float)(((double)sq * (double)sk) / std::sqrt((double)a->d));
         out->svso[(size_t)h] = (float)((double)sv / (double)so);
@@ -424,6 +432,18 @@ int derive_all(intattn_ctx *ctx, const intattn_args *a, Derived *out)
         if (all_ok[m]) {
             out->idx_mode = modes[m];
             out->hp = cand[m];
+            out->hp_c.clear();
+            // Some heads only lack top-byte constants (thresholds below 62 or of many thousands): sweep C, where that
+            // scheme saves a vector instruction per score, then takes each head's own scheme from a table of its own.
+            int n_top = 0;
+            for (int h = 0; h < n; ++h) n_top += top_ok[(size_t)h] ? 1 : 0;
+            if (modes[m] == IDX_MULHI24 && n > 1 && n_top > 0) {
+                out->hp_c = cand[m];
+                for (int h = 0; h < n; ++h) {
+                    if (top_ok[(size_t)h]) out->hp_c[(size_t)h] = cand[0][(size_t)h];
+                    out->hp_c[(size_t)h].pad[0] = top_ok[(size_t)h] ? IDX_TOP24 : IDX_MULHI24;
+                }
+            }
             return INTATTN_OK;
         }
     }
@@ -517,6 +537,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
         if (a->scale_out) add(a->scale_out, n_q);
         if (!ctx->dv_key.empty() && key == ctx->dv_key) {
             dv.hp = ctx->dv_hp;
+            dv.hp_c = ctx->dv_hp_c;
             dv.alpha = ctx->dv_alpha;
             dv.svso = ctx->dv_svso;
             dv.idx_mode = ctx->dv_mode;
@@ -525,6 +546,7 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
             if (rc) return rc;
             ctx->dv_key = key;
             ctx->dv_hp = dv.hp;
+            ctx->dv_hp_c = dv.hp_c;
             ctx->dv_alpha = dv.alpha;
             ctx->dv_svso = dv.svso;
             ctx->dv_mode = dv.idx_mode;
@@ -701,10 +723,18 @@ int run(intattn_ctx *ctx, const intattn_args *a, void *stream, const RunMode &rm
             p.sv_over_so0 = dv.svso[0];
         }
     } else {
-        rc = get_tables(a->Hq);
+        // (twice the heads: a second table for sweep C may follow the first)
+        rc = get_tables(rm.no_alloc ? a->Hq : 2 * a->Hq);
         if (rc) return rc;
         if (!rm.reserve) {
-            rc = put_table(dv.hp);
+            if (!dv.hp_c.empty() && !rm.no_alloc && !comparator) {
+                std::vector<HeadParams> both(dv.hp);
+                both.insert(both.end(), dv.hp_c.begin(), dv.hp_c.end());
+                rc = put_table(both);
+                p.hp_table_c = d_hp + a->Hq;
+            } else {
+                rc = put_table(dv.hp);
+            }
             if (rc) return rc;
             if (comparator && !(ctx->alpha_host == dv.alpha && ctx->svso_host == dv.svso)) {
                 const size_t n = (size_t)a->Hq;

@@ -120,6 +120,12 @@ int launch_fwd(const FwdParams &p_in, int d, int idx_mode, int variant, int stag
             if (e != 0 || stage == 1) return e;
         }
         if (variant == 4) return launch_shape<1, 2, 2>(p, d, idx_mode, st);
+        if (p.hp_table_c && idx_mode == IDX_MULHI24) {
+            // most heads have top-byte constants, which cost sweep C one vector instruction per score less
+            FwdParams pc = p;
+            pc.hp_table = p.hp_table_c;
+            return launch_sweep_c(pc, d, IDX_MIX, stream);
+        }
         return launch_sweep_c(p, d, idx_mode, stream);
     }
     return launch_shape<1, 2, 0>(p, d, idx_mode, st);

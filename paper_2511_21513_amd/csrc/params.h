@@ -17,8 +17,9 @@ enum IdxMode : int32_t {
     IDX_ROW64 = 5,  // the fp64 scheme with parameters per block of query rows (FwdParams::row_table): finer
                     // quantization groups over the query rows, Sec. 3.3
     IDX_KGROUP = 7, // per-logit parameters: quantization groups over the key axis (Sec. 3.3), fp64 map per key block
-    IDX_TOP24 = 6   // MAD24 with shift 24: the index is the top byte of Delta' * mul + add, which one byte
+    IDX_TOP24 = 6,  // MAD24 with shift 24: the index is the top byte of Delta' * mul + add, which one byte
                     // permute turns into the address of a table row 256 bytes apart (sweep C)
+    IDX_MIX = 8     // launchers of sweep C only: every head's own scheme, IDX_TOP24 or IDX_MULHI24, is in its parameters
 };
 
 // Per query head: everything the kernel needs that depends on the scales.
@@ -47,6 +48,7 @@ struct FwdParams {
     int32_t n_qtiles;    // tiles of (rows per workgroup) rows that [row_lo, row_lo + L) touches
     int32_t n_chunks;    // ceil(Lk / rows per workgroup of sweep C): chunks of V the column sums are kept for
     const HeadParams *hp_table; // device [Hq] when per-head or derived on the device, else nullptr
+    const HeadParams *hp_table_c; // device [Hq] or nullptr: sweep C's own table (IDX_MIX) where some heads have top-byte constants
     const HeadParams *row_table; // IDX_ROW64: device [B * Hq][n_rowblk], parameters of every block of q_block query rows
     int32_t q_block, n_rowblk;
     // IDX_KGROUP: scales per block of q_block query rows [B * Hq][n_rowblk] and per block of k_block keys

@@ -101,7 +101,12 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     const int b = wi.b, hq = wi.hq, kvh = wi.kvh, qt = wi.qt + p.row_lo / BQ;
     const int bh = b * p.Hq + hq;
     const HeadParams hp = p.hp_table ? p.hp_table[hq] : p.hp0;
-    if (p.filter && hp.pad[0] != MODE) return; // another launch of this pair serves the head (uniform for the workgroup)
+    if (MODE != IDX_MIX && p.filter && hp.pad[0] != MODE) return; // another launch of this pair serves the head (uniform for the workgroup)
+    // The rest of the kernel with the index scheme M as a compile-time constant: MODE itself, or, under IDX_MIX,
+    // the scheme named in the head's own parameters (top-byte constants where the head has them, else the
+    // multiply-high scheme that serves every head of the call).
+    auto body = [&](auto mode_tag) __attribute__((always_inline)) {
+    constexpr int M = decltype(mode_tag)::value;
     const int L = p.Lk; // keys
     // query rows: [rlo, rhi) of the numbering in which row r sees keys <= r under the causal mask
     const int rlo = p.row_lo, rhi = p.row_lo + p.L, LQ = p.L;
@@ -213,7 +218,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     const int row = qw0 + n; // this lane's query row
     const bool valid = row >= rlo && row < rhi;
     // the wave's path: the largest class among its rows (0: general path); rows outside [rlo, rhi) are inert
-    const ClassCaps caps = class_caps(MODE == IDX_ROW64 ? row_hp(row) : hp);
+    const ClassCaps caps = class_caps(M == IDX_ROW64 ? row_hp(row) : hp);
     const int my_cls = valid ? row_class((uint32_t)p.ws_row_sum[(int64_t)bh * LQ + (row - rlo)], caps) : 1;
     const int path = __any(my_cls == 5) ? 0 : __any(my_cls == 4) ? 4 : __any(my_cls == 3) ? 3 : __any(my_cls == 2) ? 2 : 1;
 
@@ -226,9 +231,9 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
     }
 
     // ---- per-row state from the first launch
-    RowIndex<MODE> ri[RB];
+    RowIndex<M> ri[RB];
     uint32_t sum[RB];
-    const HeadParams hrow = MODE == IDX_ROW64 ? row_hp(row) : hp;
+    const HeadParams hrow = M == IDX_ROW64 ? row_hp(row) : hp;
     {
         const int mx = valid ? p.ws_row_max[(int64_t)bh * LQ + (row - rlo)] : 0;
         sum[0] = valid ? (uint32_t)p.ws_row_sum[(int64_t)bh * LQ + (row - rlo)] : 0u;
@@ -240,7 +245,7 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
 
     // ---- register tables of the permute paths: tab[2 k], tab[2 k + 1] hold entries 8 k .. 8 k + 7 of
     // P_hat[idx] = round(255 LUT_hat[idx] / S); the clip of path n at the first distance of index 8 n
-    RowIndex<MODE> rif[RB];
+    RowIndex<M> rif[RB];
     uint32_t tab[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
     rif[0] = ri[0];
     if (path != 0) {
@@ -398,15 +403,15 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
                 // them up, a third joins the pairs, and four probabilities come out of the row's table
                 // registers.  IDX_TOP24: the index is the top byte of the scaled score and is picked up
                 // there; the other schemes deliver it in the low byte.
-                constexpr uint32_t PAIR = MODE == IDX_TOP24 ? 0x0c0c0703u : 0x0c0c0400u;
+                constexpr uint32_t PAIR = M == IDX_TOP24 ? 0x0c0c0703u : 0x0c0c0400u;
                 constexpr uint32_t HID = NP == 4 ? 31u : (uint32_t)(8 * NP); // index that stands for a hidden key
-                constexpr uint32_t CLIPPED = MODE == IDX_TOP24 ? HID << 24 : HID;
+                constexpr uint32_t CLIPPED = M == IDX_TOP24 ? HID << 24 : HID;
                 uint32_t ivp = 0;
 #pragma unroll
                 for (int w = sl * EPS; w < (sl + 1) * EPS; ++w) {
                     const int rb = w / 16, e = w % 16;
                     const int c = max(sc[rb][e], rif[rb].bound);
-                    uint32_t iv = MODE == IDX_TOP24 ? rif[rb].scaled(c) : rif[rb](c);
+                    uint32_t iv = M == IDX_TOP24 ? rif[rb].scaled(c) : rif[rb](c);
                     if (MASKED) iv = visible(32 * j + acc_key(e, h), rb) ? iv : CLIPPED; // also covers hidden keys above the row max
                     if (e % 2 == 0) {
                         ivp = iv;
@@ -541,6 +546,13 @@ __global__ __launch_bounds__(NT, RB == 1 ? 2 : 1) void sweep_c_kernel(const FwdP
             else epilogue(std::false_type{}, std::false_type{});
         }
     }
+    };
+    if constexpr (MODE == IDX_MIX) {
+        if (hp.pad[0] == IDX_TOP24) body(std::integral_constant<int, IDX_TOP24>{}); // uniform for the workgroup
+        else body(std::integral_constant<int, IDX_MULHI24>{});
+    } else {
+        body(std::integral_constant<int, MODE>{});
+    }
 }
 
 template <int D, int RB, bool CAUSAL>
@@ -556,7 +568,9 @@ int launch_mode(const FwdParams &p, int idx_mode, hipStream_t st)
         hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_FP64>), grid, block, 0, st, pf);
         return (int)hipGetLastError();
     }
-    if (idx_mode == IDX_TOP24)
+    if (idx_mode == IDX_MIX)
+        hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_MIX>), grid, block, 0, st, p);
+    else if (idx_mode == IDX_TOP24)
         hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_TOP24>), grid, block, 0, st, p);
     else if (idx_mode == IDX_MAD24)
         hipLaunchKernelGGL((sweep_c_kernel<D, RB, CAUSAL, IDX_MAD24>), grid, block, 0, st, p);

@@ -406,6 +406,34 @@ def test_dynamic_forward_mixed_schemes(torch_mod, ia, oracle):
     assert int((got != want).sum()) == 0
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("d,causal", [(64, True), (128, True), (128, False)], ids=lambda v: str(v))
+def test_host_scales_mixed_schemes_in_sweep_c(torch_mod, oracle, d, causal):
+    """Per-head host scales where most heads have top-byte index constants and some do not (thresholds below 62
+    and of tens of thousands): the two-launch path gives its second launch a table with each head's own scheme;
+    every tap and the output equal the oracle's, also on a second call and after the scales change."""
+    from paper_2511_21513_amd import binding
+
+    torch = torch_mod
+    p = inputs.random_problem(43, 2, 8, 4, 700, d, causal, per_head=True, spread=1.2)
+    ia = binding.IntAttn(device=0, variant=5)
+    dev = torch.device("cuda:0")
+    q, k, v = (torch.from_numpy(x).to(dev) for x in (p.q, p.k, p.v))
+    base = np.float32(np.sqrt(6.6 * np.sqrt(d) / 900.0))  # s_q = s_k = base: c_int = 900
+    for mult in ([1, 1, 18, 1, 1, 0.03, 1, 1], [1, 20, 1, 1, 1, 1, 1, 1], [1] * 8):  # c_int 900; 50 and 30000; 45
+        s_q = (base * np.asarray(mult, dtype=np.float32)).astype(np.float32)
+        s_k = np.full(4, base, dtype=np.float32)
+        cs = [oracle.c_int(6.6, s_q[h], s_k[h // 2], d) for h in range(8)]
+        print("c_int per head", cs, flush=True)
+        want = oracle.forward(p.q, p.k, p.v, s_q, s_k, p.s_v, None, causal=causal, per_head=True, taps=True, threads=8)
+        for rep in range(2):
+            got = ia.forward(q, k, v, s_q, s_k, p.s_v, None, causal=causal, per_head=True, taps=True)
+            torch.cuda.synchronize()
+            for key in ("row_max", "row_sum", "acc", "out"):
+                assert int((got[key].cpu().numpy() != want[key]).sum()) == 0, (mult, rep, key)
+    ia.close()
+
+
 def test_dynamic_forward_on_the_workload_configs(torch_mod, oracle):
     """Two of the workload configurations in full, through the automatic variant."""
     from paper_2511_21513_amd import binding
